@@ -1,0 +1,175 @@
+/*
+ * tilefusion.h -- C ABI of the tile-fusion library for the matrix chain  D = A (B C)  on gfx950.
+ *
+ * The operation (paper Section 1, Eq. 1): A is an n x n CSR sparse matrix, B is n x bCol and
+ * either dense or CSR sparse, C is a dense bCol x cCol matrix.  Unfused, the chain is
+ * D1 = B C followed by D = A D1.  Tile fusion (Section 3) inspects the sparsity pattern of A
+ * once, builds a schedule of two wavefronts -- fused tiles that produce a block of D1 rows and
+ * at once consume them for the rows of D that depend on nothing else, then the leftover rows
+ * of D -- and reuses that schedule for every later execution (Section 3, first paragraph).
+ *
+ * Conventions for every call
+ *   - Dense matrices are row-major and contiguous; B is n x bCol, C is bCol x cCol, D is n x cCol.
+ *   - Dense operands and every pointer handed to an execution call are DEVICE pointers, aligned
+ *     to 16 bytes.  The element type of B, C, D is the element type of A.
+ *   - CSR matrices use int32 row pointers (n_rows + 1 entries, rowptr[0] = 0) and int32 column
+ *     indices.  Explicit zeros, duplicate and unsorted column indices are legal; entries are
+ *     summed in an unspecified order.
+ *   - D is overwritten (the listings of Section 3.2 accumulate into zeroed outputs).
+ *   - The caller owns A, B, C and D.  The plan owns a device copy of A (pattern and values), the
+ *     schedule and a workspace for the D1 rows that cross tiles.
+ *   - Errors are reported by return code; tf_last_error() gives a message for the calling
+ *     thread's most recent failure.  No call throws or aborts.
+ */
+#ifndef TILEFUSION_H
+#define TILEFUSION_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    TF_OK = 0,
+    TF_EINVAL = 1,        /* null pointer, non-positive size, bad alignment, bad parameter   */
+    TF_EBADCSR = 2,       /* malformed CSR: rowptr not monotone, rowptr[n] != nnz, col range  */
+    TF_ENOMEM = 3,        /* host or device allocation failed                                 */
+    TF_EHIP = 4,          /* a HIP runtime call failed                                        */
+    TF_EUNSUPPORTED = 5,  /* shape outside what the kernels cover (see tf_plan_create)        */
+    TF_EMISMATCH = 6      /* plan and call disagree (dtype, kind of B, shape of B)            */
+} tf_status;
+
+typedef enum { TF_F32 = 0, TF_F64 = 1 } tf_dtype;
+
+/* A CSR matrix.  Caller-owned, read-only.  on_device tells where the three arrays live
+ * (all three in the same place). */
+typedef struct tf_csr {
+    int64_t n_rows;
+    int64_t n_cols;
+    int64_t nnz;
+    const int32_t *rowptr;
+    const int32_t *colidx;
+    const void *vals;
+    int32_t dtype;      /* tf_dtype */
+    int32_t on_device;  /* 0 = host pointers, 1 = device pointers */
+} tf_csr;
+
+/* Inputs of the scheduler (Algorithm 1) besides the pattern.  Zero selects the default. */
+typedef struct tf_tile_params {
+    int32_t ct_size;         /* coarse tile size ctSize (Section 3.1.1); default 2048           */
+    int32_t p;               /* wanted number of tiles per wavefront ("cores"); default 32      */
+    int64_t fast_mem_bytes;  /* fast memory of one tile: the LDS a workgroup may use;
+                                default = the device's LDS per workgroup (160 KiB on gfx950)    */
+    int32_t col_slice;       /* columns of C/D handled by one workgroup; default = cCol, capped
+                                at what the kernels cover; a last narrower slice is allowed     */
+    uint32_t flags;          /* TF_FLAG_* */
+} tf_tile_params;
+
+/* Skip step 2 (tile splitting): tiles that do not fit the fast memory make plan creation fail. */
+#define TF_FLAG_NO_SPLIT 1u
+/* Build the schedule only: no device is touched and no device memory is allocated, A must be in
+ * host memory, fast_mem_bytes is taken as given (default 160 KiB).  The plan serves
+ * tf_plan_schedule; execution calls on it fail with TF_EINVAL. */
+#define TF_FLAG_SCHEDULE_ONLY 2u
+
+typedef struct tf_plan tf_plan; /* opaque, library-owned */
+
+/* Host-readable view of a plan's schedule.  All pointers are HOST memory owned by the plan and
+ * stay valid until tf_plan_destroy.  A tile v of the first wavefront produces the D1 rows
+ *   first_rows[tile_first_ptr[v] .. tile_first_ptr[v+1])      (the tile's "first" list)
+ * and then computes the rows of D
+ *   second_rows[tile_second_ptr[v] .. tile_second_ptr[v+1])   (the tile's "second" list);
+ * unit u of the second wavefront computes the rows wf1_rows[wf1_unit_ptr[u] .. wf1_unit_ptr[u+1]).
+ * spill[i] != 0 marks D1 rows that are also stored to device memory because a row of the
+ * second wavefront reads them. */
+typedef struct tf_schedule_view {
+    int64_t n;
+    int64_t nnz;
+    int32_t t;                  /* uniform tile size chosen by step 1                          */
+    int32_t col_slice;
+    int32_t n_slices;
+    int32_t dtype;
+    int32_t b_is_sparse;
+    int32_t reserved0;
+    int64_t n_coarse_tiles;     /* tiles after step 1                                          */
+    int64_t n_tiles;            /* tiles after step 2                                          */
+    const int32_t *tile_first_ptr;
+    const int32_t *first_rows;
+    const int32_t *tile_second_ptr;
+    const int32_t *second_rows;
+    int64_t n_wf1_units;
+    const int32_t *wf1_unit_ptr;
+    const int32_t *wf1_rows;
+    const uint8_t *spill;
+    int64_t n_fused_rows;
+    int64_t n_wf1_rows;
+    int64_t n_spill_rows;
+    int64_t fused_nnz;          /* stored entries of A that belong to fused rows               */
+    double fused_ratio_eq3;     /* Eq. 3 literally: fused rows / (|I| + |J|) = / 2n            */
+    double fused_ratio_rows;    /* fused rows / n                                              */
+    double fused_ratio_nnz;     /* share of the second operation's work done in wavefront 0    */
+    int64_t fast_mem_bytes;     /* the budget the tiles were fitted to                         */
+    int64_t lds_fixed_bytes;    /* LDS a fused workgroup uses besides its D1 tile              */
+    int64_t lds_bytes_per_row;  /* LDS per D1 row of a tile; footprint = fixed + rows_pad*this */
+    int32_t lds_row_granule;    /* rows_pad = rows rounded up to a multiple of this            */
+    int32_t reserved1;
+    double eq2_cost_max;        /* largest Eq. 2 data-movement cost over the tiles (elements)  */
+    double plan_seconds;        /* host time spent building the schedule                       */
+    int64_t alg_bytes;          /* algorithmic HBM bytes of one fused execution                */
+    int64_t alg_bytes_unfused;  /* the same for the unfused two-kernel execution               */
+} tf_schedule_view;
+
+/* Inspector: builds the fused schedule for the pattern of A (Algorithm 1: step 1, coarse tile
+ * fusion; step 2, tile splitting against the fast-memory size) plus the spill set and the
+ * balanced units of the second wavefront.  bCol and cCol are the column counts of B and C;
+ * for a sparse B, bCol is the number of columns of B (= rows of C).  b_is_sparse selects which
+ * execution call the plan serves.  tp may be NULL for defaults.
+ * Validates: A square, 0 <= nnz < 2^31, rowptr monotone with rowptr[0] = 0 and rowptr[n] = nnz,
+ * 0 <= col < n, bCol > 0, cCol > 0, one D1 row fits the fast memory.
+ * Synchronous; allocates host and device memory owned by the plan.  On failure *out is NULL. */
+tf_status tf_plan_create(const tf_csr *A, int64_t bCol, int64_t cCol, int32_t b_is_sparse,
+                         const tf_tile_params *tp, tf_plan **out);
+
+/* Frees everything the plan owns.  NULL is accepted. */
+tf_status tf_plan_destroy(tf_plan *plan);
+
+/* Fills *out with the plan's schedule (host pointers, see tf_schedule_view). */
+tf_status tf_plan_schedule(const tf_plan *plan, tf_schedule_view *out);
+
+/* Fused execution of D = A (B C) with dense B (Section 3.2, fused GeMM-SpMM listing): first
+ * wavefront = one launch over the fused tiles, second wavefront = one launch over the leftover
+ * rows; stream order is the single barrier between them.  B, C, D are device pointers.
+ * Asynchronous on `hip_stream` (a hipStream_t, NULL = the default stream); allocates nothing,
+ * never synchronises.  Two executions of one plan must not overlap (they share the plan's
+ * workspace). */
+tf_status tf_gemm_spmm(const tf_plan *plan, const void *B, const void *C, void *D,
+                       void *hip_stream);
+
+/* Fused execution with CSR B (Section 3.2, fused SpMM-SpMM listing).  B must be on the device,
+ * n x bCol with the plan's bCol and dtype; C is bCol x cCol.  B may alias A's arrays. */
+tf_status tf_spmm_spmm(const tf_plan *plan, const tf_csr *B, const void *C, void *D,
+                       void *hip_stream);
+
+/* The unfused two-kernel baseline on the same plan (Section 4.1: an unfused parallel
+ * implementation with the same optimisations): D1 = B C for all rows into the plan's
+ * workspace, then D = A D1 for all rows.  Same argument rules as the fused calls. */
+tf_status tf_unfused_gemm_spmm(const tf_plan *plan, const void *B, const void *C, void *D,
+                               void *hip_stream);
+tf_status tf_unfused_spmm_spmm(const tf_plan *plan, const tf_csr *B, const void *C, void *D,
+                               void *hip_stream);
+
+/* Device pointer of the plan's D1 workspace (n x cCol, row-major).  After a fused execution
+ * only the spilled rows hold D1; after an unfused execution all rows do.  For tests. */
+tf_status tf_plan_workspace(const tf_plan *plan, void **d1_device);
+
+/* Message for the most recent failure on the calling thread ("" if none). */
+const char *tf_last_error(void);
+
+/* Library version, "major.minor". */
+const char *tf_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TILEFUSION_H */

@@ -1,0 +1,416 @@
+// C ABI of the tile-fusion library: argument checks, device memory owned by a plan, and the
+// two-launch execution (first wavefront, then second wavefront, in stream order).
+#include <hip/hip_runtime_api.h>
+
+#include <chrono>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "tf_internal.h"
+
+namespace {
+
+thread_local std::string g_err;
+
+tf_status fail(tf_status st, const std::string &msg) {
+    g_err = msg;
+    return st;
+}
+
+tf_status hip_fail(hipError_t e, const char *what) {
+    g_err = std::string(what) + ": " + hipGetErrorString(e);
+    return e == hipErrorOutOfMemory ? TF_ENOMEM : TF_EHIP;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Device buffers owned by a plan.
+struct DevBuf {
+    void *p = nullptr;
+    ~DevBuf() {
+        if (p) (void)hipFree(p);
+    }
+    hipError_t upload(const void *src, size_t bytes) {
+        hipError_t e = hipMalloc(&p, bytes ? bytes : 16);
+        if (e != hipSuccess) return e;
+        if (bytes) e = hipMemcpy(p, src, bytes, hipMemcpyHostToDevice);
+        return e;
+    }
+    hipError_t alloc(size_t bytes) { return hipMalloc(&p, bytes ? bytes : 16); }
+};
+
+}  // namespace
+
+struct tf_plan {
+    int64_t n = 0, nnz = 0, bcol = 0, ccol = 0;
+    int32_t dtype = 0, b_is_sparse = 0;
+    int device = 0;
+    bool schedule_only = false;
+    tf::Schedule s;
+    double plan_seconds = 0.0;
+    DevBuf a_rowptr, a_colidx, a_vals, lcol;
+    DevBuf tile_first_ptr, first_rows_enc, tile_second_ptr, second_rows;
+    DevBuf wf1_unit_ptr, wf1_rows, all_unit_ptr, all_rows;
+    DevBuf d1;
+};
+
+namespace {
+
+tf_status check_csr_host(int64_t n_rows, int64_t n_cols, int64_t nnz, const int32_t *rowptr,
+                         const int32_t *colidx) {
+    if (rowptr[0] != 0) return fail(TF_EBADCSR, "rowptr[0] != 0");
+    for (int64_t i = 0; i < n_rows; ++i)
+        if (rowptr[i + 1] < rowptr[i]) return fail(TF_EBADCSR, "rowptr is not monotone");
+    if (rowptr[n_rows] != nnz) return fail(TF_EBADCSR, "rowptr[n_rows] != nnz");
+    for (int64_t q = 0; q < nnz; ++q)
+        if (colidx[q] < 0 || colidx[q] >= n_cols)
+            return fail(TF_EBADCSR, "column index out of range");
+    return TF_OK;
+}
+
+template <typename V> hipError_t up(DevBuf &b, const std::vector<V> &v) {
+    return b.upload(v.data(), v.size() * sizeof(V));
+}
+
+tf::FusedLaunch fused_args(const tf_plan *p, const void *C, void *D) {
+    tf::FusedLaunch a{};
+    a.dtype = p->dtype;
+    a.n_tiles = (int32_t)(p->s.tile_first_ptr.size() - 1);
+    a.n_slices = p->s.n_slices;
+    a.cs = p->s.col_slice;
+    a.ccol = (int32_t)p->ccol;
+    a.bcol = (int32_t)p->bcol;
+    a.max_tile_rows = (int32_t)p->s.max_tile_rows;
+    a.lds_bytes = p->s.lds_fixed_bytes +
+                  tf::round_up(p->s.max_tile_rows, p->s.lds_row_granule) * p->s.lds_bytes_per_row;
+    a.tile_first_ptr = static_cast<const int32_t *>(p->tile_first_ptr.p);
+    a.first_rows_enc = static_cast<const int32_t *>(p->first_rows_enc.p);
+    a.tile_second_ptr = static_cast<const int32_t *>(p->tile_second_ptr.p);
+    a.second_rows = static_cast<const int32_t *>(p->second_rows.p);
+    a.a_rowptr = static_cast<const int32_t *>(p->a_rowptr.p);
+    a.lcol = static_cast<const uint16_t *>(p->lcol.p);
+    a.a_vals = p->a_vals.p;
+    a.C = C;
+    a.D = D;
+    a.D1 = p->d1.p;
+    return a;
+}
+
+tf::SpmmLaunch second_wavefront_args(const tf_plan *p, void *D) {
+    tf::SpmmLaunch w{};
+    w.dtype = p->dtype;
+    w.n_units = (int64_t)p->s.wf1_unit_ptr.size() - 1;
+    w.unit_ptr = static_cast<const int32_t *>(p->wf1_unit_ptr.p);
+    w.rows = static_cast<const int32_t *>(p->wf1_rows.p);
+    w.n_rows = p->n;
+    w.uniform_rows = 0;
+    w.S.rowptr = static_cast<const int32_t *>(p->a_rowptr.p);
+    w.S.colidx = static_cast<const int32_t *>(p->a_colidx.p);
+    w.S.vals = p->a_vals.p;
+    w.X = p->d1.p;
+    w.Y = D;
+    w.ccol = (int32_t)p->ccol;
+    return w;
+}
+
+tf::SpmmLaunch all_rows_args(const tf_plan *p, void *D) {
+    tf::SpmmLaunch w = second_wavefront_args(p, D);
+    w.n_units = (int64_t)p->s.all_unit_ptr.size() - 1;
+    w.unit_ptr = static_cast<const int32_t *>(p->all_unit_ptr.p);
+    w.rows = static_cast<const int32_t *>(p->all_rows.p);
+    return w;
+}
+
+tf_status check_exec(const tf_plan *p, int want_sparse, const void *C, const void *D) {
+    if (!p || !C || !D) return fail(TF_EINVAL, "null argument");
+    if (p->schedule_only) return fail(TF_EINVAL, "the plan was built with TF_FLAG_SCHEDULE_ONLY");
+    if (p->b_is_sparse != want_sparse)
+        return fail(TF_EMISMATCH, want_sparse ? "plan was built for a dense B"
+                                              : "plan was built for a sparse B");
+    if (!aligned16(C) || !aligned16(D)) return fail(TF_EINVAL, "C and D must be 16-byte aligned");
+    return TF_OK;
+}
+
+tf_status check_sparse_b(const tf_plan *p, const tf_csr *B) {
+    if (!B || !B->rowptr || (B->nnz > 0 && (!B->colidx || !B->vals)))
+        return fail(TF_EINVAL, "null argument");
+    if (!B->on_device) return fail(TF_EINVAL, "B must be on the device for execution");
+    if (B->dtype != p->dtype) return fail(TF_EMISMATCH, "B has a different element type than A");
+    if (B->n_rows != p->n || B->n_cols != p->bcol)
+        return fail(TF_EMISMATCH, "B is not n x bCol for this plan");
+    return TF_OK;
+}
+
+int device_lds_limit() {
+    int dev = 0, lds = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 64 * 1024;
+    if (hipDeviceGetAttribute(&lds, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess ||
+        lds <= 0)
+        return 64 * 1024;
+    return lds;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *tf_last_error(void) { return g_err.c_str(); }
+
+const char *tf_version(void) { return "0.1"; }
+
+tf_status tf_plan_create(const tf_csr *A, int64_t bCol, int64_t cCol, int32_t b_is_sparse,
+                         const tf_tile_params *tp, tf_plan **out) {
+    if (out) *out = nullptr;
+    if (!A || !out) return fail(TF_EINVAL, "null argument");
+    if (A->n_rows < 0 || A->nnz < 0 || !A->rowptr || (A->nnz > 0 && (!A->colidx || !A->vals)))
+        return fail(TF_EINVAL, "A is missing an array or has a negative size");
+    if (A->n_rows != A->n_cols) return fail(TF_EINVAL, "A must be square");
+    if (A->nnz >= (int64_t(1) << 31) || A->n_rows >= (int64_t(1) << 31) - 1)
+        return fail(TF_EUNSUPPORTED, "indices are 32 bit: n and nnz must be below 2^31");
+    if (A->dtype != TF_F32 && A->dtype != TF_F64) return fail(TF_EINVAL, "unknown dtype");
+    if (bCol <= 0 || cCol <= 0) return fail(TF_EINVAL, "bCol and cCol must be positive");
+    if (bCol >= (int64_t(1) << 31) || cCol > (1 << 20))
+        return fail(TF_EUNSUPPORTED, "bCol or cCol too large");
+    if (tp && (tp->ct_size < 0 || tp->p < 0 || tp->fast_mem_bytes < 0))
+        return fail(TF_EINVAL, "negative tile parameter");
+
+    const bool schedule_only = tp && (tp->flags & TF_FLAG_SCHEDULE_ONLY);
+    if (schedule_only && A->on_device)
+        return fail(TF_EINVAL, "TF_FLAG_SCHEDULE_ONLY needs A in host memory");
+    const int64_t n = A->n_rows, nnz = A->nnz;
+    const int es = tf::elem_size(A->dtype);
+    const auto t_start = std::chrono::steady_clock::now();
+
+    // Host view of A's pattern (the scheduler runs on the host).
+    std::vector<int32_t> h_rowptr, h_colidx;
+    std::vector<unsigned char> h_vals;
+    const int32_t *rowptr = A->rowptr, *colidx = A->colidx;
+    const void *vals = A->vals;
+    try {
+        if (A->on_device) {
+            h_rowptr.resize((size_t)n + 1);
+            h_colidx.resize((size_t)nnz);
+            h_vals.resize((size_t)nnz * es);
+            hipError_t e = hipMemcpy(h_rowptr.data(), A->rowptr, (n + 1) * 4, hipMemcpyDeviceToHost);
+            if (e == hipSuccess && nnz)
+                e = hipMemcpy(h_colidx.data(), A->colidx, nnz * 4, hipMemcpyDeviceToHost);
+            if (e == hipSuccess && nnz)
+                e = hipMemcpy(h_vals.data(), A->vals, nnz * es, hipMemcpyDeviceToHost);
+            if (e != hipSuccess) return hip_fail(e, "copying A to the host");
+            rowptr = h_rowptr.data();
+            colidx = h_colidx.data();
+            vals = h_vals.data();
+        }
+        tf_status st = check_csr_host(n, n, nnz, rowptr, colidx);
+        if (st != TF_OK) return st;
+
+        tf_plan *p = new (std::nothrow) tf_plan();
+        if (!p) return fail(TF_ENOMEM, "out of host memory");
+        struct Guard {
+            tf_plan *p;
+            ~Guard() { delete p; }
+        } guard{p};
+        p->n = n;
+        p->nnz = nnz;
+        p->bcol = bCol;
+        p->ccol = cCol;
+        p->dtype = A->dtype;
+        p->b_is_sparse = b_is_sparse ? 1 : 0;
+        p->schedule_only = schedule_only;
+        if (!schedule_only) (void)hipGetDevice(&p->device);
+
+        tf::InspectorInput in{};
+        in.n = n;
+        in.nnz = nnz;
+        in.rowptr = rowptr;
+        in.colidx = colidx;
+        in.bcol = bCol;
+        in.ccol = cCol;
+        in.b_is_sparse = p->b_is_sparse;
+        in.dtype = A->dtype;
+        in.ct_size = tp ? tp->ct_size : 0;
+        in.p = tp ? tp->p : 0;
+        in.col_slice = tp ? tp->col_slice : 0;
+        in.flags = tp ? tp->flags : 0;
+        const int64_t lds_limit = schedule_only ? 160 * 1024 : device_lds_limit();
+        in.fast_mem_bytes = (tp && tp->fast_mem_bytes > 0) ? tp->fast_mem_bytes : lds_limit;
+        if (!schedule_only && in.fast_mem_bytes > lds_limit) in.fast_mem_bytes = lds_limit;
+        std::string err;
+        st = tf::build_schedule(in, p->s, err);
+        if (st != TF_OK) return fail(st, err);
+        p->plan_seconds =
+            std::chrono::duration<double>(std::chrono::steady_clock::now() - t_start).count();
+
+        if (schedule_only) {
+            guard.p = nullptr;
+            *out = p;
+            return TF_OK;
+        }
+        // first_rows with the spill flag folded into the top bit
+        std::vector<int32_t> enc(p->s.first_rows.size());
+        for (size_t i = 0; i < enc.size(); ++i) {
+            const int32_t r = p->s.first_rows[i];
+            enc[i] = (int32_t)((uint32_t)r | (p->s.spill[r] ? tf::kSpillBit : 0u));
+        }
+        hipError_t e = hipSuccess;
+        auto ok = [&](hipError_t r) {
+            if (e == hipSuccess) e = r;
+        };
+        ok(p->a_rowptr.upload(rowptr, (size_t)(n + 1) * 4));
+        ok(p->a_colidx.upload(colidx, (size_t)nnz * 4));
+        ok(p->a_vals.upload(vals, (size_t)nnz * es));
+        ok(up(p->lcol, p->s.lcol));
+        ok(up(p->tile_first_ptr, p->s.tile_first_ptr));
+        ok(up(p->first_rows_enc, enc));
+        ok(up(p->tile_second_ptr, p->s.tile_second_ptr));
+        ok(up(p->second_rows, p->s.second_rows));
+        ok(up(p->wf1_unit_ptr, p->s.wf1_unit_ptr));
+        ok(up(p->wf1_rows, p->s.wf1_rows));
+        ok(up(p->all_unit_ptr, p->s.all_unit_ptr));
+        ok(up(p->all_rows, p->s.all_rows));
+        ok(p->d1.alloc((size_t)n * cCol * es));
+        if (e != hipSuccess) return hip_fail(e, "allocating the plan's device memory");
+        guard.p = nullptr;
+        *out = p;
+        return TF_OK;
+    } catch (const std::bad_alloc &) {
+        return fail(TF_ENOMEM, "out of host memory");
+    }
+}
+
+tf_status tf_plan_destroy(tf_plan *plan) {
+    delete plan;
+    return TF_OK;
+}
+
+tf_status tf_plan_schedule(const tf_plan *p, tf_schedule_view *v) {
+    if (!p || !v) return fail(TF_EINVAL, "null argument");
+    std::memset(v, 0, sizeof(*v));
+    const tf::Schedule &s = p->s;
+    const int es = tf::elem_size(p->dtype);
+    v->n = p->n;
+    v->nnz = p->nnz;
+    v->t = s.t;
+    v->col_slice = s.col_slice;
+    v->n_slices = s.n_slices;
+    v->dtype = p->dtype;
+    v->b_is_sparse = p->b_is_sparse;
+    v->n_coarse_tiles = s.n_coarse_tiles;
+    v->n_tiles = (int64_t)s.tile_first_ptr.size() - 1;
+    v->tile_first_ptr = s.tile_first_ptr.data();
+    v->first_rows = s.first_rows.data();
+    v->tile_second_ptr = s.tile_second_ptr.data();
+    v->second_rows = s.second_rows.data();
+    v->n_wf1_units = (int64_t)s.wf1_unit_ptr.size() - 1;
+    v->wf1_unit_ptr = s.wf1_unit_ptr.data();
+    v->wf1_rows = s.wf1_rows.data();
+    v->spill = s.spill.data();
+    v->n_fused_rows = s.n_fused_rows;
+    v->n_wf1_rows = (int64_t)s.wf1_rows.size();
+    v->n_spill_rows = s.n_spill_rows;
+    v->fused_nnz = s.fused_nnz;
+    v->fused_ratio_eq3 = p->n ? (double)s.n_fused_rows / (2.0 * (double)p->n) : 0.0;
+    v->fused_ratio_rows = p->n ? (double)s.n_fused_rows / (double)p->n : 0.0;
+    v->fused_ratio_nnz = p->nnz ? (double)s.fused_nnz / (double)p->nnz : 0.0;
+    v->fast_mem_bytes = s.fast_mem_bytes;
+    v->lds_fixed_bytes = s.lds_fixed_bytes;
+    v->lds_bytes_per_row = s.lds_bytes_per_row;
+    v->lds_row_granule = s.lds_row_granule;
+    v->eq2_cost_max = s.eq2_cost_max;
+    v->plan_seconds = p->plan_seconds;
+    // algorithmic bytes: A once, B once (dense; a sparse B is not known to the plan and is left
+    // out), C once, D once, and every spilled D1 row written once and read once
+    const int64_t a_bytes = 4 * (p->n + 1) + p->nnz * (4 + es);
+    const int64_t b_bytes = p->b_is_sparse ? 0 : p->n * p->bcol * es;
+    const int64_t c_bytes = p->bcol * p->ccol * es;
+    const int64_t d_bytes = p->n * p->ccol * es;
+    v->alg_bytes = a_bytes + b_bytes + c_bytes + d_bytes + 2 * s.n_spill_rows * p->ccol * es;
+    v->alg_bytes_unfused = a_bytes + b_bytes + c_bytes + 3 * d_bytes;
+    return TF_OK;
+}
+
+tf_status tf_plan_workspace(const tf_plan *p, void **d1_device) {
+    if (!p || !d1_device) return fail(TF_EINVAL, "null argument");
+    *d1_device = p->d1.p;
+    return TF_OK;
+}
+
+tf_status tf_gemm_spmm(const tf_plan *p, const void *B, const void *C, void *D, void *stream) {
+    tf_status st = check_exec(p, 0, C, D);
+    if (st != TF_OK) return st;
+    if (!B || !aligned16(B)) return fail(TF_EINVAL, "B must be a 16-byte aligned device pointer");
+    tf::FusedLaunch a = fused_args(p, C, D);
+    a.B = B;
+    int e = tf::launch_fused_gemm_spmm(a, stream);
+    if (e) return hip_fail((hipError_t)e, "launching the first wavefront");
+    e = tf::launch_spmm_units(second_wavefront_args(p, D), stream);
+    if (e) return hip_fail((hipError_t)e, "launching the second wavefront");
+    return TF_OK;
+}
+
+tf_status tf_spmm_spmm(const tf_plan *p, const tf_csr *B, const void *C, void *D, void *stream) {
+    tf_status st = check_exec(p, 1, C, D);
+    if (st != TF_OK) return st;
+    st = check_sparse_b(p, B);
+    if (st != TF_OK) return st;
+    tf::FusedLaunch a = fused_args(p, C, D);
+    a.Bs.rowptr = B->rowptr;
+    a.Bs.colidx = B->colidx;
+    a.Bs.vals = B->vals;
+    int e = tf::launch_fused_spmm_spmm(a, stream);
+    if (e) return hip_fail((hipError_t)e, "launching the first wavefront");
+    e = tf::launch_spmm_units(second_wavefront_args(p, D), stream);
+    if (e) return hip_fail((hipError_t)e, "launching the second wavefront");
+    return TF_OK;
+}
+
+tf_status tf_unfused_gemm_spmm(const tf_plan *p, const void *B, const void *C, void *D,
+                               void *stream) {
+    tf_status st = check_exec(p, 0, C, D);
+    if (st != TF_OK) return st;
+    if (!B || !aligned16(B)) return fail(TF_EINVAL, "B must be a 16-byte aligned device pointer");
+    tf::GemmLaunch g{};
+    g.dtype = p->dtype;
+    g.n = p->n;
+    g.bcol = (int32_t)p->bcol;
+    g.ccol = (int32_t)p->ccol;
+    g.cs = p->ccol > tf::kMaxMfmaSliceCols ? tf::kMaxMfmaSliceCols : (int32_t)p->ccol;
+    g.n_slices = (int32_t)((p->ccol + g.cs - 1) / g.cs);
+    g.B = B;
+    g.C = C;
+    g.D1 = p->d1.p;
+    int e = tf::launch_gemm(g, stream);
+    if (e) return hip_fail((hipError_t)e, "launching the GeMM");
+    e = tf::launch_spmm_units(all_rows_args(p, D), stream);
+    if (e) return hip_fail((hipError_t)e, "launching the SpMM");
+    return TF_OK;
+}
+
+tf_status tf_unfused_spmm_spmm(const tf_plan *p, const tf_csr *B, const void *C, void *D,
+                               void *stream) {
+    tf_status st = check_exec(p, 1, C, D);
+    if (st != TF_OK) return st;
+    st = check_sparse_b(p, B);
+    if (st != TF_OK) return st;
+    tf::SpmmLaunch f{};
+    f.dtype = p->dtype;
+    f.uniform_rows = 64;
+    f.n_rows = p->n;
+    f.n_units = (p->n + f.uniform_rows - 1) / f.uniform_rows;
+    f.S.rowptr = B->rowptr;
+    f.S.colidx = B->colidx;
+    f.S.vals = B->vals;
+    f.X = C;
+    f.Y = p->d1.p;
+    f.ccol = (int32_t)p->ccol;
+    int e = tf::launch_spmm_units(f, stream);
+    if (e) return hip_fail((hipError_t)e, "launching the first SpMM");
+    e = tf::launch_spmm_units(all_rows_args(p, D), stream);
+    if (e) return hip_fail((hipError_t)e, "launching the second SpMM");
+    return TF_OK;
+}
+
+}  // extern "C"

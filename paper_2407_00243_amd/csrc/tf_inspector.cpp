@@ -1,0 +1,209 @@
+// Inspector: the tile fusion scheduler (paper Section 3.1, Algorithm 1) for one GPU.
+//
+// Step 1 forms uniform tiles of t consecutive rows and fuses a row of the second operation
+// into the tile that produces the same row range exactly when every column index of that row
+// of A lies inside the range.  Step 2 halves every tile whose fast-memory footprint exceeds
+// the budget.  The GPU additions are the spill set (D1 rows that a second-wavefront row
+// reads and that therefore must also reach device memory) and the work-balanced units of the
+// second wavefront (the `balance` routine of Algorithm 1, read as: spread the leftover rows
+// over units of about equal work; rows too long for one unit get a workgroup of their own).
+//
+// Pure host code: no HIP calls.
+#include <algorithm>
+#include <chrono>
+#include <numeric>
+
+#include "tf_internal.h"
+
+namespace tf {
+
+namespace {
+
+struct Range {
+    int64_t i0, i1;
+};
+
+int64_t tile_footprint(const Schedule &s, int64_t rows) {
+    return s.lds_fixed_bytes + round_up(rows, s.lds_row_granule) * s.lds_bytes_per_row;
+}
+
+// Step 2 for one coarse tile: halve (left half gets floor(rows / 2)) until the footprint fits.
+void split_tile(const Schedule &s, Range r, bool allow_split, std::vector<Range> &out) {
+    const int64_t rows = r.i1 - r.i0;
+    if (!allow_split || rows <= 1 || tile_footprint(s, rows) <= s.fast_mem_bytes) {
+        out.push_back(r);
+        return;
+    }
+    const int64_t mid = r.i0 + rows / 2;
+    split_tile(s, Range{r.i0, mid}, allow_split, out);
+    split_tile(s, Range{mid, r.i1}, allow_split, out);
+}
+
+}  // namespace
+
+void balance_units(const int32_t *rowptr, const std::vector<int32_t> &rows, bool long_first,
+                   std::vector<int32_t> &rows_out, std::vector<int32_t> &unit_ptr) {
+    rows_out.clear();
+    unit_ptr.clear();
+    unit_ptr.push_back(0);
+    std::vector<int32_t> longs;
+    if (long_first) {
+        for (int32_t j : rows)
+            if (rowptr[j + 1] - rowptr[j] >= kLongRowNnz) longs.push_back(j);
+        std::stable_sort(longs.begin(), longs.end(), [&](int32_t a, int32_t b) {
+            return rowptr[a + 1] - rowptr[a] > rowptr[b + 1] - rowptr[b];
+        });
+        for (int32_t j : longs) {
+            rows_out.push_back(j);
+            unit_ptr.push_back((int32_t)rows_out.size());
+        }
+    }
+    int64_t work = 0;
+    for (int32_t j : rows) {
+        const int64_t len = rowptr[j + 1] - rowptr[j];
+        if (long_first && len >= kLongRowNnz) continue;
+        rows_out.push_back(j);
+        work += len + 8;
+        if (work >= kUnitWork) {
+            unit_ptr.push_back((int32_t)rows_out.size());
+            work = 0;
+        }
+    }
+    if (unit_ptr.back() != (int32_t)rows_out.size()) unit_ptr.push_back((int32_t)rows_out.size());
+}
+
+tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err) {
+    const int64_t n = in.n;
+    const int es = elem_size(in.dtype);
+    s = Schedule();
+    s.n = n;
+    s.nnz = in.nnz;
+
+    // ---- column slice -------------------------------------------------------------------
+    const int v = vec_elems(in.dtype);
+    int64_t max_cs = in.b_is_sparse ? 64 * v : kMaxMfmaSliceCols;
+    if (in.ccol % v != 0) max_cs = 64;                 // scalar lanes: one column per lane
+    int64_t cs = in.col_slice > 0 ? in.col_slice : in.ccol;
+    if (in.col_slice < 0) {
+        err = "col_slice must be >= 0";
+        return TF_EINVAL;
+    }
+    cs = std::min<int64_t>(cs, in.ccol);
+    if (cs > max_cs) {
+        if (in.col_slice > 0) {
+            err = "col_slice is wider than the kernels cover for this shape";
+            return TF_EUNSUPPORTED;
+        }
+        cs = max_cs;
+    }
+    if (in.ccol % v == 0 && cs % v != 0 && cs != in.ccol) {
+        err = "col_slice must be a multiple of 16 bytes of elements";
+        return TF_EINVAL;
+    }
+    s.col_slice = (int32_t)cs;
+    s.n_slices = (int32_t)((in.ccol + cs - 1) / cs);
+
+    // ---- fast-memory model --------------------------------------------------------------
+    s.lds_fixed_bytes = lds_fixed_bytes(in.dtype, in.b_is_sparse, (int)in.bcol, (int)cs);
+    s.lds_bytes_per_row = lds_ldl(in.dtype, in.b_is_sparse, (int)cs) * es;
+    s.lds_row_granule = lds_row_granule(in.b_is_sparse);
+    s.fast_mem_bytes = in.fast_mem_bytes;
+    if (tile_footprint(s, 1) > s.fast_mem_bytes) {
+        err = "fast_mem_bytes cannot hold one D1 row of the chosen column slice (plus the C slice)";
+        return TF_EUNSUPPORTED;
+    }
+
+    // ---- step 1: tile size --------------------------------------------------------------
+    const int64_t ct = in.ct_size > 0 ? in.ct_size : 2048;
+    const int64_t p = in.p > 0 ? in.p : 32;
+    int64_t t = ct;
+    if (n > 0 && (n + ct - 1) / ct < p) t = (n + p - 1) / p;
+    if (t < 1) t = 1;
+    s.t = (int32_t)std::min<int64_t>(t, INT32_MAX);
+
+    // ---- step 1 + step 2: tile ranges ---------------------------------------------------
+    std::vector<Range> tiles;
+    const bool allow_split = !(in.flags & TF_FLAG_NO_SPLIT);
+    for (int64_t i0 = 0; i0 < n; i0 += t) {
+        ++s.n_coarse_tiles;
+        split_tile(s, Range{i0, std::min(n, i0 + t)}, allow_split, tiles);
+    }
+    for (const Range &r : tiles) {
+        if (tile_footprint(s, r.i1 - r.i0) > s.fast_mem_bytes) {
+            err = "a tile does not fit the fast memory and splitting is disabled";
+            return TF_EUNSUPPORTED;
+        }
+        if (r.i1 - r.i0 > 65536) {
+            err = "a tile has more than 65536 rows (tile-local column indices are 16 bit)";
+            return TF_EUNSUPPORTED;
+        }
+        s.max_tile_rows = std::max(s.max_tile_rows, r.i1 - r.i0);
+    }
+
+    // ---- classification: fused rows, tile-local column indices ---------------------------
+    const int64_t nt = (int64_t)tiles.size();
+    s.tile_first_ptr.resize(nt + 1);
+    s.tile_second_ptr.resize(nt + 1);
+    s.first_rows.resize(n);
+    s.second_rows.reserve(n);
+    s.lcol.assign((size_t)in.nnz, 0);
+    s.spill.assign((size_t)n, 0);
+    std::vector<int32_t> wf1;
+    std::vector<int32_t> seen((size_t)n, -1);      // Eq. 2: distinct columns per tile
+    for (int64_t vt = 0; vt < nt; ++vt) {
+        const Range r = tiles[vt];
+        s.tile_first_ptr[vt] = (int32_t)r.i0;
+        s.tile_second_ptr[vt] = (int32_t)s.second_rows.size();
+        int64_t tile_nnz = 0, uc = 0;
+        for (int64_t j = r.i0; j < r.i1; ++j) {
+            s.first_rows[j] = (int32_t)j;
+            bool inside = true;
+            for (int64_t q = in.rowptr[j]; q < in.rowptr[j + 1]; ++q) {
+                const int64_t c = in.colidx[q];
+                if (c < r.i0 || c >= r.i1) {
+                    inside = false;
+                    break;
+                }
+            }
+            if (inside) {
+                s.second_rows.push_back((int32_t)j);
+                for (int64_t q = in.rowptr[j]; q < in.rowptr[j + 1]; ++q) {
+                    const int32_t c = in.colidx[q];
+                    s.lcol[q] = (uint16_t)(c - r.i0);
+                    if (seen[c] != (int32_t)vt) {
+                        seen[c] = (int32_t)vt;
+                        ++uc;
+                    }
+                }
+                tile_nnz += in.rowptr[j + 1] - in.rowptr[j];
+            } else {
+                wf1.push_back((int32_t)j);
+            }
+        }
+        const int64_t rows = r.i1 - r.i0;
+        const int64_t nj = (int64_t)s.second_rows.size() - s.tile_second_ptr[vt];
+        // Eq. 2 (diagnostic): (nz + uc + t + |J|) * cCol + idx, counted in elements; for a dense B
+        // the tile's rows x bCol block of B is added to nz, a sparse B is unknown here.
+        const double nz = (double)tile_nnz + (in.b_is_sparse ? 0.0 : (double)rows * in.bcol);
+        const double idx = (double)(rows + 1) + (double)tile_nnz;
+        s.eq2_cost_max = std::max(s.eq2_cost_max, (nz + uc + rows + nj) * (double)in.ccol + idx);
+        s.fused_nnz += tile_nnz;
+    }
+    s.tile_first_ptr[nt] = (int32_t)n;
+    s.tile_second_ptr[nt] = (int32_t)s.second_rows.size();
+    s.n_fused_rows = (int64_t)s.second_rows.size();
+
+    // ---- spill set ----------------------------------------------------------------------
+    for (int32_t j : wf1)
+        for (int64_t q = in.rowptr[j]; q < in.rowptr[j + 1]; ++q) s.spill[in.colidx[q]] = 1;
+    s.n_spill_rows = std::accumulate(s.spill.begin(), s.spill.end(), (int64_t)0);
+
+    // ---- balance: units of the second wavefront, and of the unfused baseline ------------
+    balance_units(in.rowptr, wf1, true, s.wf1_rows, s.wf1_unit_ptr);
+    std::vector<int32_t> all((size_t)n);
+    std::iota(all.begin(), all.end(), 0);
+    balance_units(in.rowptr, all, true, s.all_rows, s.all_unit_ptr);
+    return TF_OK;
+}
+
+}  // namespace tf

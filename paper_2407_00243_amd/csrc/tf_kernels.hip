@@ -1,0 +1,532 @@
+// gfx950 kernels of the tile-fusion path  D = A (B C).
+//
+//   k_fused_gemm_spmm   first wavefront, dense B   (paper Section 3.2, fused GeMM-SpMM listing)
+//   k_fused_spmm_spmm   first wavefront, CSR B     (Section 3.2, fused SpMM-SpMM listing)
+//   k_spmm_units        second wavefront (rows whose D1 rows come from device memory); also the
+//                       SpMM of the unfused baseline
+//   k_gemm              D1 = B C for all rows: the GeMM of the unfused baseline
+//
+// A fused workgroup owns one tile (a list of D1 rows) and one column slice.  It produces the
+// tile's D1 rows into LDS -- by MFMA for a dense B, by a row gather over C for a CSR B -- stores
+// the rows flagged "spill" to device memory as well, and after one workgroup barrier computes
+// the tile's fused rows of D straight out of LDS.  Nothing is accumulated with atomics: every
+// output element is written by exactly one lane.
+//
+// Wave size is 64.  Lanes run across columns (16 bytes per lane where alignment allows), row
+// groups across the rest of the wave.
+#include <hip/hip_runtime.h>
+
+#include <type_traits>
+
+#include "tf_internal.h"
+
+namespace tf {
+namespace {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef double doublex4 __attribute__((ext_vector_type(4)));
+
+template <typename T> struct Tr;
+// D(16x16) += A(16x4) * B(4x16), one wave.  Lane l supplies A[l % 16][l / 16] and
+// B[l / 16][l % 16].  Afterwards lane l = 16 g + r holds, in component v, D[4 g + v][r] for
+// fp32 but D[4 v + g][r] for fp64 (measured on gfx950).  `col_of_m` maps the M index that a
+// lane feeds to the column of the C slice it stands for, chosen so that in both precisions
+// lane (g, r) ends up with the four consecutive columns 4 g .. 4 g + 3 of row r.
+template <> struct Tr<float> {
+    static constexpr int V = 4;
+    typedef floatx4 Acc;
+    __device__ static __forceinline__ int col_of_m(int m) { return m; }
+};
+template <> struct Tr<double> {
+    static constexpr int V = 2;
+    typedef doublex4 Acc;
+    __device__ static __forceinline__ int col_of_m(int m) { return 4 * (m & 3) + (m >> 2); }
+};
+
+__device__ __forceinline__ floatx4 mfma16(float a, float b, floatx4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ doublex4 mfma16(double a, double b, doublex4 c) {
+    return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
+}
+
+template <typename T, int N> struct alignas(sizeof(T) * N) Pack {
+    T x[N];
+};
+
+template <typename T, int N> __device__ __forceinline__ void load_pack(T (&dst)[N], const T *p) {
+    const Pack<T, N> v = *reinterpret_cast<const Pack<T, N> *>(p);
+#pragma unroll
+    for (int i = 0; i < N; ++i) dst[i] = v.x[i];
+}
+template <typename T, int N> __device__ __forceinline__ void store_pack(T *p, const T (&src)[N]) {
+    Pack<T, N> v;
+#pragma unroll
+    for (int i = 0; i < N; ++i) v.x[i] = src[i];
+    *reinterpret_cast<Pack<T, N> *>(p) = v;
+}
+
+__device__ __forceinline__ int pow2_at_least(int x) {
+    int g = 1;
+    while (g < x) g <<= 1;
+    return g;
+}
+
+// acc[0..N) += sum_{k in [kbeg, kend)} val[k] * X[idx[k] * ldx + 0..N), k ascending.
+// X already includes the lane's column offset.  Four independent gathers are kept in flight.
+template <typename T, int N, typename IdxT>
+__device__ __forceinline__ void row_dot(T (&acc)[N], const IdxT *__restrict__ idx,
+                                        const T *__restrict__ val, int kbeg, int kend,
+                                        const T *X, int64_t ldx) {
+    int k = kbeg;
+    for (; k + 4 <= kend; k += 4) {
+        const int64_t c0 = idx[k], c1 = idx[k + 1], c2 = idx[k + 2], c3 = idx[k + 3];
+        const T v0 = val[k], v1 = val[k + 1], v2 = val[k + 2], v3 = val[k + 3];
+        T x0[N], x1[N], x2[N], x3[N];
+        load_pack<T, N>(x0, X + c0 * ldx);
+        load_pack<T, N>(x1, X + c1 * ldx);
+        load_pack<T, N>(x2, X + c2 * ldx);
+        load_pack<T, N>(x3, X + c3 * ldx);
+#pragma unroll
+        for (int i = 0; i < N; ++i) acc[i] += v0 * x0[i];
+#pragma unroll
+        for (int i = 0; i < N; ++i) acc[i] += v1 * x1[i];
+#pragma unroll
+        for (int i = 0; i < N; ++i) acc[i] += v2 * x2[i];
+#pragma unroll
+        for (int i = 0; i < N; ++i) acc[i] += v3 * x3[i];
+    }
+    for (; k < kend; ++k) {
+        const int64_t c = idx[k];
+        const T v = val[k];
+        T x[N];
+        load_pack<T, N>(x, X + c * ldx);
+#pragma unroll
+        for (int i = 0; i < N; ++i) acc[i] += v * x[i];
+    }
+}
+
+// Maps a workgroup id to (tile, slice).  Consecutive workgroup ids are dealt round-robin to the
+// eight XCDs, each with its own L2; the slices of one tile read the same rows of B and A, so they
+// get ids that are congruent modulo 8 and therefore share an L2.
+__device__ __forceinline__ bool tile_and_slice(int bid, int n_tiles, int n_slices, int &tile,
+                                               int &slice) {
+    if (n_slices == 1) {
+        tile = bid;
+        slice = 0;
+    } else {
+        const int per = 8 * n_slices;
+        const int chunk = bid / per, local = bid % per;
+        slice = local >> 3;
+        tile = chunk * 8 + (local & 7);
+    }
+    return tile < n_tiles;
+}
+
+// ------------------------------------------------------------------------------------------
+// MFMA phase: stages the C slice in LDS in operand order and multiplies 16-row blocks of B.
+//
+// k is visited in a permuted order so that each lane can fetch 16 contiguous bytes of its B row:
+// with V = elements per 16 bytes and KC = 4 V, MFMA number (s, q) pairs, in lane group g = l / 16,
+// the element k = KC s + V g + q of the row with row k of C.  The C slice is laid out so that
+// MFMA (s, q, nb) reads 64 consecutive elements: Cl[((s V + q) NB + nb) 64 + l] =
+// C[KC s + V (l / 16) + q][c0 + 16 nb + col_of_m(l % 16)], zero beyond bCol or the slice width.
+//
+// The product is formed transposed (C^T in the first operand, B^T in the second), which leaves
+// lane (g, r) with D1[row r][16 nb + 4 g .. + 3]: four contiguous columns, one vector store.
+template <typename T, int NB>
+__device__ __forceinline__ void stage_c_slice(T *Cl, const T *__restrict__ C, int bcol, int ccol,
+                                              int c0, int w) {
+    constexpr int V = Tr<T>::V, KC = 4 * V;
+    const int ksteps = (bcol + KC - 1) / KC;
+    const int total = ksteps * V * NB * 64;
+    for (int e = threadIdx.x; e < total; e += blockDim.x) {
+        const int l = e & 63;
+        const int rest = e >> 6;
+        const int nb = rest % NB;
+        const int sq = rest / NB;
+        const int k = KC * (sq / V) + V * (l >> 4) + (sq % V);
+        const int col = 16 * nb + Tr<T>::col_of_m(l & 15);
+        Cl[e] = (k < bcol && col < w) ? C[(int64_t)k * ccol + c0 + col] : T(0);
+    }
+}
+
+template <typename T, int NB, bool FAST>
+__device__ __forceinline__ void mfma_row_block(typename Tr<T>::Acc (&acc)[NB], const T *Cl,
+                                               const T *__restrict__ brow, bool valid, int bcol,
+                                               int lane) {
+    constexpr int V = Tr<T>::V, KC = 4 * V;
+    const int g = lane >> 4;
+    const int ksteps = (bcol + KC - 1) / KC;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) acc[nb] = typename Tr<T>::Acc{0, 0, 0, 0};
+    for (int s = 0; s < ksteps; ++s) {
+        const int kb = KC * s + V * g;
+        T av[V];
+        if (FAST) {
+            if (valid && kb < bcol) {
+                load_pack<T, V>(av, brow + kb);
+            } else {
+#pragma unroll
+                for (int q = 0; q < V; ++q) av[q] = T(0);
+            }
+        } else {
+#pragma unroll
+            for (int q = 0; q < V; ++q) av[q] = (valid && kb + q < bcol) ? brow[kb + q] : T(0);
+        }
+#pragma unroll
+        for (int q = 0; q < V; ++q) {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+                acc[nb] = mfma16(Cl[((s * V + q) * NB + nb) * 64 + lane], av[q], acc[nb]);
+        }
+    }
+}
+
+// Stores the four columns a lane holds of accumulator block nb to `dst` (which points at the
+// lane's first column), keeping to columns below w.
+template <typename T, bool FAST>
+__device__ __forceinline__ void store_acc4(T *dst, const typename Tr<T>::Acc &a, int col, int w) {
+    constexpr int V = Tr<T>::V;
+    if (FAST) {
+#pragma unroll
+        for (int h = 0; h < 4 / V; ++h) {
+            if (col + V * h < w) {
+                T tmp[V];
+#pragma unroll
+                for (int i = 0; i < V; ++i) tmp[i] = a[V * h + i];
+                store_pack<T, V>(dst + V * h, tmp);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (col + i < w) dst[i] = a[i];
+    }
+}
+
+// Second phase of a fused tile: rows of D whose D1 operands all sit in the LDS tile.
+template <typename T, bool FAST>
+__device__ __forceinline__ void fused_second_phase(const FusedLaunch &a, const T *tileD1, int ldl,
+                                                   int tile, int c0, int w) {
+    constexpr int VV = FAST ? Tr<T>::V : 1;
+    const int G = pow2_at_least((a.cs + VV - 1) / VV);
+    const int gl = threadIdx.x % G, grp = threadIdx.x / G, ngrp = blockDim.x / G;
+    const int sp0 = a.tile_second_ptr[tile];
+    const int nj = a.tile_second_ptr[tile + 1] - sp0;
+    const T *__restrict__ avals = static_cast<const T *>(a.a_vals);
+    T *__restrict__ D = static_cast<T *>(a.D);
+    const bool active = VV * gl < w;
+    for (int idx = grp; idx < nj; idx += ngrp) {
+        const int j = a.second_rows[sp0 + idx];
+        const int kbeg = a.a_rowptr[j], kend = a.a_rowptr[j + 1];
+        if (active) {
+            T acc[VV];
+#pragma unroll
+            for (int i = 0; i < VV; ++i) acc[i] = T(0);
+            row_dot<T, VV, uint16_t>(acc, a.lcol, avals, kbeg, kend, tileD1 + VV * gl, ldl);
+            store_pack<T, VV>(D + (int64_t)j * a.ccol + c0 + VV * gl, acc);
+        }
+    }
+}
+
+extern __shared__ __align__(16) unsigned char tf_smem[];
+
+template <typename T, int NB, bool FAST>
+__global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLaunch a) {
+    constexpr int V = Tr<T>::V, KC = 4 * V;
+    int tile, slice;
+    if (!tile_and_slice(blockIdx.x, a.n_tiles, a.n_slices, tile, slice)) return;
+    const int c0 = slice * a.cs;
+    const int w = min(a.cs, a.ccol - c0);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+    const int g = lane >> 4, r = lane & 15;
+    const int bcol_pad = (a.bcol + KC - 1) / KC * KC;
+    const int ldl = 16 * NB + V;
+    T *Cl = reinterpret_cast<T *>(tf_smem);
+    T *tileD1 = Cl + (int64_t)bcol_pad * 16 * NB;
+
+    stage_c_slice<T, NB>(Cl, static_cast<const T *>(a.C), a.bcol, a.ccol, c0, w);
+    __syncthreads();
+
+    const int fp0 = a.tile_first_ptr[tile];
+    const int rows = a.tile_first_ptr[tile + 1] - fp0;
+    const int nblk = (rows + 15) >> 4;
+    const T *__restrict__ B = static_cast<const T *>(a.B);
+    T *__restrict__ D1 = static_cast<T *>(a.D1);
+    for (int lb = wave; lb < nblk; lb += nwaves) {
+        const int lr = lb * 16 + r;
+        const bool valid = lr < rows;
+        const uint32_t enc = valid ? (uint32_t)a.first_rows_enc[fp0 + lr] : 0u;
+        const int64_t row = enc & ~kSpillBit;
+        const bool spill = valid && (enc & kSpillBit);
+        typename Tr<T>::Acc acc[NB];
+        mfma_row_block<T, NB, FAST>(acc, Cl, B + row * a.bcol, valid, a.bcol, lane);
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            const int col = 16 * nb + 4 * g;
+            store_acc4<T, true>(tileD1 + (int64_t)lr * ldl + col, acc[nb], 0, 4);
+            if (spill) store_acc4<T, FAST>(D1 + row * a.ccol + c0 + col, acc[nb], col, w);
+        }
+    }
+    __syncthreads();
+    fused_second_phase<T, FAST>(a, tileD1, ldl, tile, c0, w);
+}
+
+template <typename T, bool FAST>
+__global__ __launch_bounds__(kFusedThreads) void k_fused_spmm_spmm(const FusedLaunch a) {
+    constexpr int VV = FAST ? Tr<T>::V : 1;
+    int tile, slice;
+    if (!tile_and_slice(blockIdx.x, a.n_tiles, a.n_slices, tile, slice)) return;
+    const int c0 = slice * a.cs;
+    const int w = min(a.cs, a.ccol - c0);
+    const int ldl = (a.cs + Tr<T>::V - 1) / Tr<T>::V * Tr<T>::V;
+    T *tileD1 = reinterpret_cast<T *>(tf_smem);
+
+    const int G = pow2_at_least((a.cs + VV - 1) / VV);
+    const int gl = threadIdx.x % G, grp = threadIdx.x / G, ngrp = blockDim.x / G;
+    const bool active = VV * gl < w;
+    const int fp0 = a.tile_first_ptr[tile];
+    const int rows = a.tile_first_ptr[tile + 1] - fp0;
+    const T *__restrict__ bvals = static_cast<const T *>(a.Bs.vals);
+    const T *__restrict__ C = static_cast<const T *>(a.C);
+    T *__restrict__ D1 = static_cast<T *>(a.D1);
+    for (int lr = grp; lr < rows; lr += ngrp) {
+        const uint32_t enc = (uint32_t)a.first_rows_enc[fp0 + lr];
+        const int64_t row = enc & ~kSpillBit;
+        const int kbeg = a.Bs.rowptr[row], kend = a.Bs.rowptr[row + 1];
+        if (active) {
+            T acc[VV];
+#pragma unroll
+            for (int i = 0; i < VV; ++i) acc[i] = T(0);
+            row_dot<T, VV, int32_t>(acc, a.Bs.colidx, bvals, kbeg, kend, C + c0 + VV * gl, a.ccol);
+            store_pack<T, VV>(tileD1 + (int64_t)lr * ldl + VV * gl, acc);
+            if (enc & kSpillBit) store_pack<T, VV>(D1 + row * a.ccol + c0 + VV * gl, acc);
+        }
+    }
+    __syncthreads();
+    fused_second_phase<T, FAST>(a, tileD1, ldl, tile, c0, w);
+}
+
+// Row-list SpMM: Y[j][:] = sum_k S.vals[k] X[S.colidx[k]][:] for the rows of one unit per
+// workgroup.  A unit that consists of a single long row is shared by all lane groups of the
+// workgroup, whose partial sums are added in a fixed order through LDS.
+template <typename T, bool FAST>
+__global__ __launch_bounds__(kSpmmThreads) void k_spmm_units(const SpmmLaunch a) {
+    constexpr int VV = FAST ? Tr<T>::V : 1;
+    __shared__ T red[kSpmmThreads * VV];
+    const int u = blockIdx.x;
+    int64_t r0, r1;
+    if (a.unit_ptr) {
+        r0 = a.unit_ptr[u];
+        r1 = a.unit_ptr[u + 1];
+    } else {
+        r0 = (int64_t)u * a.uniform_rows;
+        r1 = r0 + a.uniform_rows < a.n_rows ? r0 + a.uniform_rows : a.n_rows;
+    }
+    const int G = min(64, pow2_at_least((a.ccol + VV - 1) / VV));
+    const int gl = threadIdx.x % G, grp = threadIdx.x / G, ngrp = blockDim.x / G;
+    const T *__restrict__ vals = static_cast<const T *>(a.S.vals);
+    const T *__restrict__ X = static_cast<const T *>(a.X);
+    T *__restrict__ Y = static_cast<T *>(a.Y);
+
+    bool coop = false;
+    if (r1 - r0 == 1) {
+        const int64_t j = a.rows ? a.rows[r0] : r0;
+        coop = a.S.rowptr[j + 1] - a.S.rowptr[j] >= kLongRowNnz;
+    }
+    for (int cb = 0; cb < a.ccol; cb += G * VV) {
+        const int col = cb + VV * gl;
+        const bool active = col < a.ccol;
+        if (!coop) {
+            for (int64_t ri = r0 + grp; ri < r1; ri += ngrp) {
+                const int64_t j = a.rows ? a.rows[ri] : ri;
+                const int kbeg = a.S.rowptr[j], kend = a.S.rowptr[j + 1];
+                if (active) {
+                    T acc[VV];
+#pragma unroll
+                    for (int i = 0; i < VV; ++i) acc[i] = T(0);
+                    row_dot<T, VV, int32_t>(acc, a.S.colidx, vals, kbeg, kend, X + col, a.ccol);
+                    store_pack<T, VV>(Y + j * a.ccol + col, acc);
+                }
+            }
+        } else {
+            const int64_t j = a.rows ? a.rows[r0] : r0;
+            const int kbeg = a.S.rowptr[j], kend = a.S.rowptr[j + 1];
+            const int chunk = (kend - kbeg + ngrp - 1) / ngrp;
+            const int kb = min(kend, kbeg + grp * chunk), ke = min(kend, kb + chunk);
+            T acc[VV];
+#pragma unroll
+            for (int i = 0; i < VV; ++i) acc[i] = T(0);
+            if (active) row_dot<T, VV, int32_t>(acc, a.S.colidx, vals, kb, ke, X + col, a.ccol);
+#pragma unroll
+            for (int i = 0; i < VV; ++i) red[(grp * G + gl) * VV + i] = acc[i];
+            __syncthreads();
+            if (grp == 0 && active) {
+                T sum[VV];
+#pragma unroll
+                for (int i = 0; i < VV; ++i) sum[i] = T(0);
+                for (int gg = 0; gg < ngrp; ++gg)
+#pragma unroll
+                    for (int i = 0; i < VV; ++i) sum[i] += red[(gg * G + gl) * VV + i];
+                store_pack<T, VV>(Y + j * a.ccol + col, sum);
+            }
+            __syncthreads();
+        }
+    }
+}
+
+// D1 = B C for all rows (unfused baseline): one 16-row block per wave at a time.
+template <typename T, int NB, bool FAST>
+__global__ __launch_bounds__(kFusedThreads) void k_gemm(const GemmLaunch a) {
+    const int slice = blockIdx.y;
+    const int c0 = slice * a.cs;
+    const int w = min(a.cs, a.ccol - c0);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+    const int g = lane >> 4, r = lane & 15;
+    T *Cl = reinterpret_cast<T *>(tf_smem);
+    stage_c_slice<T, NB>(Cl, static_cast<const T *>(a.C), a.bcol, a.ccol, c0, w);
+    __syncthreads();
+    const int64_t nblk = (a.n + 15) >> 4;
+    const T *__restrict__ B = static_cast<const T *>(a.B);
+    T *__restrict__ D1 = static_cast<T *>(a.D1);
+    for (int64_t lb = (int64_t)blockIdx.x * nwaves + wave; lb < nblk; lb += (int64_t)gridDim.x * nwaves) {
+        const int64_t row = lb * 16 + r;
+        const bool valid = row < a.n;
+        typename Tr<T>::Acc acc[NB];
+        mfma_row_block<T, NB, FAST>(acc, Cl, B + (valid ? row : 0) * a.bcol, valid, a.bcol, lane);
+        if (valid) {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                const int col = 16 * nb + 4 * g;
+                store_acc4<T, FAST>(D1 + row * a.ccol + c0 + col, acc[nb], col, w);
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------ host
+
+template <typename K> int raise_lds_limit(K kernel, int64_t bytes) {
+    return (int)hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+}
+
+template <typename T, int NB, bool FAST> int run_fused_gemm(const FusedLaunch &a, hipStream_t st) {
+    static int64_t raised = -1;
+    if (a.lds_bytes > raised) {
+        int e = raise_lds_limit(k_fused_gemm_spmm<T, NB, FAST>, a.lds_bytes);
+        if (e) return e;
+        raised = a.lds_bytes;
+    }
+    int64_t grid = a.n_slices == 1 ? a.n_tiles : (int64_t)((a.n_tiles + 7) / 8) * 8 * a.n_slices;
+    k_fused_gemm_spmm<T, NB, FAST><<<dim3((unsigned)grid), dim3(kFusedThreads), a.lds_bytes, st>>>(a);
+    return (int)hipGetLastError();
+}
+
+template <typename T, bool FAST> int run_fused_spmm(const FusedLaunch &a, hipStream_t st) {
+    static int64_t raised = -1;
+    if (a.lds_bytes > raised) {
+        int e = raise_lds_limit(k_fused_spmm_spmm<T, FAST>, a.lds_bytes);
+        if (e) return e;
+        raised = a.lds_bytes;
+    }
+    int64_t grid = a.n_slices == 1 ? a.n_tiles : (int64_t)((a.n_tiles + 7) / 8) * 8 * a.n_slices;
+    k_fused_spmm_spmm<T, FAST><<<dim3((unsigned)grid), dim3(kFusedThreads), a.lds_bytes, st>>>(a);
+    return (int)hipGetLastError();
+}
+
+template <typename T, int NB, bool FAST> int run_gemm(const GemmLaunch &a, hipStream_t st) {
+    const int64_t lds = lds_fixed_bytes(a.dtype, 0, a.bcol, a.cs);
+    static int64_t raised = -1;
+    if (lds > raised) {
+        int e = raise_lds_limit(k_gemm<T, NB, FAST>, lds);
+        if (e) return e;
+        raised = lds;
+    }
+    const int nwaves = kFusedThreads / 64;
+    const int64_t nblk = (a.n + 15) / 16;
+    int64_t gx = (nblk + nwaves - 1) / nwaves;
+    gx = gx < 1 ? 1 : (gx > 1024 ? 1024 : gx);
+    k_gemm<T, NB, FAST><<<dim3((unsigned)gx, (unsigned)a.n_slices), dim3(kFusedThreads), lds, st>>>(a);
+    return (int)hipGetLastError();
+}
+
+template <typename L> int dispatch_nb(int cs, L &&f) {
+    switch (mfma_blocks(cs)) {
+        case 1: return f(std::integral_constant<int, 1>());
+        case 2: return f(std::integral_constant<int, 2>());
+        case 4: return f(std::integral_constant<int, 4>());
+        case 8: return f(std::integral_constant<int, 8>());
+    }
+    return (int)hipErrorInvalidValue;
+}
+
+bool gemm_fast(int dtype, int bcol, int ccol, int cs) {
+    const int v = vec_elems(dtype);
+    return bcol % v == 0 && ccol % v == 0 && (cs % v == 0);
+}
+bool spmm_fast(int dtype, int ccol, int cs) {
+    const int v = vec_elems(dtype);
+    return ccol % v == 0 && cs % v == 0;
+}
+
+}  // namespace
+
+int launch_fused_gemm_spmm(const FusedLaunch &a, void *stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (a.n_tiles == 0) return 0;
+    const bool fast = gemm_fast(a.dtype, a.bcol, a.ccol, a.cs);
+#define TF_GO(T, FAST)                                                                   \
+    return dispatch_nb(a.cs, [&](auto nb) {                                     \
+        return run_fused_gemm<T, decltype(nb)::value, FAST>(a, st);                      \
+    })
+    if (a.dtype == TF_F32) {
+        if (fast) TF_GO(float, true); else TF_GO(float, false);
+    } else {
+        if (fast) TF_GO(double, true); else TF_GO(double, false);
+    }
+#undef TF_GO
+}
+
+int launch_fused_spmm_spmm(const FusedLaunch &a, void *stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (a.n_tiles == 0) return 0;
+    const bool fast = spmm_fast(a.dtype, a.ccol, a.cs);
+    if (a.dtype == TF_F32)
+        return fast ? run_fused_spmm<float, true>(a, st) : run_fused_spmm<float, false>(a, st);
+    return fast ? run_fused_spmm<double, true>(a, st) : run_fused_spmm<double, false>(a, st);
+}
+
+int launch_spmm_units(const SpmmLaunch &a, void *stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (a.n_units == 0) return 0;
+    const bool fast = spmm_fast(a.dtype, a.ccol, a.ccol);
+    const dim3 grid((unsigned)a.n_units), block(kSpmmThreads);
+    if (a.dtype == TF_F32) {
+        if (fast) k_spmm_units<float, true><<<grid, block, 0, st>>>(a);
+        else k_spmm_units<float, false><<<grid, block, 0, st>>>(a);
+    } else {
+        if (fast) k_spmm_units<double, true><<<grid, block, 0, st>>>(a);
+        else k_spmm_units<double, false><<<grid, block, 0, st>>>(a);
+    }
+    return (int)hipGetLastError();
+}
+
+int launch_gemm(const GemmLaunch &a, void *stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (a.n == 0) return 0;
+    const bool fast = gemm_fast(a.dtype, a.bcol, a.ccol, a.cs);
+#define TF_GO(T, FAST)                                                                   \
+    return dispatch_nb(a.cs, [&](auto nb) {                                     \
+        return run_gemm<T, decltype(nb)::value, FAST>(a, st);                            \
+    })
+    if (a.dtype == TF_F32) {
+        if (fast) TF_GO(float, true); else TF_GO(float, false);
+    } else {
+        if (fast) TF_GO(double, true); else TF_GO(double, false);
+    }
+#undef TF_GO
+}
+
+}  // namespace tf

@@ -1,0 +1,57 @@
+"""GPU-side harness for the parity tests: upload, run through the C ABI, download."""
+import numpy as np
+import torch
+
+import oracle
+import paper_2407_00243_amd as tf
+import tf_inputs as ti
+
+TOL = {np.dtype(np.float32): 1e-5, np.dtype(np.float64): 1e-12}
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def dev_csr(M):
+    return tf.DeviceCsr(M.n_rows, M.n_cols, dev(M.rowptr), dev(M.colidx), dev(M.vals))
+
+
+class Case:
+    """One problem resident on the GPU with a plan; `run(fused)` returns D as numpy."""
+
+    def __init__(self, prob, **params):
+        self.prob = prob
+        self.sparse = prob.kind == "spmm_spmm"
+        self.plan = tf.Plan(prob.A, prob.bcol, prob.ccol, self.sparse, **params)
+        self.B = dev_csr(prob.B) if self.sparse else dev(prob.B)
+        self.C = dev(prob.C)
+        self.tdtype = torch.float32 if prob.dtype == np.float32 else torch.float64
+
+    def run(self, fused=True, fill=float("nan")):
+        D = torch.full((self.prob.n, self.prob.ccol), fill, dtype=self.tdtype, device="cuda")
+        stream = torch.cuda.current_stream().cuda_stream
+        if fused:
+            self.plan.run(self.B, self.C, D, stream)
+        else:
+            self.plan.run_unfused(self.B, self.C, D, stream)
+        torch.cuda.synchronize()
+        return D.cpu().numpy()
+
+    def close(self):
+        self.plan.close()
+
+
+def assert_parity(prob, D_gpu, rows=None, what=""):
+    """Element-by-element comparison with the oracle, row-wise normalised by |A||B||C|."""
+    if rows is None:
+        D_ref, W = oracle.chain(prob.A, prob.B, prob.C, parallel=True)
+        got = D_gpu
+    else:
+        D_ref, W = oracle.chain_rows(prob.A, prob.B, prob.C, rows)
+        got = D_gpu[rows]
+    assert np.all(np.isfinite(got)), f"{what}: non-finite output (a row was not written?)"
+    err = oracle.rowwise_rel_err(got, D_ref, W)
+    tol = TOL[np.dtype(prob.dtype)]
+    assert err <= tol, f"{what}: row-wise relative error {err:.3e} > {tol:.0e}"
+    return err

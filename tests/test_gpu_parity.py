@@ -1,0 +1,162 @@
+"""Parity of the HIP path with the CPU oracle, through the C ABI.  All tests need a GPU."""
+import numpy as np
+import pytest
+
+import oracle
+import tf_inputs as ti
+from util import check_schedule, tiles_of, units_of
+
+pytestmark = pytest.mark.gpu
+
+
+def _case(prob, **params):
+    from gpu_util import Case
+    return Case(prob, **params)
+
+
+def _parity(prob, rows=None, fused=True, **params):
+    from gpu_util import assert_parity
+    c = _case(prob, **params)
+    try:
+        D = c.run(fused=fused)
+        err = assert_parity(prob, D, rows, what=f"{prob.name} {params} fused={fused}")
+        return c.plan.schedule(), D, err
+    finally:
+        c.close()
+
+
+# ---------------------------------------------------------------- small versions of the configs
+
+SMALL = [
+    (1, 1000, dict(ct_size=128, p=1)),                    # ragged: 1000 rows, 7 full tiles + 104
+    (1, 4096, dict(ct_size=2048, p=32)),                  # config 1 itself, default rule
+    (1, 4096, dict(ct_size=256, p=1, col_slice=16)),      # two column slices
+    (2, 96, dict(ct_size=1024, p=1)),                     # n = 9216, half-bandwidth 96
+    (2, 96, dict(ct_size=2048, p=1, col_slice=16)),       # sliced, tiles split by step 2
+    (3, 12, dict(ct_size=2048, p=32)),                    # graph with hubs and isolated vertices
+    (4, 20, dict(ct_size=2048, p=1)),                     # n = 8000
+    (4, 20, dict(ct_size=4000, p=1, col_slice=8)),        # sliced so that whole planes fuse
+    (5, 12, dict(ct_size=2048, p=32)),
+]
+
+
+@pytest.mark.parametrize("cfg,scale,params", SMALL)
+@pytest.mark.parametrize("fused", [True, False])
+def test_small_configs(cfg, scale, params, fused):
+    prob = ti.config(cfg, scale_down=scale)
+    s, D, err = _parity(prob, fused=fused, **params)
+    check_schedule(prob.A, s, params["ct_size"], params["p"])
+    empty = np.diff(prob.A.rowptr) == 0
+    assert np.all(D[empty] == 0)
+
+
+# ---------------------------------------------------------------- exact integer inputs
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("kind", ["gemm_spmm", "spmm_spmm"])
+@pytest.mark.parametrize("shape", [(300, 32, 32), (257, 20, 12), (130, 7, 5), (64, 1, 1),
+                                   (500, 48, 160)])
+def test_small_integers_bit_exact(dtype, kind, shape):
+    """Entries in {-2..2}: every summation order is exact, so the fused path, the unfused path
+    and the oracle must agree bit for bit; any missed, doubled or mis-indexed term shows."""
+    n, bcol, ccol = shape
+    A = ti.random_local_csr(n, 6, 5, 0.15, dtype, 41, int_values=True)
+    if kind == "gemm_spmm":
+        B = ti.dense_small_int(n, bcol, dtype, 42)
+    else:
+        B = ti.random_pattern_csr(n, bcol, min(1.0, 4.0 / bcol), dtype, 42, int_values=True,
+                                  duplicates=True, sort_cols=False)
+    C = ti.dense_small_int(bcol, ccol, dtype, 43)
+    prob = ti.Problem("ints", kind, np.dtype(dtype), A, B, C)
+    D_ref, _ = oracle.chain(A, B, C)
+    import paper_2407_00243_amd as tf
+    with tf.Plan(A, bcol, ccol, kind == "spmm_spmm", flags=tf.TF_FLAG_SCHEDULE_ONLY) as pl:
+        s0 = pl.schedule()
+    small_lds = s0["lds_fixed_bytes"] + 48 * s0["lds_bytes_per_row"]     # forces step 2 to split
+    for params in (dict(ct_size=64, p=1), dict(ct_size=150, p=1, fast_mem_bytes=small_lds)):
+        c = _case(prob, **params)
+        try:
+            s = c.plan.schedule()
+            assert 0 < s["n_fused_rows"] and (n < 100 or s["n_wf1_rows"] > 0)
+            check_schedule(A, s, params["ct_size"], params["p"])
+            for fused in (True, False):
+                D = c.run(fused=fused)
+                assert np.array_equal(D.astype(np.float64), D_ref), (params, fused)
+        finally:
+            c.close()
+
+
+# ---------------------------------------------------------------- invariants on the GPU
+
+def test_identity_a_returns_bc():
+    n, bcol, ccol = 777, 64, 64
+    eye = ti.Csr(n, n, np.arange(n + 1, dtype=np.int32), np.arange(n, dtype=np.int32),
+                 np.ones(n, dtype=np.float64))
+    B = ti.dense_normal(n, bcol, np.float64, 51)
+    C = ti.dense_normal(bcol, ccol, np.float64, 52)
+    prob = ti.Problem("A=I", "gemm_spmm", np.dtype(np.float64), eye, B, C)
+    s, D, _ = _parity(prob, ct_size=100, p=1)
+    assert s["n_fused_rows"] == n and s["n_spill_rows"] == 0 and s["n_wf1_units"] == 0
+    _, D_unf, _ = _parity(prob, fused=False, ct_size=100, p=1)
+    assert np.array_equal(D, D_unf)          # same MFMA order for D1, then 1.0 * x
+
+
+def test_column_slices_do_not_change_the_result():
+    """Columns of D are independent and slicing keeps every element's summation order."""
+    prob = ti.config(1, scale_down=2048)
+    _, D_full, _ = _parity(prob, ct_size=256, p=1)
+    for cs in (16, 8):
+        _, D_cs, _ = _parity(prob, ct_size=256, p=1, col_slice=cs)
+        assert np.array_equal(D_full, D_cs)
+
+
+def test_plan_is_reusable_and_overwrites():
+    prob = ti.config(2, scale_down=64)
+    c = _case(prob, ct_size=512, p=1)
+    try:
+        D1 = c.run(fill=7.0)
+        D2 = c.run(fill=float("nan"))
+        D3 = c.run(fused=False)
+        assert np.array_equal(D1, D2)
+        from gpu_util import assert_parity
+        assert_parity(prob, D3)
+    finally:
+        c.close()
+
+
+def test_plan_from_device_csr():
+    from gpu_util import assert_parity, dev, dev_csr
+    import paper_2407_00243_amd as tf
+    import torch
+    prob = ti.config(4, scale_down=12)
+    Ad = dev_csr(prob.A)
+    with tf.Plan(Ad, prob.bcol, prob.ccol, True, ct_size=300, p=1) as pl:
+        C = dev(prob.C)
+        D = torch.empty((prob.n, prob.ccol), dtype=torch.float64, device="cuda")
+        pl.run(Ad, C, D, torch.cuda.current_stream().cuda_stream)      # B aliases A
+        torch.cuda.synchronize()
+        assert_parity(prob, D.cpu().numpy())
+
+
+def test_execution_error_paths():
+    import paper_2407_00243_amd as tf
+    import torch
+    from gpu_util import dev, dev_csr
+    prob = ti.config(1, scale_down=256)
+    with tf.Plan(prob.A, 32, 32, False) as pl:
+        B, C = dev(prob.B), dev(prob.C)
+        D = torch.empty((256, 32), dtype=torch.float64, device="cuda")
+        with pytest.raises(tf.TfError) as e:
+            tf.tf_spmm_spmm(pl.handle, dev_csr(prob.A), C, D)
+        assert e.value.status_name == "TF_EMISMATCH"
+        with pytest.raises(tf.TfError) as e:
+            tf.tf_gemm_spmm(pl.handle, B, C, D.data_ptr() + 8)
+        assert e.value.status_name == "TF_EINVAL"
+        with pytest.raises(tf.TfError) as e:
+            tf.tf_gemm_spmm(pl.handle, None, C, D)
+        assert e.value.status_name == "TF_EINVAL"
+    with tf.Plan(prob.A, 256, 32, True) as pl:
+        A32 = prob.A._replace(vals=prob.A.vals.astype(np.float32))
+        with pytest.raises(tf.TfError) as e:
+            tf.tf_spmm_spmm(pl.handle, dev_csr(A32), dev(prob.C), D)
+        assert e.value.status_name == "TF_EMISMATCH"

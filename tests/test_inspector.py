@@ -1,0 +1,129 @@
+"""Host logic of the library: the inspector behind tf_plan_create, checked without a GPU
+(TF_FLAG_SCHEDULE_ONLY) against the schedule oracle, bit for bit, and its error paths."""
+import numpy as np
+import pytest
+
+import paper_2407_00243_amd as tf
+import tf_inputs as ti
+from util import check_schedule, footprint, tiles_of, units_of
+
+SO = tf.TF_FLAG_SCHEDULE_ONLY
+
+
+def plan_schedule(A, bcol, ccol, sparse, **kw):
+    flags = kw.pop("flags", 0) | SO
+    with tf.Plan(A, bcol, ccol, sparse, flags=flags, **kw) as pl:
+        return pl.schedule()
+
+
+@pytest.mark.parametrize("seed", range(5))
+def test_random_patterns_match_oracle(seed):
+    n = 200 + 37 * seed
+    A = ti.random_pattern_csr(n, n, 0.02, np.float64, seed, sort_cols=False, duplicates=True,
+                              empty_row_prob=0.15)
+    # widen the band of some rows so that fused and unfused rows both occur
+    for ct, p in ((16, 1), (64, 1), (50, 3), (2048, 7), (2048, 1)):
+        s = plan_schedule(A, 8, 8, False, ct_size=ct, p=p)
+        check_schedule(A, s, ct, p)
+        s = plan_schedule(A, n, 8, True, ct_size=ct, p=p)
+        check_schedule(A, s, ct, p)
+
+
+@pytest.mark.parametrize("cfg,params", [
+    (1, dict(ct_size=2048, p=256)), (1, dict(ct_size=2048, p=32)), (1, dict(ct_size=256, p=1)),
+    (2, dict(ct_size=2048, p=32)), (2, dict(ct_size=4096, p=1, col_slice=16)),
+    (2, dict(ct_size=8192, p=1, col_slice=8)),
+    (4, dict(ct_size=2048, p=32)), (4, dict(ct_size=16384, p=1, col_slice=2)),
+])
+def test_structured_configs_match_oracle(cfg, params):
+    prob = ti.config(cfg)
+    s = plan_schedule(prob.A, prob.bcol, prob.ccol, prob.kind == "spmm_spmm", **params)
+    check_schedule(prob.A, s, params["ct_size"], params["p"])
+    assert s["n_slices"] == -(-prob.ccol // s["col_slice"])
+    for first, _ in tiles_of(s):
+        assert footprint(s, first.size) <= s["fast_mem_bytes"]
+
+
+def test_closed_form_counts_through_the_abi():
+    A = ti.banded(4096, 8, np.float64, 1)
+    for t, want in ((16, 16), (32, 2064), (256, 3856)):
+        s = plan_schedule(A, 32, 32, False, ct_size=t, p=1)
+        assert s["n_fused_rows"] == want
+    s = plan_schedule(A, 32, 32, False, ct_size=256, p=1)
+    assert s["n_spill_rows"] == 480
+    # Algorithm 1's rule with p = 256 "cores" leaves 16-row tiles and almost nothing to fuse
+    s = plan_schedule(A, 32, 32, False, ct_size=2048, p=256)
+    assert s["t"] == 16 and s["n_fused_rows"] == 16
+
+
+@pytest.mark.parametrize("cfg,scale", [(3, 14), (5, 14)])
+def test_graph_configs_match_oracle(cfg, scale):
+    prob = ti.config(cfg, scale_down=scale)
+    s = plan_schedule(prob.A, prob.bcol, prob.ccol, prob.kind == "spmm_spmm", ct_size=2048, p=32)
+    check_schedule(prob.A, s, 2048, 32)
+    lens = np.diff(prob.A.rowptr)
+    # long rows get a unit of their own, placed first, longest first
+    units = units_of(s)
+    long_rows = [u[0] for u in units if u.size == 1 and lens[u[0]] >= 2048]
+    assert all(lens[long_rows[i]] >= lens[long_rows[i + 1]] for i in range(len(long_rows) - 1))
+    assert set(np.nonzero(lens >= 2048)[0]) - set(s["second_rows"]) == set(long_rows)
+
+
+def test_step2_splits_to_the_lds_budget():
+    prob = ti.config(2, scale_down=128)           # n = 16384, fp32, 64 -> 64
+    s = plan_schedule(prob.A, 64, 64, False, ct_size=4096, p=1, fast_mem_bytes=96 * 1024)
+    ref = check_schedule(prob.A, s, 4096, 1)
+    sizes = {i1 - i0 for (i0, i1, _) in ref["tiles"]}
+    assert sizes == {256}                          # 4096 -> ... -> 256 rows * 272 B + 16 KiB
+    assert s["n_coarse_tiles"] == 4 and s["n_tiles"] == 64
+    with pytest.raises(tf.TfError) as e:
+        plan_schedule(prob.A, 64, 64, False, ct_size=4096, p=1, fast_mem_bytes=96 * 1024,
+                      flags=tf.TF_FLAG_NO_SPLIT)
+    assert e.value.status_name == "TF_EUNSUPPORTED"
+
+
+def test_degenerate_inputs():
+    empty = ti.Csr(0, 0, np.zeros(1, np.int32), np.zeros(0, np.int32), np.zeros(0, np.float32))
+    s = plan_schedule(empty, 4, 4, False)
+    assert s["n_tiles"] == 0 and s["n_wf1_units"] == 0 and s["n_fused_rows"] == 0
+    n = 10
+    no_entries = ti.Csr(n, n, np.zeros(n + 1, np.int32), np.zeros(0, np.int32),
+                        np.zeros(0, np.float64))
+    s = plan_schedule(no_entries, 4, 4, False, ct_size=4, p=1)
+    assert s["n_fused_rows"] == n and s["n_wf1_rows"] == 0 and s["n_spill_rows"] == 0
+    one = ti.Csr(1, 1, np.array([0, 1], np.int32), np.array([0], np.int32), np.ones(1, np.float32))
+    s = plan_schedule(one, 1, 1, False)
+    assert s["n_tiles"] == 1 and s["n_fused_rows"] == 1
+
+
+def bad(A, **kw):
+    with pytest.raises(tf.TfError) as e:
+        plan_schedule(A, kw.pop("bcol", 4), kw.pop("ccol", 4), False, **kw)
+    return e.value.status_name
+
+
+def test_error_paths():
+    A = ti.banded(32, 2, np.float64, 1)
+    assert bad(A, bcol=0) == "TF_EINVAL"
+    assert bad(A, ccol=-1) == "TF_EINVAL"
+    assert bad(A, ct_size=-1) == "TF_EINVAL"
+    assert bad(A, fast_mem_bytes=64) == "TF_EUNSUPPORTED"     # not even one D1 row fits
+    assert bad(A, ccol=64, col_slice=5) == "TF_EINVAL"        # not a multiple of 16 bytes
+    rp = A.rowptr.copy()
+    rp[5], rp[6] = rp[6], rp[5]
+    assert bad(A._replace(rowptr=rp)) == "TF_EBADCSR"
+    rp = A.rowptr.copy()
+    rp[-1] -= 1
+    assert bad(A._replace(rowptr=rp)) == "TF_EBADCSR"
+    ci = A.colidx.copy()
+    ci[3] = 32
+    assert bad(A._replace(colidx=ci)) == "TF_EBADCSR"
+    ci[3] = -1
+    assert bad(A._replace(colidx=ci)) == "TF_EBADCSR"
+    assert bad(A._replace(n_cols=33)) == "TF_EINVAL"           # not square
+    assert "square" in tf.tf_last_error()
+    # a schedule-only plan cannot execute
+    with tf.Plan(A, 4, 4, False, flags=SO) as pl:
+        with pytest.raises(tf.TfError) as e:
+            tf.tf_gemm_spmm(pl.handle, 16, 16, 16)
+        assert e.value.status_name == "TF_EINVAL"

@@ -232,6 +232,32 @@ def random_pattern_csr(n_rows: int, n_cols: int, density: float, dtype, seed: in
     return Csr(n_rows, n_cols, np.asarray(rowptr, dtype=np.int32), colidx, vals)
 
 
+def random_local_csr(n: int, width: int, nnz_per_row: int, far_prob: float, dtype, seed: int,
+                     int_values: bool = False, empty_row_prob: float = 0.1) -> Csr:
+    """Small square test matrix whose rows mostly stay within `width` of the diagonal, so that
+    consecutive tiles fuse many rows, while a fraction `far_prob` of the rows also holds one
+    far-away column.  Columns are unsorted and may repeat."""
+    rng = _rng(seed)
+    rowptr = [0]
+    cols = []
+    for j in range(n):
+        if rng.random() < empty_row_prob:
+            rowptr.append(rowptr[-1])
+            continue
+        lo, hi = max(0, j - width), min(n, j + width + 1)
+        c = rng.integers(lo, hi, size=nnz_per_row)
+        if rng.random() < far_prob:
+            c = np.append(c, rng.integers(0, n))
+        cols.append(c)
+        rowptr.append(rowptr[-1] + c.size)
+    colidx = np.concatenate(cols).astype(np.int32) if cols else np.zeros(0, np.int32)
+    if int_values:
+        vals = rng.integers(-2, 3, size=colidx.size).astype(dtype)
+    else:
+        vals = rng.uniform(-1.0, 1.0, size=colidx.size).astype(dtype)
+    return Csr(n, n, np.asarray(rowptr, dtype=np.int32), colidx, vals)
+
+
 def dense_normal(rows: int, cols: int, dtype, seed: int, std: float = 1.0) -> np.ndarray:
     return np.ascontiguousarray((_rng(seed).standard_normal((rows, cols)) * std).astype(dtype))
 
