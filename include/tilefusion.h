@@ -159,6 +159,13 @@ tf_status tf_unfused_gemm_spmm(const tf_plan *plan, const void *B, const void *C
 tf_status tf_unfused_spmm_spmm(const tf_plan *plan, const tf_csr *B, const void *C, void *D,
                                void *hip_stream);
 
+/* One wavefront of the fused execution on its own (wavefront 0 = fused tiles, 1 = leftover
+ * rows), for per-kernel timing and tests.  Pass the dense B in B_dense or the CSR B in B_csr
+ * according to the plan (the other NULL; both may be NULL for wavefront 1, which reads only the
+ * plan's workspace).  Wavefront 1 is only meaningful after wavefront 0 of the same inputs. */
+tf_status tf_run_wavefront(const tf_plan *plan, int32_t wavefront, const void *B_dense,
+                           const tf_csr *B_csr, const void *C, void *D, void *hip_stream);
+
 /* Device pointer of the plan's D1 workspace (n x cCol, row-major).  After a fused execution
  * only the spilled rows hold D1; after an unfused execution all rows do.  For tests. */
 tf_status tf_plan_workspace(const tf_plan *plan, void **d1_device);

@@ -70,7 +70,7 @@ class tf_schedule_view(ctypes.Structure):
 
 EXPORTS = ["tf_plan_create", "tf_plan_destroy", "tf_plan_schedule", "tf_plan_workspace",
            "tf_gemm_spmm", "tf_spmm_spmm", "tf_unfused_gemm_spmm", "tf_unfused_spmm_spmm",
-           "tf_last_error", "tf_version"]
+           "tf_run_wavefront", "tf_last_error", "tf_version"]
 
 
 def library_path() -> str:
@@ -96,7 +96,8 @@ def load_library():
     lib.tf_unfused_gemm_spmm.argtypes = [vp, vp, vp, vp, vp]
     lib.tf_spmm_spmm.argtypes = [vp, ctypes.POINTER(tf_csr), vp, vp, vp]
     lib.tf_unfused_spmm_spmm.argtypes = [vp, ctypes.POINTER(tf_csr), vp, vp, vp]
-    for name in EXPORTS[:8]:
+    lib.tf_run_wavefront.argtypes = [vp, i32, vp, ctypes.POINTER(tf_csr), vp, vp, vp]
+    for name in EXPORTS[:9]:
         getattr(lib, name).restype = ctypes.c_int
     lib.tf_last_error.restype = ctypes.c_char_p
     lib.tf_version.restype = ctypes.c_char_p
@@ -235,6 +236,18 @@ def tf_unfused_spmm_spmm(plan: int, B, C, D, stream=None) -> None:
                                                _addr(stream)))
 
 
+def tf_run_wavefront(plan: int, wavefront: int, B, C, D, stream=None) -> None:
+    """B: dense device operand, DeviceCsr / tf_csr, or None (wavefront 1 only)."""
+    lib = load_library()
+    if B is None or hasattr(B, "data_ptr") or isinstance(B, int):
+        _check(lib.tf_run_wavefront(plan, wavefront, _addr(B), None, _addr(C), _addr(D),
+                                    _addr(stream)))
+    else:
+        b = _csr_arg(B)
+        _check(lib.tf_run_wavefront(plan, wavefront, None, ctypes.byref(b), _addr(C), _addr(D),
+                                    _addr(stream)))
+
+
 class Plan:
     """Owns a plan handle; a convenience over the tf_* functions."""
 
@@ -251,6 +264,9 @@ class Plan:
     def run_unfused(self, B, C, D, stream=None) -> None:
         (tf_unfused_spmm_spmm if self.b_is_sparse else tf_unfused_gemm_spmm)(
             self.handle, B, C, D, stream)
+
+    def run_wavefront(self, wavefront: int, B, C, D, stream=None) -> None:
+        tf_run_wavefront(self.handle, wavefront, B, C, D, stream)
 
     def workspace(self) -> int:
         return tf_plan_workspace(self.handle)

@@ -367,6 +367,36 @@ tf_status tf_spmm_spmm(const tf_plan *p, const tf_csr *B, const void *C, void *D
     return TF_OK;
 }
 
+tf_status tf_run_wavefront(const tf_plan *p, int32_t wavefront, const void *B_dense,
+                           const tf_csr *B_csr, const void *C, void *D, void *stream) {
+    if (!p) return fail(TF_EINVAL, "null argument");
+    tf_status st = check_exec(p, p->b_is_sparse, C, D);
+    if (st != TF_OK) return st;
+    if (wavefront == 1) {
+        int e = tf::launch_spmm_units(second_wavefront_args(p, D), stream);
+        if (e) return hip_fail((hipError_t)e, "launching the second wavefront");
+        return TF_OK;
+    }
+    if (wavefront != 0) return fail(TF_EINVAL, "wavefront must be 0 or 1");
+    tf::FusedLaunch a = fused_args(p, C, D);
+    int e;
+    if (p->b_is_sparse) {
+        st = check_sparse_b(p, B_csr);
+        if (st != TF_OK) return st;
+        a.Bs.rowptr = B_csr->rowptr;
+        a.Bs.colidx = B_csr->colidx;
+        a.Bs.vals = B_csr->vals;
+        e = tf::launch_fused_spmm_spmm(a, stream);
+    } else {
+        if (!B_dense || !aligned16(B_dense))
+            return fail(TF_EINVAL, "B must be a 16-byte aligned device pointer");
+        a.B = B_dense;
+        e = tf::launch_fused_gemm_spmm(a, stream);
+    }
+    if (e) return hip_fail((hipError_t)e, "launching the first wavefront");
+    return TF_OK;
+}
+
 tf_status tf_unfused_gemm_spmm(const tf_plan *p, const void *B, const void *C, void *D,
                                void *stream) {
     tf_status st = check_exec(p, 0, C, D);

@@ -14,7 +14,7 @@ constexpr int kRowGranuleDense = 16;     // dense-B tiles are produced in blocks
 constexpr int kFusedThreads = 512;       // workgroup size of the fused kernels
 constexpr int kSpmmThreads = 256;        // workgroup size of the row-list SpMM kernel
 constexpr int kLongRowNnz = 2048;        // a second-wavefront row this long gets a workgroup of its own
-constexpr int kUnitWork = 4096;          // target work (nnz + 8 per row) of one second-wavefront unit
+constexpr int kUnitWork = 1024;          // target work (nnz + 8 per row) of one second-wavefront unit
 constexpr uint32_t kSpillBit = 0x80000000u;
 
 inline int elem_size(int dtype) { return dtype == TF_F64 ? 8 : 4; }
@@ -37,7 +37,7 @@ inline int mfma_blocks(int cs) {
 inline int mfma_cols(int cs) { return 16 * mfma_blocks(cs); }
 inline int64_t lds_ldl(int dtype, int b_is_sparse, int cs) {
     const int v = vec_elems(dtype);
-    return b_is_sparse ? round_up(cs, v) : mfma_cols(cs) + v;
+    return b_is_sparse ? round_up(cs, v) : round_up(cs, v) + v;
 }
 inline int64_t lds_fixed_bytes(int dtype, int b_is_sparse, int bcol, int cs) {
     if (b_is_sparse) return 0;

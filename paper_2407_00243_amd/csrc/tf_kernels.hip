@@ -106,21 +106,24 @@ __device__ __forceinline__ void row_dot(T (&acc)[N], const IdxT *__restrict__ id
     }
 }
 
-// Maps a workgroup id to (tile, slice).  Consecutive workgroup ids are dealt round-robin to the
-// eight XCDs, each with its own L2; the slices of one tile read the same rows of B and A, so they
-// get ids that are congruent modulo 8 and therefore share an L2.
+// Consecutive workgroup ids are dealt round-robin to the eight XCDs, each with its own L2.
+// Work items that touch neighbouring rows (adjacent tiles, the column slices of one tile, adjacent
+// units of the second wavefront) should share an L2, so item ids are handed out in eight
+// contiguous ranges, one per XCD: workgroup b works on item (b % 8) * ceil(total / 8) + b / 8.
+__device__ __forceinline__ int64_t xcd_contiguous(int64_t bid, int64_t total) {
+    const int64_t per = (total + 7) >> 3;
+    return (bid & 7) * per + (bid >> 3);
+}
+
+// (tile, slice) of a fused workgroup: the slices of a tile run back to back on one XCD.
 __device__ __forceinline__ bool tile_and_slice(int bid, int n_tiles, int n_slices, int &tile,
                                                int &slice) {
-    if (n_slices == 1) {
-        tile = bid;
-        slice = 0;
-    } else {
-        const int per = 8 * n_slices;
-        const int chunk = bid / per, local = bid % per;
-        slice = local >> 3;
-        tile = chunk * 8 + (local & 7);
-    }
-    return tile < n_tiles;
+    const int per = (n_tiles + 7) >> 3;
+    const int q = bid >> 3;
+    slice = q % n_slices;
+    const int local = q / n_slices;
+    tile = (bid & 7) * per + local;
+    return local < per && tile < n_tiles;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -205,6 +208,99 @@ __device__ __forceinline__ void store_acc4(T *dst, const typename Tr<T>::Acc &a,
     }
 }
 
+// Gathers for R rows at once by one lane group: acc[r][0..N) += sum_k val[k] * X[idx[k] * ldx + ..]
+// over k in [kb[r], ke[r]), k ascending per row.  E entries of every row are fetched per pass, so
+// R * E independent gathers are in flight per lane; this is what hides the latency of the
+// dependent index -> operand loads for short rows.  Slots beyond a row's end repeat a valid
+// entry (so every load is unconditional and nothing waits on a branch) and are masked out of
+// the sum; `k_any` is any valid entry index, used for rows that are empty.
+template <typename T, int N, typename IdxT, int R, int E>
+__device__ __forceinline__ void rows_dot(T (&acc)[R][N], const IdxT *__restrict__ idx,
+                                         const T *__restrict__ val, const int (&kb)[R],
+                                         const int (&ke)[R], const T *X, int64_t ldx) {
+    int maxlen = 0, k_any = 0;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        if (ke[r] - kb[r] > maxlen) {
+            maxlen = ke[r] - kb[r];
+            k_any = kb[r];
+        }
+    }
+    for (int off = 0; off < maxlen; off += E) {
+        int64_t c[R][E];
+        T v[R][E];
+        bool ok[R][E];
+        T x[R][E][N];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int last = ke[r] > kb[r] ? ke[r] - 1 : k_any;
+#pragma unroll
+            for (int e = 0; e < E; ++e) {
+                const int k = kb[r] + off + e;
+                ok[r][e] = k < ke[r];
+                const int kc = ok[r][e] ? k : last;
+                c[r][e] = (int64_t)idx[kc];
+                v[r][e] = val[kc];
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int e = 0; e < E; ++e) load_pack<T, N>(x[r][e], X + c[r][e] * ldx);
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+#pragma unroll
+            for (int e = 0; e < E; ++e) {
+                const T vv = ok[r][e] ? v[r][e] : T(0);
+#pragma unroll
+                for (int i = 0; i < N; ++i) acc[r][i] += vv * (ok[r][e] ? x[r][e][i] : T(0));
+            }
+        }
+    }
+}
+
+// One lane group walks the list positions first, first + stride, ... below count, R at a time.
+// row_of(pos) names the CSR row at a list position; out(pos, row, acc) consumes its result.
+template <typename T, int N, typename IdxT, int R, int E, typename RowFn, typename OutFn>
+__device__ __forceinline__ void gather_rows(int first, int count, int stride,
+                                            const int32_t *__restrict__ rowptr,
+                                            const IdxT *__restrict__ idx,
+                                            const T *__restrict__ val, const T *X, int64_t ldx,
+                                            bool active, RowFn row_of, OutFn out) {
+    for (int base = first; base < count; base += stride * R) {
+        int64_t row[R];
+        int kb[R], ke[R];
+        bool ok[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int pos = base + r * stride;
+            ok[r] = pos < count;
+            row[r] = (int64_t)row_of(ok[r] ? pos : base);      // `base` is always in range
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            kb[r] = rowptr[row[r]];
+            ke[r] = rowptr[row[r] + 1];
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) ke[r] = ok[r] ? ke[r] : kb[r];
+        if (active) {
+            T acc[R][N];
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int i = 0; i < N; ++i) acc[r][i] = T(0);
+            rows_dot<T, N, IdxT, R, E>(acc, idx, val, kb, ke, X, ldx);
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                if (ok[r]) out(base + r * stride, row[r], acc[r]);
+        }
+    }
+}
+
+constexpr int kRowsPerPass = 4;     // R: rows a lane group works on at once
+constexpr int kEntriesPerPass = 4;  // E: entries of each of those rows fetched per pass
+
 // Second phase of a fused tile: rows of D whose D1 operands all sit in the LDS tile.
 template <typename T, bool FAST>
 __device__ __forceinline__ void fused_second_phase(const FusedLaunch &a, const T *tileD1, int ldl,
@@ -216,23 +312,56 @@ __device__ __forceinline__ void fused_second_phase(const FusedLaunch &a, const T
     const int nj = a.tile_second_ptr[tile + 1] - sp0;
     const T *__restrict__ avals = static_cast<const T *>(a.a_vals);
     T *__restrict__ D = static_cast<T *>(a.D);
-    const bool active = VV * gl < w;
-    for (int idx = grp; idx < nj; idx += ngrp) {
-        const int j = a.second_rows[sp0 + idx];
-        const int kbeg = a.a_rowptr[j], kend = a.a_rowptr[j + 1];
-        if (active) {
-            T acc[VV];
-#pragma unroll
-            for (int i = 0; i < VV; ++i) acc[i] = T(0);
-            row_dot<T, VV, uint16_t>(acc, a.lcol, avals, kbeg, kend, tileD1 + VV * gl, ldl);
-            store_pack<T, VV>(D + (int64_t)j * a.ccol + c0 + VV * gl, acc);
-        }
-    }
+    const int32_t *__restrict__ second = a.second_rows + sp0;
+    const int ccol = a.ccol;
+    gather_rows<T, VV, uint16_t, kRowsPerPass, kEntriesPerPass>(
+        grp, nj, ngrp, a.a_rowptr, a.lcol, avals, tileD1 + VV * gl, ldl, VV * gl < w,
+        [&](int pos) { return second[pos]; },
+        [&](int, int64_t j, const T(&acc)[VV]) {
+            store_pack<T, VV>(D + j * ccol + c0 + VV * gl, acc);
+        });
 }
 
 extern __shared__ __align__(16) unsigned char tf_smem[];
 
-template <typename T, int NB, bool FAST>
+// B operand of one 16-row block, all k: KS vectors of V elements per lane.
+template <typename T, int KS> struct BFrag {
+    T v[KS][Tr<T>::V];
+};
+
+template <typename T, int KS>
+__device__ __forceinline__ void load_b_frag(BFrag<T, KS> &f, const T *__restrict__ brow,
+                                            bool valid, int g) {
+    constexpr int V = Tr<T>::V, KC = 4 * V;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+        if (valid) {
+            load_pack<T, V>(f.v[s], brow + KC * s + V * g);
+        } else {
+#pragma unroll
+            for (int q = 0; q < V; ++q) f.v[s][q] = T(0);
+        }
+    }
+}
+
+template <typename T, int NB, int KS>
+__device__ __forceinline__ void mfma_frag(typename Tr<T>::Acc (&acc)[NB], const T *Cl,
+                                          const BFrag<T, KS> &f, int lane) {
+    constexpr int V = Tr<T>::V;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) acc[nb] = typename Tr<T>::Acc{0, 0, 0, 0};
+#pragma unroll
+    for (int s = 0; s < KS; ++s)
+#pragma unroll
+        for (int q = 0; q < V; ++q)
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+                acc[nb] = mfma16(Cl[((s * V + q) * NB + nb) * 64 + lane], f.v[s][q], acc[nb]);
+}
+
+// First wavefront, dense B.  KS > 0: bCol = 4 V KS exactly, the B rows of the next 16-row block
+// are fetched while the current block is multiplied; KS = 0: any bCol, no prefetch.
+template <typename T, int NB, int KS, bool FAST>
 __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLaunch a) {
     constexpr int V = Tr<T>::V, KC = 4 * V;
     int tile, slice;
@@ -242,7 +371,8 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
     const int g = lane >> 4, r = lane & 15;
     const int bcol_pad = (a.bcol + KC - 1) / KC * KC;
-    const int ldl = 16 * NB + V;
+    const int csv = (a.cs + V - 1) / V * V;
+    const int ldl = csv + V;
     T *Cl = reinterpret_cast<T *>(tf_smem);
     T *tileD1 = Cl + (int64_t)bcol_pad * 16 * NB;
 
@@ -254,19 +384,48 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
     const int nblk = (rows + 15) >> 4;
     const T *__restrict__ B = static_cast<const T *>(a.B);
     T *__restrict__ D1 = static_cast<T *>(a.D1);
-    for (int lb = wave; lb < nblk; lb += nwaves) {
+    const int32_t *__restrict__ first = a.first_rows_enc + fp0;
+    auto enc_of = [&](int lb) -> uint32_t {      // row id and spill flag of this lane's row, 0 if none
         const int lr = lb * 16 + r;
-        const bool valid = lr < rows;
-        const uint32_t enc = valid ? (uint32_t)a.first_rows_enc[fp0 + lr] : 0u;
+        return (lb < nblk && lr < rows) ? ((uint32_t)first[lr] | 0u) : 0xffffffffu;
+    };
+    auto write_block = [&](int lb, uint32_t enc, typename Tr<T>::Acc(&acc)[NB]) {
+        const int lr = lb * 16 + r;
+        const bool valid = enc != 0xffffffffu;
         const int64_t row = enc & ~kSpillBit;
         const bool spill = valid && (enc & kSpillBit);
-        typename Tr<T>::Acc acc[NB];
-        mfma_row_block<T, NB, FAST>(acc, Cl, B + row * a.bcol, valid, a.bcol, lane);
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
             const int col = 16 * nb + 4 * g;
-            store_acc4<T, true>(tileD1 + (int64_t)lr * ldl + col, acc[nb], 0, 4);
+            store_acc4<T, true>(tileD1 + (int64_t)lr * ldl + col, acc[nb], col, csv);
             if (spill) store_acc4<T, FAST>(D1 + row * a.ccol + c0 + col, acc[nb], col, w);
+        }
+    };
+    if constexpr (KS > 0) {
+        constexpr int KSF = KS;
+        BFrag<T, KSF> cur, nxt;
+        uint32_t enc_cur = enc_of(wave), enc_nxt = enc_of(wave + nwaves);
+        load_b_frag<T, KSF>(cur, B + (int64_t)(enc_cur & ~kSpillBit) * a.bcol,
+                            enc_cur != 0xffffffffu, g);
+        for (int lb = wave; lb < nblk; lb += nwaves) {
+            const uint32_t enc_nn = enc_of(lb + 2 * nwaves);
+            load_b_frag<T, KSF>(nxt, B + (int64_t)(enc_nxt & ~kSpillBit) * a.bcol,
+                                enc_nxt != 0xffffffffu, g);
+            typename Tr<T>::Acc acc[NB];
+            mfma_frag<T, NB, KSF>(acc, Cl, cur, lane);
+            write_block(lb, enc_cur, acc);
+            cur = nxt;
+            enc_cur = enc_nxt;
+            enc_nxt = enc_nn;
+        }
+    } else {
+        for (int lb = wave; lb < nblk; lb += nwaves) {
+            const uint32_t enc = enc_of(lb);
+            const bool valid = enc != 0xffffffffu;
+            typename Tr<T>::Acc acc[NB];
+            mfma_row_block<T, NB, FAST>(acc, Cl, B + (int64_t)(enc & ~kSpillBit) * a.bcol, valid,
+                                        a.bcol, lane);
+            write_block(lb, enc, acc);
         }
     }
     __syncthreads();
@@ -285,25 +444,21 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_spmm_spmm(const FusedLa
 
     const int G = pow2_at_least((a.cs + VV - 1) / VV);
     const int gl = threadIdx.x % G, grp = threadIdx.x / G, ngrp = blockDim.x / G;
-    const bool active = VV * gl < w;
     const int fp0 = a.tile_first_ptr[tile];
     const int rows = a.tile_first_ptr[tile + 1] - fp0;
     const T *__restrict__ bvals = static_cast<const T *>(a.Bs.vals);
     const T *__restrict__ C = static_cast<const T *>(a.C);
     T *__restrict__ D1 = static_cast<T *>(a.D1);
-    for (int lr = grp; lr < rows; lr += ngrp) {
-        const uint32_t enc = (uint32_t)a.first_rows_enc[fp0 + lr];
-        const int64_t row = enc & ~kSpillBit;
-        const int kbeg = a.Bs.rowptr[row], kend = a.Bs.rowptr[row + 1];
-        if (active) {
-            T acc[VV];
-#pragma unroll
-            for (int i = 0; i < VV; ++i) acc[i] = T(0);
-            row_dot<T, VV, int32_t>(acc, a.Bs.colidx, bvals, kbeg, kend, C + c0 + VV * gl, a.ccol);
-            store_pack<T, VV>(tileD1 + (int64_t)lr * ldl + VV * gl, acc);
-            if (enc & kSpillBit) store_pack<T, VV>(D1 + row * a.ccol + c0 + VV * gl, acc);
-        }
-    }
+    const int32_t *__restrict__ first = a.first_rows_enc + fp0;
+    const int ccol = a.ccol;
+    gather_rows<T, VV, int32_t, kRowsPerPass, kEntriesPerPass>(
+        grp, rows, ngrp, a.Bs.rowptr, a.Bs.colidx, bvals, C + c0 + VV * gl, ccol, VV * gl < w,
+        [&](int pos) { return (int32_t)((uint32_t)first[pos] & ~kSpillBit); },
+        [&](int pos, int64_t row, const T(&acc)[VV]) {
+            store_pack<T, VV>(tileD1 + (int64_t)pos * ldl + VV * gl, acc);
+            if ((uint32_t)first[pos] & kSpillBit)
+                store_pack<T, VV>(D1 + row * ccol + c0 + VV * gl, acc);
+        });
     __syncthreads();
     fused_second_phase<T, FAST>(a, tileD1, ldl, tile, c0, w);
 }
@@ -315,13 +470,14 @@ template <typename T, bool FAST>
 __global__ __launch_bounds__(kSpmmThreads) void k_spmm_units(const SpmmLaunch a) {
     constexpr int VV = FAST ? Tr<T>::V : 1;
     __shared__ T red[kSpmmThreads * VV];
-    const int u = blockIdx.x;
+    const int64_t u = xcd_contiguous(blockIdx.x, a.n_units);
+    if (u >= a.n_units) return;
     int64_t r0, r1;
     if (a.unit_ptr) {
         r0 = a.unit_ptr[u];
         r1 = a.unit_ptr[u + 1];
     } else {
-        r0 = (int64_t)u * a.uniform_rows;
+        r0 = u * a.uniform_rows;
         r1 = r0 + a.uniform_rows < a.n_rows ? r0 + a.uniform_rows : a.n_rows;
     }
     const int G = min(64, pow2_at_least((a.ccol + VV - 1) / VV));
@@ -329,36 +485,40 @@ __global__ __launch_bounds__(kSpmmThreads) void k_spmm_units(const SpmmLaunch a)
     const T *__restrict__ vals = static_cast<const T *>(a.S.vals);
     const T *__restrict__ X = static_cast<const T *>(a.X);
     T *__restrict__ Y = static_cast<T *>(a.Y);
+    const int32_t *__restrict__ rows = a.rows;
+    const int ccol = a.ccol;
 
     bool coop = false;
     if (r1 - r0 == 1) {
-        const int64_t j = a.rows ? a.rows[r0] : r0;
+        const int64_t j = rows ? rows[r0] : r0;
         coop = a.S.rowptr[j + 1] - a.S.rowptr[j] >= kLongRowNnz;
     }
-    for (int cb = 0; cb < a.ccol; cb += G * VV) {
+    for (int cb = 0; cb < ccol; cb += G * VV) {
         const int col = cb + VV * gl;
-        const bool active = col < a.ccol;
+        const bool active = col < ccol;
         if (!coop) {
-            for (int64_t ri = r0 + grp; ri < r1; ri += ngrp) {
-                const int64_t j = a.rows ? a.rows[ri] : ri;
-                const int kbeg = a.S.rowptr[j], kend = a.S.rowptr[j + 1];
-                if (active) {
-                    T acc[VV];
-#pragma unroll
-                    for (int i = 0; i < VV; ++i) acc[i] = T(0);
-                    row_dot<T, VV, int32_t>(acc, a.S.colidx, vals, kbeg, kend, X + col, a.ccol);
-                    store_pack<T, VV>(Y + j * a.ccol + col, acc);
-                }
+            auto out = [&](int, int64_t j, const T(&acc)[VV]) {
+                store_pack<T, VV>(Y + j * ccol + col, acc);
+            };
+            if (rows) {
+                const int32_t *__restrict__ list = rows + r0;
+                gather_rows<T, VV, int32_t, kRowsPerPass, kEntriesPerPass>(
+                    grp, (int)(r1 - r0), ngrp, a.S.rowptr, a.S.colidx, vals, X + col, ccol, active,
+                    [&](int pos) { return list[pos]; }, out);
+            } else {
+                gather_rows<T, VV, int32_t, kRowsPerPass, kEntriesPerPass>(
+                    grp, (int)(r1 - r0), ngrp, a.S.rowptr, a.S.colidx, vals, X + col, ccol, active,
+                    [&](int pos) { return (int32_t)(r0 + pos); }, out);
             }
         } else {
-            const int64_t j = a.rows ? a.rows[r0] : r0;
+            const int64_t j = rows ? rows[r0] : r0;
             const int kbeg = a.S.rowptr[j], kend = a.S.rowptr[j + 1];
             const int chunk = (kend - kbeg + ngrp - 1) / ngrp;
             const int kb = min(kend, kbeg + grp * chunk), ke = min(kend, kb + chunk);
             T acc[VV];
 #pragma unroll
             for (int i = 0; i < VV; ++i) acc[i] = T(0);
-            if (active) row_dot<T, VV, int32_t>(acc, a.S.colidx, vals, kb, ke, X + col, a.ccol);
+            if (active) row_dot<T, VV, int32_t>(acc, a.S.colidx, vals, kb, ke, X + col, ccol);
 #pragma unroll
             for (int i = 0; i < VV; ++i) red[(grp * G + gl) * VV + i] = acc[i];
             __syncthreads();
@@ -369,15 +529,16 @@ __global__ __launch_bounds__(kSpmmThreads) void k_spmm_units(const SpmmLaunch a)
                 for (int gg = 0; gg < ngrp; ++gg)
 #pragma unroll
                     for (int i = 0; i < VV; ++i) sum[i] += red[(gg * G + gl) * VV + i];
-                store_pack<T, VV>(Y + j * a.ccol + col, sum);
+                store_pack<T, VV>(Y + j * ccol + col, sum);
             }
             __syncthreads();
         }
     }
 }
 
-// D1 = B C for all rows (unfused baseline): one 16-row block per wave at a time.
-template <typename T, int NB, bool FAST>
+// D1 = B C for all rows (unfused baseline): one 16-row block per wave at a time, the next
+// block's rows of B in flight while the current one is multiplied (KS > 0, as above).
+template <typename T, int NB, int KS, bool FAST>
 __global__ __launch_bounds__(kFusedThreads) void k_gemm(const GemmLaunch a) {
     const int slice = blockIdx.y;
     const int c0 = slice * a.cs;
@@ -390,17 +551,48 @@ __global__ __launch_bounds__(kFusedThreads) void k_gemm(const GemmLaunch a) {
     const int64_t nblk = (a.n + 15) >> 4;
     const T *__restrict__ B = static_cast<const T *>(a.B);
     T *__restrict__ D1 = static_cast<T *>(a.D1);
-    for (int64_t lb = (int64_t)blockIdx.x * nwaves + wave; lb < nblk; lb += (int64_t)gridDim.x * nwaves) {
+    // contiguous range of row blocks per workgroup, waves interleaved inside it
+    const int64_t per_wg = (nblk + gridDim.x - 1) / gridDim.x;
+    const int64_t lb0 = (int64_t)blockIdx.x * per_wg;
+    const int64_t lb1 = lb0 + per_wg < nblk ? lb0 + per_wg : nblk;
+    auto write_block = [&](int64_t lb, typename Tr<T>::Acc(&acc)[NB]) {
         const int64_t row = lb * 16 + r;
-        const bool valid = row < a.n;
-        typename Tr<T>::Acc acc[NB];
-        mfma_row_block<T, NB, FAST>(acc, Cl, B + (valid ? row : 0) * a.bcol, valid, a.bcol, lane);
-        if (valid) {
+        if (row < a.n) {
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
                 const int col = 16 * nb + 4 * g;
                 store_acc4<T, FAST>(D1 + row * a.ccol + c0 + col, acc[nb], col, w);
             }
+        }
+    };
+    if constexpr (KS > 0) {
+        constexpr int KSF = KS;
+        BFrag<T, KSF> cur, nxt;
+        int64_t lb = lb0 + wave;
+        {
+            const int64_t row = lb * 16 + r;
+            const bool valid = lb < lb1 && row < a.n;
+            load_b_frag<T, KSF>(cur, B + (valid ? row : 0) * a.bcol, valid, g);
+        }
+        for (; lb < lb1; lb += nwaves) {
+            // The C slice is loop invariant; keeping all of it in registers only pays while it
+            // is small, so for larger slices the LDS reads are pinned inside the loop.
+            if constexpr (KSF * Tr<T>::V * NB * (sizeof(T) / 4) > 64) asm volatile("" ::: "memory");
+            const int64_t nrow = (lb + nwaves) * 16 + r;
+            const bool nvalid = lb + nwaves < lb1 && nrow < a.n;
+            load_b_frag<T, KSF>(nxt, B + (nvalid ? nrow : 0) * a.bcol, nvalid, g);
+            typename Tr<T>::Acc acc[NB];
+            mfma_frag<T, NB, KSF>(acc, Cl, cur, lane);
+            write_block(lb, acc);
+            cur = nxt;
+        }
+    } else {
+        for (int64_t lb = lb0 + wave; lb < lb1; lb += nwaves) {
+            const int64_t row = lb * 16 + r;
+            const bool valid = row < a.n;
+            typename Tr<T>::Acc acc[NB];
+            mfma_row_block<T, NB, FAST>(acc, Cl, B + (valid ? row : 0) * a.bcol, valid, a.bcol, lane);
+            write_block(lb, acc);
         }
     }
 }
@@ -412,15 +604,16 @@ template <typename K> int raise_lds_limit(K kernel, int64_t bytes) {
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
 }
 
-template <typename T, int NB, bool FAST> int run_fused_gemm(const FusedLaunch &a, hipStream_t st) {
+template <typename T, int NB, int KS, bool FAST>
+int run_fused_gemm(const FusedLaunch &a, hipStream_t st) {
     static int64_t raised = -1;
     if (a.lds_bytes > raised) {
-        int e = raise_lds_limit(k_fused_gemm_spmm<T, NB, FAST>, a.lds_bytes);
+        int e = raise_lds_limit(k_fused_gemm_spmm<T, NB, KS, FAST>, a.lds_bytes);
         if (e) return e;
         raised = a.lds_bytes;
     }
-    int64_t grid = a.n_slices == 1 ? a.n_tiles : (int64_t)((a.n_tiles + 7) / 8) * 8 * a.n_slices;
-    k_fused_gemm_spmm<T, NB, FAST><<<dim3((unsigned)grid), dim3(kFusedThreads), a.lds_bytes, st>>>(a);
+    const int64_t grid = (int64_t)((a.n_tiles + 7) / 8) * 8 * a.n_slices;
+    k_fused_gemm_spmm<T, NB, KS, FAST><<<dim3((unsigned)grid), dim3(kFusedThreads), a.lds_bytes, st>>>(a);
     return (int)hipGetLastError();
 }
 
@@ -431,16 +624,16 @@ template <typename T, bool FAST> int run_fused_spmm(const FusedLaunch &a, hipStr
         if (e) return e;
         raised = a.lds_bytes;
     }
-    int64_t grid = a.n_slices == 1 ? a.n_tiles : (int64_t)((a.n_tiles + 7) / 8) * 8 * a.n_slices;
+    const int64_t grid = (int64_t)((a.n_tiles + 7) / 8) * 8 * a.n_slices;
     k_fused_spmm_spmm<T, FAST><<<dim3((unsigned)grid), dim3(kFusedThreads), a.lds_bytes, st>>>(a);
     return (int)hipGetLastError();
 }
 
-template <typename T, int NB, bool FAST> int run_gemm(const GemmLaunch &a, hipStream_t st) {
+template <typename T, int NB, int KS, bool FAST> int run_gemm(const GemmLaunch &a, hipStream_t st) {
     const int64_t lds = lds_fixed_bytes(a.dtype, 0, a.bcol, a.cs);
     static int64_t raised = -1;
     if (lds > raised) {
-        int e = raise_lds_limit(k_gemm<T, NB, FAST>, lds);
+        int e = raise_lds_limit(k_gemm<T, NB, KS, FAST>, lds);
         if (e) return e;
         raised = lds;
     }
@@ -448,8 +641,32 @@ template <typename T, int NB, bool FAST> int run_gemm(const GemmLaunch &a, hipSt
     const int64_t nblk = (a.n + 15) / 16;
     int64_t gx = (nblk + nwaves - 1) / nwaves;
     gx = gx < 1 ? 1 : (gx > 1024 ? 1024 : gx);
-    k_gemm<T, NB, FAST><<<dim3((unsigned)gx, (unsigned)a.n_slices), dim3(kFusedThreads), lds, st>>>(a);
+    k_gemm<T, NB, KS, FAST><<<dim3((unsigned)gx, (unsigned)a.n_slices), dim3(kFusedThreads), lds, st>>>(a);
     return (int)hipGetLastError();
+}
+
+// Calls f(NB, KS) with compile-time constants: NB accumulator blocks for the slice width, and
+// KS = bCol / (4 V) when that is one of the specialised depths, else 0 (generic k loop).
+template <typename L> int dispatch_shape(int dtype, int cs, int bcol, bool fast, L &&f) {
+    const int kc = 4 * vec_elems(dtype);
+    int ks = (fast && bcol % kc == 0) ? bcol / kc : 0;
+    if (ks != 2 && ks != 4 && ks != 8 && ks != 16) ks = 0;
+#define TF_KS(NBV)                                                                        \
+    switch (ks) {                                                                         \
+        case 2: return f(std::integral_constant<int, NBV>(), std::integral_constant<int, 2>());   \
+        case 4: return f(std::integral_constant<int, NBV>(), std::integral_constant<int, 4>());   \
+        case 8: return f(std::integral_constant<int, NBV>(), std::integral_constant<int, 8>());   \
+        case 16: return f(std::integral_constant<int, NBV>(), std::integral_constant<int, 16>()); \
+        default: return f(std::integral_constant<int, NBV>(), std::integral_constant<int, 0>());  \
+    }
+    switch (mfma_blocks(cs)) {
+        case 1: TF_KS(1)
+        case 2: TF_KS(2)
+        case 4: TF_KS(4)
+        case 8: TF_KS(8)
+    }
+#undef TF_KS
+    return (int)hipErrorInvalidValue;
 }
 
 template <typename L> int dispatch_nb(int cs, L &&f) {
@@ -477,16 +694,18 @@ int launch_fused_gemm_spmm(const FusedLaunch &a, void *stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (a.n_tiles == 0) return 0;
     const bool fast = gemm_fast(a.dtype, a.bcol, a.ccol, a.cs);
-#define TF_GO(T, FAST)                                                                   \
-    return dispatch_nb(a.cs, [&](auto nb) {                                     \
-        return run_fused_gemm<T, decltype(nb)::value, FAST>(a, st);                      \
-    })
-    if (a.dtype == TF_F32) {
-        if (fast) TF_GO(float, true); else TF_GO(float, false);
-    } else {
-        if (fast) TF_GO(double, true); else TF_GO(double, false);
+    if (!fast) {
+        return dispatch_nb(a.cs, [&](auto nb) {
+            constexpr int NB = decltype(nb)::value;
+            return a.dtype == TF_F32 ? run_fused_gemm<float, NB, 0, false>(a, st)
+                                     : run_fused_gemm<double, NB, 0, false>(a, st);
+        });
     }
-#undef TF_GO
+    return dispatch_shape(a.dtype, a.cs, a.bcol, fast, [&](auto nb, auto ks) {
+        constexpr int NB = decltype(nb)::value, KS = decltype(ks)::value;
+        return a.dtype == TF_F32 ? run_fused_gemm<float, NB, KS, true>(a, st)
+                                 : run_fused_gemm<double, NB, KS, true>(a, st);
+    });
 }
 
 int launch_fused_spmm_spmm(const FusedLaunch &a, void *stream) {
@@ -502,7 +721,7 @@ int launch_spmm_units(const SpmmLaunch &a, void *stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (a.n_units == 0) return 0;
     const bool fast = spmm_fast(a.dtype, a.ccol, a.ccol);
-    const dim3 grid((unsigned)a.n_units), block(kSpmmThreads);
+    const dim3 grid((unsigned)((a.n_units + 7) / 8 * 8)), block(kSpmmThreads);
     if (a.dtype == TF_F32) {
         if (fast) k_spmm_units<float, true><<<grid, block, 0, st>>>(a);
         else k_spmm_units<float, false><<<grid, block, 0, st>>>(a);
@@ -517,16 +736,18 @@ int launch_gemm(const GemmLaunch &a, void *stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (a.n == 0) return 0;
     const bool fast = gemm_fast(a.dtype, a.bcol, a.ccol, a.cs);
-#define TF_GO(T, FAST)                                                                   \
-    return dispatch_nb(a.cs, [&](auto nb) {                                     \
-        return run_gemm<T, decltype(nb)::value, FAST>(a, st);                            \
-    })
-    if (a.dtype == TF_F32) {
-        if (fast) TF_GO(float, true); else TF_GO(float, false);
-    } else {
-        if (fast) TF_GO(double, true); else TF_GO(double, false);
+    if (!fast) {
+        return dispatch_nb(a.cs, [&](auto nb) {
+            constexpr int NB = decltype(nb)::value;
+            return a.dtype == TF_F32 ? run_gemm<float, NB, 0, false>(a, st)
+                                     : run_gemm<double, NB, 0, false>(a, st);
+        });
     }
-#undef TF_GO
+    return dispatch_shape(a.dtype, a.cs, a.bcol, fast, [&](auto nb, auto ks) {
+        constexpr int NB = decltype(nb)::value, KS = decltype(ks)::value;
+        return a.dtype == TF_F32 ? run_gemm<float, NB, KS, true>(a, st)
+                                 : run_gemm<double, NB, KS, true>(a, st);
+    });
 }
 
 }  // namespace tf

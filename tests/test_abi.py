@@ -20,7 +20,7 @@ def test_header_symbols_are_exported():
     names = declared_symbols()
     assert {"tf_plan_create", "tf_plan_destroy", "tf_plan_schedule", "tf_gemm_spmm",
             "tf_spmm_spmm", "tf_unfused_gemm_spmm", "tf_unfused_spmm_spmm",
-            "tf_last_error"} <= set(names)
+            "tf_run_wavefront", "tf_last_error"} <= set(names)
     for name in names:
         assert hasattr(lib, name), name
     assert sorted(binding.EXPORTS) == names
