@@ -51,9 +51,21 @@ struct tf_plan {
     bool schedule_only = false;
     tf::Schedule s;
     double plan_seconds = 0.0;
-    DevBuf a_rowptr, a_colidx, a_vals, lcol;
-    DevBuf tile_first_ptr, first_rows_enc, tile_second_ptr, second_rows;
-    DevBuf wf1_unit_ptr, wf1_rows, all_unit_ptr, all_rows;
+    struct PackBufs {
+        DevBuf units, rows, idx, vals;
+        int64_t n_units = 0;
+        bool sorted = false;
+        tf::PackDev dev() const {
+            tf::PackDev d;
+            d.units = static_cast<const tf::UnitDesc *>(units.p);
+            d.rows = static_cast<const int32_t *>(rows.p);
+            d.idx = idx.p;
+            d.vals = vals.p;
+            return d;
+        }
+    };
+    DevBuf tile_first_ptr, first_rows_enc, tile_unit_ptr;
+    PackBufs fused, wf1, all;
     DevBuf d1;
 };
 
@@ -75,6 +87,20 @@ template <typename V> hipError_t up(DevBuf &b, const std::vector<V> &v) {
     return b.upload(v.data(), v.size() * sizeof(V));
 }
 
+hipError_t upload_pack(tf_plan::PackBufs &b, tf::RowPack &pk) {
+    hipError_t e = up(b.units, pk.units);
+    if (e == hipSuccess) e = up(b.rows, pk.rows);
+    if (e == hipSuccess) e = pk.idx16.empty() ? up(b.idx, pk.idx32) : up(b.idx, pk.idx16);
+    if (e == hipSuccess) e = up(b.vals, pk.vals);
+    b.n_units = (int64_t)pk.units.size();
+    b.sorted = pk.sorted;
+    // the packed entries live on the device from here on; the row lists stay for the schedule view
+    std::vector<int32_t>().swap(pk.idx32);
+    std::vector<uint16_t>().swap(pk.idx16);
+    std::vector<unsigned char>().swap(pk.vals);
+    return e;
+}
+
 tf::FusedLaunch fused_args(const tf_plan *p, const void *C, void *D) {
     tf::FusedLaunch a{};
     a.dtype = p->dtype;
@@ -88,41 +114,32 @@ tf::FusedLaunch fused_args(const tf_plan *p, const void *C, void *D) {
                   tf::round_up(p->s.max_tile_rows, p->s.lds_row_granule) * p->s.lds_bytes_per_row;
     a.tile_first_ptr = static_cast<const int32_t *>(p->tile_first_ptr.p);
     a.first_rows_enc = static_cast<const int32_t *>(p->first_rows_enc.p);
-    a.tile_second_ptr = static_cast<const int32_t *>(p->tile_second_ptr.p);
-    a.second_rows = static_cast<const int32_t *>(p->second_rows.p);
-    a.a_rowptr = static_cast<const int32_t *>(p->a_rowptr.p);
-    a.lcol = static_cast<const uint16_t *>(p->lcol.p);
-    a.a_vals = p->a_vals.p;
+    a.tile_unit_ptr = static_cast<const int32_t *>(p->tile_unit_ptr.p);
+    a.second = p->fused.dev();
     a.C = C;
     a.D = D;
     a.D1 = p->d1.p;
     return a;
 }
 
-tf::SpmmLaunch second_wavefront_args(const tf_plan *p, void *D) {
-    tf::SpmmLaunch w{};
+tf::PackedSpmmLaunch packed_args(const tf_plan *p, const tf_plan::PackBufs &b, void *D) {
+    tf::PackedSpmmLaunch w{};
     w.dtype = p->dtype;
-    w.n_units = (int64_t)p->s.wf1_unit_ptr.size() - 1;
-    w.unit_ptr = static_cast<const int32_t *>(p->wf1_unit_ptr.p);
-    w.rows = static_cast<const int32_t *>(p->wf1_rows.p);
-    w.n_rows = p->n;
-    w.uniform_rows = 0;
-    w.S.rowptr = static_cast<const int32_t *>(p->a_rowptr.p);
-    w.S.colidx = static_cast<const int32_t *>(p->a_colidx.p);
-    w.S.vals = p->a_vals.p;
+    w.n_units = b.n_units;
+    w.contiguous = b.sorted ? 0 : 1;
+    w.wide = (double)p->n * (double)p->ccol * tf::elem_size(p->dtype) >= 4294967296.0 ? 1 : 0;
+    w.pack = b.dev();
     w.X = p->d1.p;
     w.Y = D;
     w.ccol = (int32_t)p->ccol;
     return w;
 }
 
-tf::SpmmLaunch all_rows_args(const tf_plan *p, void *D) {
-    tf::SpmmLaunch w = second_wavefront_args(p, D);
-    w.n_units = (int64_t)p->s.all_unit_ptr.size() - 1;
-    w.unit_ptr = static_cast<const int32_t *>(p->all_unit_ptr.p);
-    w.rows = static_cast<const int32_t *>(p->all_rows.p);
-    return w;
+tf::PackedSpmmLaunch second_wavefront_args(const tf_plan *p, void *D) {
+    return packed_args(p, p->wf1, D);
 }
+
+tf::PackedSpmmLaunch all_rows_args(const tf_plan *p, void *D) { return packed_args(p, p->all, D); }
 
 tf_status check_exec(const tf_plan *p, int want_sparse, const void *C, const void *D) {
     if (!p || !C || !D) return fail(TF_EINVAL, "null argument");
@@ -227,6 +244,7 @@ tf_status tf_plan_create(const tf_csr *A, int64_t bCol, int64_t cCol, int32_t b_
         in.nnz = nnz;
         in.rowptr = rowptr;
         in.colidx = colidx;
+        in.vals = vals;
         in.bcol = bCol;
         in.ccol = cCol;
         in.b_is_sparse = p->b_is_sparse;
@@ -259,18 +277,12 @@ tf_status tf_plan_create(const tf_csr *A, int64_t bCol, int64_t cCol, int32_t b_
         auto ok = [&](hipError_t r) {
             if (e == hipSuccess) e = r;
         };
-        ok(p->a_rowptr.upload(rowptr, (size_t)(n + 1) * 4));
-        ok(p->a_colidx.upload(colidx, (size_t)nnz * 4));
-        ok(p->a_vals.upload(vals, (size_t)nnz * es));
-        ok(up(p->lcol, p->s.lcol));
         ok(up(p->tile_first_ptr, p->s.tile_first_ptr));
         ok(up(p->first_rows_enc, enc));
-        ok(up(p->tile_second_ptr, p->s.tile_second_ptr));
-        ok(up(p->second_rows, p->s.second_rows));
-        ok(up(p->wf1_unit_ptr, p->s.wf1_unit_ptr));
-        ok(up(p->wf1_rows, p->s.wf1_rows));
-        ok(up(p->all_unit_ptr, p->s.all_unit_ptr));
-        ok(up(p->all_rows, p->s.all_rows));
+        ok(up(p->tile_unit_ptr, p->s.tile_unit_ptr));
+        ok(upload_pack(p->fused, p->s.fused));
+        ok(upload_pack(p->wf1, p->s.wf1));
+        ok(upload_pack(p->all, p->s.all));
         ok(p->d1.alloc((size_t)n * cCol * es));
         if (e != hipSuccess) return hip_fail(e, "allocating the plan's device memory");
         guard.p = nullptr;
@@ -346,7 +358,7 @@ tf_status tf_gemm_spmm(const tf_plan *p, const void *B, const void *C, void *D, 
     a.B = B;
     int e = tf::launch_fused_gemm_spmm(a, stream);
     if (e) return hip_fail((hipError_t)e, "launching the first wavefront");
-    e = tf::launch_spmm_units(second_wavefront_args(p, D), stream);
+    e = tf::launch_packed_spmm(second_wavefront_args(p, D), stream);
     if (e) return hip_fail((hipError_t)e, "launching the second wavefront");
     return TF_OK;
 }
@@ -362,7 +374,7 @@ tf_status tf_spmm_spmm(const tf_plan *p, const tf_csr *B, const void *C, void *D
     a.Bs.vals = B->vals;
     int e = tf::launch_fused_spmm_spmm(a, stream);
     if (e) return hip_fail((hipError_t)e, "launching the first wavefront");
-    e = tf::launch_spmm_units(second_wavefront_args(p, D), stream);
+    e = tf::launch_packed_spmm(second_wavefront_args(p, D), stream);
     if (e) return hip_fail((hipError_t)e, "launching the second wavefront");
     return TF_OK;
 }
@@ -373,7 +385,7 @@ tf_status tf_run_wavefront(const tf_plan *p, int32_t wavefront, const void *B_de
     tf_status st = check_exec(p, p->b_is_sparse, C, D);
     if (st != TF_OK) return st;
     if (wavefront == 1) {
-        int e = tf::launch_spmm_units(second_wavefront_args(p, D), stream);
+        int e = tf::launch_packed_spmm(second_wavefront_args(p, D), stream);
         if (e) return hip_fail((hipError_t)e, "launching the second wavefront");
         return TF_OK;
     }
@@ -414,7 +426,7 @@ tf_status tf_unfused_gemm_spmm(const tf_plan *p, const void *B, const void *C, v
     g.D1 = p->d1.p;
     int e = tf::launch_gemm(g, stream);
     if (e) return hip_fail((hipError_t)e, "launching the GeMM");
-    e = tf::launch_spmm_units(all_rows_args(p, D), stream);
+    e = tf::launch_packed_spmm(all_rows_args(p, D), stream);
     if (e) return hip_fail((hipError_t)e, "launching the SpMM");
     return TF_OK;
 }
@@ -425,20 +437,19 @@ tf_status tf_unfused_spmm_spmm(const tf_plan *p, const tf_csr *B, const void *C,
     if (st != TF_OK) return st;
     st = check_sparse_b(p, B);
     if (st != TF_OK) return st;
-    tf::SpmmLaunch f{};
+    tf::CsrSpmmLaunch f{};
     f.dtype = p->dtype;
-    f.uniform_rows = 64;
+    f.rows_per_wg = 64;
     f.n_rows = p->n;
-    f.n_units = (p->n + f.uniform_rows - 1) / f.uniform_rows;
     f.S.rowptr = B->rowptr;
     f.S.colidx = B->colidx;
     f.S.vals = B->vals;
     f.X = C;
     f.Y = p->d1.p;
     f.ccol = (int32_t)p->ccol;
-    int e = tf::launch_spmm_units(f, stream);
+    int e = tf::launch_csr_spmm(f, stream);
     if (e) return hip_fail((hipError_t)e, "launching the first SpMM");
-    e = tf::launch_spmm_units(all_rows_args(p, D), stream);
+    e = tf::launch_packed_spmm(all_rows_args(p, D), stream);
     if (e) return hip_fail((hipError_t)e, "launching the second SpMM");
     return TF_OK;
 }

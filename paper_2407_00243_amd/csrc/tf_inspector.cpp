@@ -11,6 +11,7 @@
 // Pure host code: no HIP calls.
 #include <algorithm>
 #include <chrono>
+#include <cstring>
 #include <numeric>
 
 #include "tf_internal.h"
@@ -41,36 +42,99 @@ void split_tile(const Schedule &s, Range r, bool allow_split, std::vector<Range>
 
 }  // namespace
 
-void balance_units(const int32_t *rowptr, const std::vector<int32_t> &rows, bool long_first,
-                   std::vector<int32_t> &rows_out, std::vector<int32_t> &unit_ptr) {
-    rows_out.clear();
-    unit_ptr.clear();
-    unit_ptr.push_back(0);
-    std::vector<int32_t> longs;
-    if (long_first) {
-        for (int32_t j : rows)
-            if (rowptr[j + 1] - rowptr[j] >= kLongRowNnz) longs.push_back(j);
-        std::stable_sort(longs.begin(), longs.end(), [&](int32_t a, int32_t b) {
-            return rowptr[a + 1] - rowptr[a] > rowptr[b + 1] - rowptr[b];
-        });
-        for (int32_t j : longs) {
-            rows_out.push_back(j);
-            unit_ptr.push_back((int32_t)rows_out.size());
-        }
-    }
-    int64_t work = 0;
-    for (int32_t j : rows) {
-        const int64_t len = rowptr[j + 1] - rowptr[j];
-        if (long_first && len >= kLongRowNnz) continue;
-        rows_out.push_back(j);
-        work += len + 8;
-        if (work >= kUnitWork) {
-            unit_ptr.push_back((int32_t)rows_out.size());
-            work = 0;
-        }
-    }
-    if (unit_ptr.back() != (int32_t)rows_out.size()) unit_ptr.push_back((int32_t)rows_out.size());
+namespace {
+
+struct PackRules {
+    int max_rows;        // most rows per unit
+    int64_t max_slots;   // most padded entries per unit
+    int split_groups;    // lane groups available for splitting long rows; 0 = never split
+};
+
+int pow2_at_least(int64_t x) {
+    int g = 1;
+    while (g < x) g *= 2;
+    return g;
 }
+
+// Re-packs the rows `list` of the CSR matrix into units of uniform padded length and appends
+// them to `out` (see RowPack).  local(c) maps a column index to what the kernel should index
+// its operand with.
+template <typename IdxVec, typename LocalFn>
+void pack_rows(const int32_t *rowptr, const int32_t *colidx, const unsigned char *vals, int es,
+               std::vector<int32_t> list, const PackRules &rules, bool may_sort, LocalFn local,
+               IdxVec &idx_out, RowPack &out) {
+    auto len = [&](int32_t j) { return (int64_t)rowptr[j + 1] - rowptr[j]; };
+    const int64_t count = (int64_t)list.size();
+    // empty rows last, so that no unit mixes them with rows that need padding entries
+    std::stable_partition(list.begin(), list.end(), [&](int32_t j) { return len(j) > 0; });
+    if (may_sort && count > 0) {
+        // padded size in the given order; re-order by length when padding would cost over 15 %
+        int64_t real = 0, padded = 0;
+        for (int64_t p0 = 0; p0 < count; p0 += rules.max_rows) {
+            const int64_t p1 = std::min(count, p0 + rules.max_rows);
+            int64_t mx = 0;
+            for (int64_t q = p0; q < p1; ++q) {
+                mx = std::max(mx, len(list[q]));
+                real += len(list[q]);
+            }
+            padded += mx * (p1 - p0);
+        }
+        if (padded > real + real * 15 / 100) {
+            std::stable_sort(list.begin(), list.end(),
+                             [&](int32_t a, int32_t b) { return len(a) > len(b); });
+            out.sorted = true;
+        }
+    }
+    const int64_t list_base = (int64_t)out.rows.size();
+    out.rows.insert(out.rows.end(), list.begin(), list.end());
+    int64_t pos = 0;
+    while (pos < count) {
+        UnitDesc u{};
+        u.row_begin = (int32_t)(list_base + pos);
+        u.entry_base = (int64_t)idx_out.size();
+        const int64_t len0 = len(list[pos]);
+        int64_t L = len0;
+        int64_t take = 1;
+        if (rules.split_groups > 1 && len0 >= kSplitMinSlots) {
+            int split = pow2_at_least((len0 + kSplitPartSlots - 1) / kSplitPartSlots);
+            split = std::min(split, rules.split_groups);
+            const int cap = rules.split_groups / split;
+            while (take < cap && pos + take < count && len(list[pos + take]) >= kSplitMinSlots) {
+                L = std::max(L, len(list[pos + take]));
+                ++take;
+            }
+            u.split = split;
+        } else {
+            u.split = 1;
+            while (take < rules.max_rows && pos + take < count) {
+                const int64_t ln = len(list[pos + take]);
+                if ((ln == 0) != (len0 == 0)) break;
+                if (rules.split_groups > 1 && ln >= kSplitMinSlots) break;
+                const int64_t nl = std::max(L, ln);
+                if (nl * (take + 1) > rules.max_slots) break;
+                L = nl;
+                ++take;
+            }
+        }
+        u.n_rows = (int32_t)take;
+        u.slots = (int32_t)L;
+        for (int64_t q = pos; q < pos + take; ++q) {
+            const int32_t j = list[q];
+            const int64_t k0 = rowptr[j], ln = len(j);
+            for (int64_t s = 0; s < L; ++s) {
+                const int64_t k = k0 + (s < ln ? s : ln - 1);      // padding repeats the last entry
+                idx_out.push_back((typename IdxVec::value_type)local(colidx[k]));
+                const size_t at = out.vals.size();
+                out.vals.resize(at + es, 0);
+                if (s < ln) std::memcpy(&out.vals[at], vals + (size_t)k * es, es);
+            }
+        }
+        out.units.push_back(u);
+        pos += take;
+    }
+}
+
+}  // namespace
 
 tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err) {
     const int64_t n = in.n;
@@ -145,15 +209,16 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
     s.tile_first_ptr.resize(nt + 1);
     s.tile_second_ptr.resize(nt + 1);
     s.first_rows.resize(n);
-    s.second_rows.reserve(n);
-    s.lcol.assign((size_t)in.nnz, 0);
+    s.tile_unit_ptr.assign(1, 0);
     s.spill.assign((size_t)n, 0);
+    const unsigned char *vals = static_cast<const unsigned char *>(in.vals);
+    const PackRules tile_rules{kTileUnitRows, (int64_t)kTileUnitRows * 64, 0};
     std::vector<int32_t> wf1;
     std::vector<int32_t> seen((size_t)n, -1);      // Eq. 2: distinct columns per tile
     for (int64_t vt = 0; vt < nt; ++vt) {
         const Range r = tiles[vt];
         s.tile_first_ptr[vt] = (int32_t)r.i0;
-        s.tile_second_ptr[vt] = (int32_t)s.second_rows.size();
+        std::vector<int32_t> tile_rows;
         int64_t tile_nnz = 0, uc = 0;
         for (int64_t j = r.i0; j < r.i1; ++j) {
             s.first_rows[j] = (int32_t)j;
@@ -166,10 +231,9 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
                 }
             }
             if (inside) {
-                s.second_rows.push_back((int32_t)j);
+                tile_rows.push_back((int32_t)j);
                 for (int64_t q = in.rowptr[j]; q < in.rowptr[j + 1]; ++q) {
                     const int32_t c = in.colidx[q];
-                    s.lcol[q] = (uint16_t)(c - r.i0);
                     if (seen[c] != (int32_t)vt) {
                         seen[c] = (int32_t)vt;
                         ++uc;
@@ -181,7 +245,14 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
             }
         }
         const int64_t rows = r.i1 - r.i0;
-        const int64_t nj = (int64_t)s.second_rows.size() - s.tile_second_ptr[vt];
+        const int64_t nj = (int64_t)tile_rows.size();
+        s.tile_second_ptr[vt] = (int32_t)s.fused.rows.size();
+        {   // second phase of this tile: its fused rows, packed with tile-local column indices
+            const int64_t i0 = r.i0;
+            pack_rows(in.rowptr, in.colidx, vals, es, tile_rows, tile_rules, true,
+                      [i0](int32_t c) { return c - i0; }, s.fused.idx16, s.fused);
+            s.tile_unit_ptr.push_back((int32_t)s.fused.units.size());
+        }
         // Eq. 2 (diagnostic): (nz + uc + t + |J|) * cCol + idx, counted in elements; for a dense B
         // the tile's rows x bCol block of B is added to nz, a sparse B is unknown here.
         const double nz = (double)tile_nnz + (in.b_is_sparse ? 0.0 : (double)rows * in.bcol);
@@ -190,7 +261,8 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
         s.fused_nnz += tile_nnz;
     }
     s.tile_first_ptr[nt] = (int32_t)n;
-    s.tile_second_ptr[nt] = (int32_t)s.second_rows.size();
+    s.tile_second_ptr[nt] = (int32_t)s.fused.rows.size();
+    s.second_rows = s.fused.rows;
     s.n_fused_rows = (int64_t)s.second_rows.size();
 
     // ---- spill set ----------------------------------------------------------------------
@@ -199,10 +271,17 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
     s.n_spill_rows = std::accumulate(s.spill.begin(), s.spill.end(), (int64_t)0);
 
     // ---- balance: units of the second wavefront, and of the unfused baseline ------------
-    balance_units(in.rowptr, wf1, true, s.wf1_rows, s.wf1_unit_ptr);
+    const int vv = in.ccol % v == 0 ? v : 1;
+    PackRules wf1_rules{kUnitRows, kUnitSlots, kSpmmThreads / lane_group((int)in.ccol, vv)};
+    auto ident = [](int32_t c) { return c; };
+    pack_rows(in.rowptr, in.colidx, vals, es, wf1, wf1_rules, true, ident, s.wf1.idx32, s.wf1);
+    s.wf1_rows = s.wf1.rows;
+    s.wf1_unit_ptr.clear();
+    for (const UnitDesc &u : s.wf1.units) s.wf1_unit_ptr.push_back(u.row_begin);
+    s.wf1_unit_ptr.push_back((int32_t)s.wf1_rows.size());
     std::vector<int32_t> all((size_t)n);
     std::iota(all.begin(), all.end(), 0);
-    balance_units(in.rowptr, all, true, s.all_rows, s.all_unit_ptr);
+    pack_rows(in.rowptr, in.colidx, vals, es, all, wf1_rules, true, ident, s.all.idx32, s.all);
     return TF_OK;
 }
 

@@ -13,9 +13,21 @@ constexpr int kMaxMfmaSliceCols = 128;   // one wave holds at most 8 accumulator
 constexpr int kRowGranuleDense = 16;     // dense-B tiles are produced in blocks of 16 rows (MFMA M/N)
 constexpr int kFusedThreads = 512;       // workgroup size of the fused kernels
 constexpr int kSpmmThreads = 256;        // workgroup size of the row-list SpMM kernel
-constexpr int kLongRowNnz = 2048;        // a second-wavefront row this long gets a workgroup of its own
-constexpr int kUnitWork = 1024;          // target work (nnz + 8 per row) of one second-wavefront unit
+constexpr int kUnitRows = 64;            // most rows in one unit of a packed row list
+constexpr int kUnitSlots = 4096;         // most padded entries (rows x slots) in one such unit
+constexpr int kSplitMinSlots = 128;      // rows at least this long are split over several lane groups
+constexpr int kSplitPartSlots = 96;      // target slots per part of a split row
+constexpr int kTileUnitRows = 128;       // most rows in one unit of a fused tile's second phase
 constexpr uint32_t kSpillBit = 0x80000000u;
+
+// Lanes that share one row in the gather kernels: each lane owns vv columns (vv = elements per
+// 16 bytes when rows are 16-byte aligned, else 1); the group is the smallest power of two of
+// lanes that covers `cols` columns, at most one wave.
+inline int lane_group(int cols, int vv) {
+    int g = 1;
+    while (g * vv < cols && g < 64) g *= 2;
+    return g;
+}
 
 inline int elem_size(int dtype) { return dtype == TF_F64 ? 8 : 4; }
 inline int vec_elems(int dtype) { return dtype == TF_F64 ? 2 : 4; }   // elements per 16 bytes
@@ -46,6 +58,30 @@ inline int64_t lds_fixed_bytes(int dtype, int b_is_sparse, int bcol, int cs) {
 }
 inline int lds_row_granule(int b_is_sparse) { return b_is_sparse ? 1 : kRowGranuleDense; }
 
+// One unit of a packed row list: n_rows rows, all padded to `slots` entries, stored row after
+// row from entry_base on.  split > 1: every row is shared by `split` lane groups, each summing
+// a contiguous part of the slots.
+struct UnitDesc {
+    int64_t entry_base;
+    int32_t row_begin;    // position of the unit's first row in the list
+    int32_t n_rows;
+    int32_t slots;
+    int32_t split;
+};
+
+// A list of rows of A re-packed for the gather kernels: per unit a uniform padded row length,
+// so the kernels need no row pointers and no per-row bounds.  Padding repeats the row's last
+// column index with value 0.
+struct RowPack {
+    std::vector<UnitDesc> units;
+    std::vector<int32_t> rows;           // row ids, list order
+    std::vector<int32_t> idx32;          // global column indices (second wavefront), or
+    std::vector<uint16_t> idx16;         // tile-local indices (fused tiles)
+    std::vector<unsigned char> vals;     // packed values, element size of the plan's dtype
+    bool sorted = false;                 // rows were re-ordered by length
+    int64_t entries() const { return (int64_t)(idx32.size() + idx16.size()); }
+};
+
 // Host-side schedule produced by the inspector.
 struct Schedule {
     int64_t n = 0, nnz = 0;
@@ -56,8 +92,10 @@ struct Schedule {
     std::vector<int32_t> tile_second_ptr, second_rows;
     std::vector<int32_t> wf1_unit_ptr, wf1_rows;
     std::vector<uint8_t> spill;
-    std::vector<uint16_t> lcol;    // per stored entry of A: tile-local index of its column (fused rows only)
-    std::vector<int32_t> all_unit_ptr, all_rows;          // balanced units over all rows (unfused baseline)
+    RowPack fused;                 // second_rows re-packed with tile-local column indices
+    std::vector<int32_t> tile_unit_ptr;                   // units of `fused` per tile
+    RowPack wf1;                   // wf1_rows re-packed
+    RowPack all;                   // all rows re-packed (unfused baseline)
     int64_t n_fused_rows = 0, n_spill_rows = 0, fused_nnz = 0;
     int64_t max_tile_rows = 0;
     int64_t lds_fixed_bytes = 0, lds_bytes_per_row = 0, fast_mem_bytes = 0;
@@ -68,6 +106,7 @@ struct Schedule {
 struct InspectorInput {
     int64_t n, nnz;
     const int32_t *rowptr, *colidx;   // host
+    const void *vals;                 // host, element size of dtype
     int64_t bcol, ccol;
     int32_t b_is_sparse;
     int32_t dtype;
@@ -80,9 +119,6 @@ struct InspectorInput {
 // Builds the schedule; returns TF_OK or an error with a message in `err`.
 tf_status build_schedule(const InspectorInput &in, Schedule &out, std::string &err);
 
-// Balanced partition of a row list into units of about equal work (host helper).
-void balance_units(const int32_t *rowptr, const std::vector<int32_t> &rows, bool long_first,
-                   std::vector<int32_t> &rows_out, std::vector<int32_t> &unit_ptr);
 
 // ---------------------------------------------------------------- device launch interface
 
@@ -92,16 +128,21 @@ struct CsrDev {
     const void *vals = nullptr;
 };
 
+struct PackDev {
+    const UnitDesc *units = nullptr;
+    const int32_t *rows = nullptr;
+    const void *idx = nullptr;        // int32 or uint16
+    const void *vals = nullptr;
+};
+
 struct FusedLaunch {
     int32_t dtype;
     int32_t n_tiles, n_slices, cs, ccol, bcol;
     int32_t max_tile_rows;            // largest tile, in rows
     int64_t lds_bytes;                // dynamic LDS of the launch
     const int32_t *tile_first_ptr, *first_rows_enc;   // first_rows with kSpillBit
-    const int32_t *tile_second_ptr, *second_rows;
-    const int32_t *a_rowptr;
-    const uint16_t *lcol;
-    const void *a_vals;
+    const int32_t *tile_unit_ptr;     // second phase: units of `second` per tile
+    PackDev second;                   // uint16 tile-local indices
     const void *B;                    // dense B (gemm) or nullptr
     CsrDev Bs;                        // sparse B (spmm)
     const void *C;
@@ -109,16 +150,26 @@ struct FusedLaunch {
     void *D1;
 };
 
-struct SpmmLaunch {
+// Y[row] = sum over the packed entries of the row of val * X[idx]; one unit per workgroup.
+struct PackedSpmmLaunch {
     int32_t dtype;
     int64_t n_units;
-    const int32_t *unit_ptr;          // nullptr: uniform units of `uniform_rows` consecutive rows
-    const int32_t *rows;              // nullptr: identity
-    int64_t n_rows;                   // used with uniform units
-    int32_t uniform_rows;
+    int32_t contiguous;               // 1: neighbouring units share an XCD; 0: round robin
+    int32_t wide;                     // 1: X spans 4 GiB or more (64-bit operand offsets)
+    PackDev pack;                     // int32 indices
+    const void *X;
+    void *Y;
+    int32_t ccol;
+};
+
+// Y[j] = S[j, :] X for a caller-supplied CSR matrix S, `rows_per_wg` consecutive rows per workgroup.
+struct CsrSpmmLaunch {
+    int32_t dtype;
+    int64_t n_rows;
+    int32_t rows_per_wg;
     CsrDev S;
-    const void *X;                    // [*, ccol]
-    void *Y;                          // [*, ccol]
+    const void *X;
+    void *Y;
     int32_t ccol;
 };
 
@@ -133,7 +184,8 @@ struct GemmLaunch {
 // Each returns hipError_t as int (0 = success).  `stream` is a hipStream_t.
 int launch_fused_gemm_spmm(const FusedLaunch &a, void *stream);
 int launch_fused_spmm_spmm(const FusedLaunch &a, void *stream);
-int launch_spmm_units(const SpmmLaunch &a, void *stream);
+int launch_packed_spmm(const PackedSpmmLaunch &a, void *stream);
+int launch_csr_spmm(const CsrSpmmLaunch &a, void *stream);
 int launch_gemm(const GemmLaunch &a, void *stream);
 int prepare_kernels(int64_t max_dynamic_lds);                 // raises the dynamic-LDS limit of the kernels
 

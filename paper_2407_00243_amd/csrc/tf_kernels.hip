@@ -301,6 +301,95 @@ __device__ __forceinline__ void gather_rows(int first, int count, int stride,
 constexpr int kRowsPerPass = 4;     // R: rows a lane group works on at once
 constexpr int kEntriesPerPass = 4;  // E: entries of each of those rows fetched per pass
 
+// ------------------------------------------------------------------------------------------
+// Packed row lists (see RowPack): every row of a unit has `slots` entries, so the gather loop has
+// a wave-uniform trip count and needs neither row pointers nor bounds on individual entries.
+//
+// X is addressed as  base + idx * ldx + lane offset.  For operands below 4 GiB (and for LDS)
+// the offset is formed in 32 bits, which lets the load use a scalar base plus a 32-bit lane
+// offset; WIDE selects 64-bit arithmetic for larger operands.
+template <typename T, int N, bool WIDE>
+__device__ __forceinline__ void load_x(T (&x)[N], const T *X, uint32_t c, uint32_t ldx,
+                                       uint32_t lane_off) {
+    if (WIDE) {
+        load_pack<T, N>(x, X + ((uint64_t)c * ldx + lane_off));
+    } else {
+        const uint32_t off = (c * ldx + lane_off) * (uint32_t)sizeof(T);
+        load_pack<T, N>(x, reinterpret_cast<const T *>(reinterpret_cast<const char *>(X) + off));
+    }
+}
+
+// One unit, rows not split: lane group `grp` of `ngrp` takes rows grp, grp + ngrp, ..., R at a
+// time, E slots of each per pass (R * E gathers in flight per lane).  out(row id, acc).
+template <typename T, int N, typename IdxT, int R, int E, bool WIDE, typename OutFn>
+__device__ __forceinline__ void unit_rows(const UnitDesc d, const int32_t *__restrict__ rows,
+                                          const IdxT *__restrict__ idx,
+                                          const T *__restrict__ val, const T *X, uint32_t ldx,
+                                          uint32_t lane_off, int grp, int ngrp, OutFn out) {
+    const int L = d.slots;
+    for (int i0 = grp; i0 < d.n_rows; i0 += ngrp * R) {
+        const IdxT *ip[R];
+        const T *vp[R];
+        int32_t rid[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int i = i0 + r * ngrp;
+            const int ic = i < d.n_rows ? i : i0;
+            const int64_t at = d.entry_base + (int64_t)ic * L;
+            ip[r] = idx + at;
+            vp[r] = val + at;
+            rid[r] = rows[d.row_begin + ic];
+        }
+        T acc[R][N];
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int i = 0; i < N; ++i) acc[r][i] = T(0);
+        int s = 0;
+        for (; s + E <= L; s += E) {
+            uint32_t c[R][E];
+            T v[R][E];
+            T x[R][E][N];
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int e = 0; e < E; ++e) {
+                    c[r][e] = (uint32_t)ip[r][s + e];
+                    v[r][e] = vp[r][s + e];
+                }
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int e = 0; e < E; ++e) load_x<T, N, WIDE>(x[r][e], X, c[r][e], ldx, lane_off);
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int e = 0; e < E; ++e)
+#pragma unroll
+                    for (int i = 0; i < N; ++i) acc[r][i] += v[r][e] * x[r][e][i];
+        }
+        for (; s < L; ++s) {
+            uint32_t c[R];
+            T v[R];
+            T x[R][N];
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                c[r] = (uint32_t)ip[r][s];
+                v[r] = vp[r][s];
+            }
+#pragma unroll
+            for (int r = 0; r < R; ++r) load_x<T, N, WIDE>(x[r], X, c[r], ldx, lane_off);
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int i = 0; i < N; ++i) acc[r][i] += v[r] * x[r][i];
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            if (i0 + r * ngrp < d.n_rows) out(rid[r], acc[r]);
+    }
+}
+
 // Second phase of a fused tile: rows of D whose D1 operands all sit in the LDS tile.
 template <typename T, bool FAST>
 __device__ __forceinline__ void fused_second_phase(const FusedLaunch &a, const T *tileD1, int ldl,
@@ -308,18 +397,21 @@ __device__ __forceinline__ void fused_second_phase(const FusedLaunch &a, const T
     constexpr int VV = FAST ? Tr<T>::V : 1;
     const int G = pow2_at_least((a.cs + VV - 1) / VV);
     const int gl = threadIdx.x % G, grp = threadIdx.x / G, ngrp = blockDim.x / G;
-    const int sp0 = a.tile_second_ptr[tile];
-    const int nj = a.tile_second_ptr[tile + 1] - sp0;
-    const T *__restrict__ avals = static_cast<const T *>(a.a_vals);
+    if (VV * gl >= w) return;
+    const UnitDesc *__restrict__ units = a.second.units;
+    const int32_t *__restrict__ rows = a.second.rows;
+    const uint16_t *__restrict__ idx = static_cast<const uint16_t *>(a.second.idx);
+    const T *__restrict__ val = static_cast<const T *>(a.second.vals);
     T *__restrict__ D = static_cast<T *>(a.D);
-    const int32_t *__restrict__ second = a.second_rows + sp0;
     const int ccol = a.ccol;
-    gather_rows<T, VV, uint16_t, kRowsPerPass, kEntriesPerPass>(
-        grp, nj, ngrp, a.a_rowptr, a.lcol, avals, tileD1 + VV * gl, ldl, VV * gl < w,
-        [&](int pos) { return second[pos]; },
-        [&](int, int64_t j, const T(&acc)[VV]) {
-            store_pack<T, VV>(D + j * ccol + c0 + VV * gl, acc);
-        });
+    const int u1 = a.tile_unit_ptr[tile + 1];
+    for (int u = a.tile_unit_ptr[tile]; u < u1; ++u) {
+        unit_rows<T, VV, uint16_t, kRowsPerPass, kEntriesPerPass, false>(
+            units[u], rows, idx, val, tileD1, (uint32_t)ldl, (uint32_t)(VV * gl), grp, ngrp,
+            [&](int32_t j, const T(&acc)[VV]) {
+                store_pack<T, VV>(D + (int64_t)j * ccol + c0 + VV * gl, acc);
+            });
+    }
 }
 
 extern __shared__ __align__(16) unsigned char tf_smem[];
@@ -329,19 +421,13 @@ template <typename T, int KS> struct BFrag {
     T v[KS][Tr<T>::V];
 };
 
+// Loads are unconditional (the caller passes a row that exists): a lane whose row is padding
+// computes garbage that is never stored, and each output row depends on its own lane only.
 template <typename T, int KS>
-__device__ __forceinline__ void load_b_frag(BFrag<T, KS> &f, const T *__restrict__ brow,
-                                            bool valid, int g) {
+__device__ __forceinline__ void load_b_frag(BFrag<T, KS> &f, const T *__restrict__ brow, int g) {
     constexpr int V = Tr<T>::V, KC = 4 * V;
 #pragma unroll
-    for (int s = 0; s < KS; ++s) {
-        if (valid) {
-            load_pack<T, V>(f.v[s], brow + KC * s + V * g);
-        } else {
-#pragma unroll
-            for (int q = 0; q < V; ++q) f.v[s][q] = T(0);
-        }
-    }
+    for (int s = 0; s < KS; ++s) load_pack<T, V>(f.v[s], brow + KC * s + V * g);
 }
 
 template <typename T, int NB, int KS>
@@ -385,15 +471,18 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
     const T *__restrict__ B = static_cast<const T *>(a.B);
     T *__restrict__ D1 = static_cast<T *>(a.D1);
     const int32_t *__restrict__ first = a.first_rows_enc + fp0;
-    auto enc_of = [&](int lb) -> uint32_t {      // row id and spill flag of this lane's row, 0 if none
+    // Row id and spill flag of this lane's row in block lb.  Padding lanes and blocks past the
+    // end name the tile's last row (so that every load below is unconditional) and are marked
+    // by `valid_of`.
+    auto enc_of = [&](int lb) -> uint32_t {
         const int lr = lb * 16 + r;
-        return (lb < nblk && lr < rows) ? ((uint32_t)first[lr] | 0u) : 0xffffffffu;
+        return (uint32_t)first[lr < rows ? lr : rows - 1];
     };
+    auto valid_of = [&](int lb) -> bool { return lb * 16 + r < rows; };
     auto write_block = [&](int lb, uint32_t enc, typename Tr<T>::Acc(&acc)[NB]) {
         const int lr = lb * 16 + r;
-        const bool valid = enc != 0xffffffffu;
         const int64_t row = enc & ~kSpillBit;
-        const bool spill = valid && (enc & kSpillBit);
+        const bool spill = valid_of(lb) && (enc & kSpillBit);
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
             const int col = 16 * nb + 4 * g;
@@ -405,12 +494,11 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
         constexpr int KSF = KS;
         BFrag<T, KSF> cur, nxt;
         uint32_t enc_cur = enc_of(wave), enc_nxt = enc_of(wave + nwaves);
-        load_b_frag<T, KSF>(cur, B + (int64_t)(enc_cur & ~kSpillBit) * a.bcol,
-                            enc_cur != 0xffffffffu, g);
+        load_b_frag<T, KSF>(cur, B + (int64_t)(enc_cur & ~kSpillBit) * a.bcol, g);
         for (int lb = wave; lb < nblk; lb += nwaves) {
             const uint32_t enc_nn = enc_of(lb + 2 * nwaves);
-            load_b_frag<T, KSF>(nxt, B + (int64_t)(enc_nxt & ~kSpillBit) * a.bcol,
-                                enc_nxt != 0xffffffffu, g);
+            load_b_frag<T, KSF>(nxt, B + (int64_t)(enc_nxt & ~kSpillBit) * a.bcol, g);
+            __builtin_amdgcn_sched_barrier(0);      // keep the prefetch ahead of the MFMAs
             typename Tr<T>::Acc acc[NB];
             mfma_frag<T, NB, KSF>(acc, Cl, cur, lane);
             write_block(lb, enc_cur, acc);
@@ -421,9 +509,8 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
     } else {
         for (int lb = wave; lb < nblk; lb += nwaves) {
             const uint32_t enc = enc_of(lb);
-            const bool valid = enc != 0xffffffffu;
             typename Tr<T>::Acc acc[NB];
-            mfma_row_block<T, NB, FAST>(acc, Cl, B + (int64_t)(enc & ~kSpillBit) * a.bcol, valid,
+            mfma_row_block<T, NB, FAST>(acc, Cl, B + (int64_t)(enc & ~kSpillBit) * a.bcol, true,
                                         a.bcol, lane);
             write_block(lb, enc, acc);
         }
@@ -463,76 +550,112 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_spmm_spmm(const FusedLa
     fused_second_phase<T, FAST>(a, tileD1, ldl, tile, c0, w);
 }
 
-// Row-list SpMM: Y[j][:] = sum_k S.vals[k] X[S.colidx[k]][:] for the rows of one unit per
-// workgroup.  A unit that consists of a single long row is shared by all lane groups of the
-// workgroup, whose partial sums are added in a fixed order through LDS.
-template <typename T, bool FAST>
-__global__ __launch_bounds__(kSpmmThreads) void k_spmm_units(const SpmmLaunch a) {
+// Packed-row SpMM: Y[row][:] = sum over the row's packed entries of val * X[idx][:], one unit per
+// workgroup (second wavefront, and the second operation of the unfused baseline).  Units whose
+// rows are split hand their partial sums through LDS and add them in a fixed order.
+template <typename T, bool FAST, bool WIDE>
+__global__ __launch_bounds__(kSpmmThreads) void k_packed_spmm(const PackedSpmmLaunch a) {
     constexpr int VV = FAST ? Tr<T>::V : 1;
     __shared__ T red[kSpmmThreads * VV];
-    const int64_t u = xcd_contiguous(blockIdx.x, a.n_units);
+    const int64_t u = a.contiguous ? xcd_contiguous(blockIdx.x, a.n_units) : (int64_t)blockIdx.x;
     if (u >= a.n_units) return;
-    int64_t r0, r1;
-    if (a.unit_ptr) {
-        r0 = a.unit_ptr[u];
-        r1 = a.unit_ptr[u + 1];
-    } else {
-        r0 = u * a.uniform_rows;
-        r1 = r0 + a.uniform_rows < a.n_rows ? r0 + a.uniform_rows : a.n_rows;
+    const UnitDesc d = a.pack.units[u];
+    const int ccol = a.ccol;
+    const int G = min(64, pow2_at_least((ccol + VV - 1) / VV));
+    const int gl = threadIdx.x % G, grp = threadIdx.x / G, ngrp = blockDim.x / G;
+    const int32_t *__restrict__ rows = a.pack.rows;
+    const int32_t *__restrict__ idx = static_cast<const int32_t *>(a.pack.idx);
+    const T *__restrict__ val = static_cast<const T *>(a.pack.vals);
+    const T *__restrict__ X = static_cast<const T *>(a.X);
+    T *__restrict__ Y = static_cast<T *>(a.Y);
+    for (int cb = 0; cb < ccol; cb += G * VV) {
+        const int col = cb + VV * gl;
+        const bool active = col < ccol;
+        const uint32_t lane_off = active ? (uint32_t)col : 0u;      // idle lanes read column 0
+        if (d.split <= 1) {
+            if (active) {
+                unit_rows<T, VV, int32_t, kRowsPerPass, kEntriesPerPass, WIDE>(
+                    d, rows, idx, val, X, (uint32_t)ccol, lane_off, grp, ngrp,
+                    [&](int32_t j, const T(&acc)[VV]) {
+                        store_pack<T, VV>(Y + (int64_t)j * ccol + col, acc);
+                    });
+            }
+        } else {
+            // group -> (row, part); `split` groups share a row, each takes a range of the slots
+            const int row_i = grp / d.split, part = grp % d.split;
+            const int chunk = (d.slots + d.split - 1) / d.split;
+            const int s0 = min(d.slots, part * chunk), s1 = min(d.slots, s0 + chunk);
+            T acc[VV];
+#pragma unroll
+            for (int i = 0; i < VV; ++i) acc[i] = T(0);
+            if (row_i < d.n_rows) {
+                const int64_t at = d.entry_base + (int64_t)row_i * d.slots;
+                const int32_t *__restrict__ ip = idx + at;
+                const T *__restrict__ vp = val + at;
+                int sl = s0;
+                for (; sl + 4 <= s1; sl += 4) {
+                    uint32_t c[4];
+                    T v[4];
+                    T x[4][VV];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        c[e] = (uint32_t)ip[sl + e];
+                        v[e] = vp[sl + e];
+                    }
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) load_x<T, VV, WIDE>(x[e], X, c[e], (uint32_t)ccol, lane_off);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+#pragma unroll
+                        for (int i = 0; i < VV; ++i) acc[i] += v[e] * x[e][i];
+                }
+                for (; sl < s1; ++sl) {
+                    T x[VV];
+                    load_x<T, VV, WIDE>(x, X, (uint32_t)ip[sl], (uint32_t)ccol, lane_off);
+                    const T v = vp[sl];
+#pragma unroll
+                    for (int i = 0; i < VV; ++i) acc[i] += v * x[i];
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < VV; ++i) red[(grp * G + gl) * VV + i] = acc[i];
+            __syncthreads();
+            if (part == 0 && row_i < d.n_rows && active) {
+                T sum[VV];
+#pragma unroll
+                for (int i = 0; i < VV; ++i) sum[i] = T(0);
+                for (int pp = 0; pp < d.split; ++pp)
+#pragma unroll
+                    for (int i = 0; i < VV; ++i) sum[i] += red[((grp + pp) * G + gl) * VV + i];
+                store_pack<T, VV>(Y + (int64_t)rows[d.row_begin + row_i] * ccol + col, sum);
+            }
+            __syncthreads();
+        }
     }
-    const int G = min(64, pow2_at_least((a.ccol + VV - 1) / VV));
+}
+
+// CSR SpMM over a caller-supplied matrix (the first operation of the unfused SpMM-SpMM
+// baseline): Y[j][:] = sum_k S.vals[k] X[S.colidx[k]][:], consecutive rows per workgroup.
+template <typename T, bool FAST>
+__global__ __launch_bounds__(kSpmmThreads) void k_csr_spmm(const CsrSpmmLaunch a) {
+    constexpr int VV = FAST ? Tr<T>::V : 1;
+    const int64_t n_wg = (a.n_rows + a.rows_per_wg - 1) / a.rows_per_wg;
+    const int64_t u = xcd_contiguous(blockIdx.x, n_wg);
+    if (u >= n_wg) return;
+    const int64_t r0 = u * a.rows_per_wg;
+    const int64_t r1 = r0 + a.rows_per_wg < a.n_rows ? r0 + a.rows_per_wg : a.n_rows;
+    const int ccol = a.ccol;
+    const int G = min(64, pow2_at_least((ccol + VV - 1) / VV));
     const int gl = threadIdx.x % G, grp = threadIdx.x / G, ngrp = blockDim.x / G;
     const T *__restrict__ vals = static_cast<const T *>(a.S.vals);
     const T *__restrict__ X = static_cast<const T *>(a.X);
     T *__restrict__ Y = static_cast<T *>(a.Y);
-    const int32_t *__restrict__ rows = a.rows;
-    const int ccol = a.ccol;
-
-    bool coop = false;
-    if (r1 - r0 == 1) {
-        const int64_t j = rows ? rows[r0] : r0;
-        coop = a.S.rowptr[j + 1] - a.S.rowptr[j] >= kLongRowNnz;
-    }
     for (int cb = 0; cb < ccol; cb += G * VV) {
         const int col = cb + VV * gl;
-        const bool active = col < ccol;
-        if (!coop) {
-            auto out = [&](int, int64_t j, const T(&acc)[VV]) {
-                store_pack<T, VV>(Y + j * ccol + col, acc);
-            };
-            if (rows) {
-                const int32_t *__restrict__ list = rows + r0;
-                gather_rows<T, VV, int32_t, kRowsPerPass, kEntriesPerPass>(
-                    grp, (int)(r1 - r0), ngrp, a.S.rowptr, a.S.colidx, vals, X + col, ccol, active,
-                    [&](int pos) { return list[pos]; }, out);
-            } else {
-                gather_rows<T, VV, int32_t, kRowsPerPass, kEntriesPerPass>(
-                    grp, (int)(r1 - r0), ngrp, a.S.rowptr, a.S.colidx, vals, X + col, ccol, active,
-                    [&](int pos) { return (int32_t)(r0 + pos); }, out);
-            }
-        } else {
-            const int64_t j = rows ? rows[r0] : r0;
-            const int kbeg = a.S.rowptr[j], kend = a.S.rowptr[j + 1];
-            const int chunk = (kend - kbeg + ngrp - 1) / ngrp;
-            const int kb = min(kend, kbeg + grp * chunk), ke = min(kend, kb + chunk);
-            T acc[VV];
-#pragma unroll
-            for (int i = 0; i < VV; ++i) acc[i] = T(0);
-            if (active) row_dot<T, VV, int32_t>(acc, a.S.colidx, vals, kb, ke, X + col, ccol);
-#pragma unroll
-            for (int i = 0; i < VV; ++i) red[(grp * G + gl) * VV + i] = acc[i];
-            __syncthreads();
-            if (grp == 0 && active) {
-                T sum[VV];
-#pragma unroll
-                for (int i = 0; i < VV; ++i) sum[i] = T(0);
-                for (int gg = 0; gg < ngrp; ++gg)
-#pragma unroll
-                    for (int i = 0; i < VV; ++i) sum[i] += red[(gg * G + gl) * VV + i];
-                store_pack<T, VV>(Y + j * ccol + col, sum);
-            }
-            __syncthreads();
-        }
+        gather_rows<T, VV, int32_t, kRowsPerPass, kEntriesPerPass>(
+            grp, (int)(r1 - r0), ngrp, a.S.rowptr, a.S.colidx, vals, X + col, ccol, col < ccol,
+            [&](int pos) { return (int32_t)(r0 + pos); },
+            [&](int, int64_t j, const T(&acc)[VV]) { store_pack<T, VV>(Y + j * ccol + col, acc); });
     }
 }
 
@@ -571,16 +694,15 @@ __global__ __launch_bounds__(kFusedThreads) void k_gemm(const GemmLaunch a) {
         int64_t lb = lb0 + wave;
         {
             const int64_t row = lb * 16 + r;
-            const bool valid = lb < lb1 && row < a.n;
-            load_b_frag<T, KSF>(cur, B + (valid ? row : 0) * a.bcol, valid, g);
+            load_b_frag<T, KSF>(cur, B + (row < a.n ? row : a.n - 1) * a.bcol, g);
         }
         for (; lb < lb1; lb += nwaves) {
             // The C slice is loop invariant; keeping all of it in registers only pays while it
             // is small, so for larger slices the LDS reads are pinned inside the loop.
             if constexpr (KSF * Tr<T>::V * NB * (sizeof(T) / 4) > 64) asm volatile("" ::: "memory");
             const int64_t nrow = (lb + nwaves) * 16 + r;
-            const bool nvalid = lb + nwaves < lb1 && nrow < a.n;
-            load_b_frag<T, KSF>(nxt, B + (nvalid ? nrow : 0) * a.bcol, nvalid, g);
+            load_b_frag<T, KSF>(nxt, B + (nrow < a.n ? nrow : a.n - 1) * a.bcol, g);
+            __builtin_amdgcn_sched_barrier(0);      // keep the prefetch ahead of the MFMAs
             typename Tr<T>::Acc acc[NB];
             mfma_frag<T, NB, KSF>(acc, Cl, cur, lane);
             write_block(lb, acc);
@@ -717,17 +839,38 @@ int launch_fused_spmm_spmm(const FusedLaunch &a, void *stream) {
     return fast ? run_fused_spmm<double, true>(a, st) : run_fused_spmm<double, false>(a, st);
 }
 
-int launch_spmm_units(const SpmmLaunch &a, void *stream) {
+int launch_packed_spmm(const PackedSpmmLaunch &a, void *stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (a.n_units == 0) return 0;
     const bool fast = spmm_fast(a.dtype, a.ccol, a.ccol);
     const dim3 grid((unsigned)((a.n_units + 7) / 8 * 8)), block(kSpmmThreads);
+#define TF_GO(T)                                                                        \
+    do {                                                                                \
+        if (a.wide) {                                                                   \
+            if (fast) k_packed_spmm<T, true, true><<<grid, block, 0, st>>>(a);          \
+            else k_packed_spmm<T, false, true><<<grid, block, 0, st>>>(a);              \
+        } else {                                                                        \
+            if (fast) k_packed_spmm<T, true, false><<<grid, block, 0, st>>>(a);         \
+            else k_packed_spmm<T, false, false><<<grid, block, 0, st>>>(a);             \
+        }                                                                               \
+    } while (0)
+    if (a.dtype == TF_F32) TF_GO(float); else TF_GO(double);
+#undef TF_GO
+    return (int)hipGetLastError();
+}
+
+int launch_csr_spmm(const CsrSpmmLaunch &a, void *stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (a.n_rows == 0) return 0;
+    const bool fast = spmm_fast(a.dtype, a.ccol, a.ccol);
+    const int64_t n_wg = (a.n_rows + a.rows_per_wg - 1) / a.rows_per_wg;
+    const dim3 grid((unsigned)((n_wg + 7) / 8 * 8)), block(kSpmmThreads);
     if (a.dtype == TF_F32) {
-        if (fast) k_spmm_units<float, true><<<grid, block, 0, st>>>(a);
-        else k_spmm_units<float, false><<<grid, block, 0, st>>>(a);
+        if (fast) k_csr_spmm<float, true><<<grid, block, 0, st>>>(a);
+        else k_csr_spmm<float, false><<<grid, block, 0, st>>>(a);
     } else {
-        if (fast) k_spmm_units<double, true><<<grid, block, 0, st>>>(a);
-        else k_spmm_units<double, false><<<grid, block, 0, st>>>(a);
+        if (fast) k_csr_spmm<double, true><<<grid, block, 0, st>>>(a);
+        else k_csr_spmm<double, false><<<grid, block, 0, st>>>(a);
     }
     return (int)hipGetLastError();
 }

@@ -33,7 +33,7 @@ def check_schedule(A, s, ct_size, p):
     for (first, second), (i0, i1, rows) in zip(tiles, ref["tiles"]):
         assert first.size == i1 - i0 and (first.size == 0 or (first[0] == i0 and first[-1] == i1 - 1))
         assert np.array_equal(first, np.arange(i0, i1))
-        assert np.array_equal(second, rows)
+        assert np.array_equal(np.sort(second), rows)     # the order inside a tile is free
     assert np.array_equal(np.sort(s["wf1_rows"]), ref["wf1_rows"])
     assert np.array_equal(s["spill"].astype(bool), ref["spill"])
     out = so.validate(A.rowptr, A.colidx, tiles, units_of(s), s["spill"].astype(bool),
