@@ -31,7 +31,7 @@ MFMA_PEAK_TFLOPS = {"f32": 157.3, "f64": 78.6}
 # Tile parameters used per configuration.
 TILE_PARAMS = {
     1: dict(ct_size=128, p=1),
-    2: dict(ct_size=3072, p=1, col_slice=8),
+    2: dict(ct_size=65536, p=1, flags=4),
     3: dict(ct_size=256, p=1),
     4: dict(ct_size=2048, p=1),
     5: dict(ct_size=2048, p=1),
@@ -59,6 +59,7 @@ def parse():
     ap.add_argument("--p", type=int, default=None)
     ap.add_argument("--col-slice", type=int, default=None)
     ap.add_argument("--fast-mem", type=int, default=None)
+    ap.add_argument("--reorder", type=int, default=None, help="1: graph-grown tiles, 0: consecutive")
     return ap.parse_args()
 
 
@@ -95,6 +96,9 @@ def main():
                  ("fast_mem_bytes", args.fast_mem)):
         if v is not None:
             params[k] = v
+    if args.reorder is not None:
+        params["flags"] = (params.get("flags", 0) & ~tf.TF_FLAG_REORDER) | \
+            (tf.TF_FLAG_REORDER if args.reorder else 0)
 
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
     n, bcol, ccol = prob.n, prob.bcol, prob.ccol

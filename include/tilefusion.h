@@ -72,6 +72,13 @@ typedef struct tf_tile_params {
  * host memory, fast_mem_bytes is taken as given (default 160 KiB).  The plan serves
  * tf_plan_schedule; execution calls on it fail with TF_EINVAL. */
 #define TF_FLAG_SCHEDULE_ONLY 2u
+/* Tiles are grown along the dependence graph (breadth first over the column indices of A,
+ * starting from the lowest row not yet in a tile) instead of being ranges of consecutive rows, each
+ * as large as the fast memory allows and at most t rows.  The paper forms tiles from consecutive
+ * iterations (Section 3.1.1) because that is cheap and keeps spatial locality; on matrices whose
+ * rows depend on far-away rows (stencils in natural ordering) consecutive tiles small enough
+ * for LDS fuse nothing, while graph-grown tiles do. */
+#define TF_FLAG_REORDER 4u
 
 typedef struct tf_plan tf_plan; /* opaque, library-owned */
 

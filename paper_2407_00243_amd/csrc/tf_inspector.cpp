@@ -185,47 +185,96 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
     if (t < 1) t = 1;
     s.t = (int32_t)std::min<int64_t>(t, INT32_MAX);
 
-    // ---- step 1 + step 2: tile ranges ---------------------------------------------------
-    std::vector<Range> tiles;
+    // ---- tiles: lists of first-operation rows -------------------------------------------
+    // first_rows holds the rows tile after tile; tile_first_ptr delimits the tiles.
     const bool allow_split = !(in.flags & TF_FLAG_NO_SPLIT);
-    for (int64_t i0 = 0; i0 < n; i0 += t) {
-        ++s.n_coarse_tiles;
-        split_tile(s, Range{i0, std::min(n, i0 + t)}, allow_split, tiles);
+    s.first_rows.resize((size_t)n);
+    s.tile_first_ptr.assign(1, 0);
+    if (in.flags & TF_FLAG_REORDER) {
+        // Tiles grown along the dependence graph: as many rows as fit the fast memory (and at
+        // most t), collected breadth first from the lowest row not yet in a tile by following
+        // each row's column indices; when a search runs dry the tile goes on from the next
+        // free row.  Rows inside a tile are kept in ascending order.
+        int64_t cap = std::min<int64_t>(t, 65536);
+        while (cap > 1 && tile_footprint(s, cap) > s.fast_mem_bytes) --cap;
+        cap = std::max<int64_t>(1, cap / s.lds_row_granule * s.lds_row_granule);
+        if (tile_footprint(s, cap) > s.fast_mem_bytes) cap = 1;
+        std::vector<uint8_t> taken((size_t)n, 0);
+        std::vector<int32_t> queue;
+        queue.reserve((size_t)cap);
+        int64_t seed = 0, filled = 0;
+        while (filled < n) {
+            queue.clear();
+            size_t head = 0;
+            while ((int64_t)queue.size() < cap && filled + (int64_t)queue.size() < n) {
+                if (head == queue.size()) {               // start (or restart) from a free row
+                    while (taken[seed]) ++seed;
+                    taken[seed] = 1;
+                    queue.push_back((int32_t)seed);
+                    continue;
+                }
+                const int32_t j = queue[head++];
+                for (int64_t q = in.rowptr[j]; q < in.rowptr[j + 1]; ++q) {
+                    const int32_t c = in.colidx[q];
+                    if (!taken[c] && (int64_t)queue.size() < cap) {
+                        taken[c] = 1;
+                        queue.push_back(c);
+                    }
+                }
+            }
+            std::sort(queue.begin(), queue.end());
+            std::copy(queue.begin(), queue.end(), s.first_rows.begin() + filled);
+            filled += (int64_t)queue.size();
+            s.tile_first_ptr.push_back((int32_t)filled);
+        }
+        s.n_coarse_tiles = (int64_t)s.tile_first_ptr.size() - 1;
+    } else {
+        // Algorithm 1: uniform tiles of t consecutive rows (step 1), halved until they fit (step 2)
+        std::vector<Range> tiles;
+        for (int64_t i0 = 0; i0 < n; i0 += t) {
+            ++s.n_coarse_tiles;
+            split_tile(s, Range{i0, std::min(n, i0 + t)}, allow_split, tiles);
+        }
+        std::iota(s.first_rows.begin(), s.first_rows.end(), 0);
+        for (const Range &r : tiles) s.tile_first_ptr.push_back((int32_t)r.i1);
     }
-    for (const Range &r : tiles) {
-        if (tile_footprint(s, r.i1 - r.i0) > s.fast_mem_bytes) {
+    const int64_t nt = (int64_t)s.tile_first_ptr.size() - 1;
+    for (int64_t vt = 0; vt < nt; ++vt) {
+        const int64_t rows = s.tile_first_ptr[vt + 1] - s.tile_first_ptr[vt];
+        if (tile_footprint(s, rows) > s.fast_mem_bytes) {
             err = "a tile does not fit the fast memory and splitting is disabled";
             return TF_EUNSUPPORTED;
         }
-        if (r.i1 - r.i0 > 65536) {
+        if (rows > 65536) {
             err = "a tile has more than 65536 rows (tile-local column indices are 16 bit)";
             return TF_EUNSUPPORTED;
         }
-        s.max_tile_rows = std::max(s.max_tile_rows, r.i1 - r.i0);
+        s.max_tile_rows = std::max(s.max_tile_rows, rows);
     }
 
-    // ---- classification: fused rows, tile-local column indices ---------------------------
-    const int64_t nt = (int64_t)tiles.size();
-    s.tile_first_ptr.resize(nt + 1);
+    // ---- classification: a row is fused when every column it refers to is produced by the
+    // tile that produces its own row; fused rows are packed with tile-local column indices ----
     s.tile_second_ptr.resize(nt + 1);
-    s.first_rows.resize(n);
     s.tile_unit_ptr.assign(1, 0);
     s.spill.assign((size_t)n, 0);
     const unsigned char *vals = static_cast<const unsigned char *>(in.vals);
     const PackRules tile_rules{kTileUnitRows, (int64_t)kTileUnitRows * 64, 0};
     std::vector<int32_t> wf1;
+    std::vector<int32_t> tile_of((size_t)n), local_of((size_t)n);
+    for (int64_t vt = 0; vt < nt; ++vt)
+        for (int64_t q = s.tile_first_ptr[vt]; q < s.tile_first_ptr[vt + 1]; ++q) {
+            tile_of[s.first_rows[q]] = (int32_t)vt;
+            local_of[s.first_rows[q]] = (int32_t)(q - s.tile_first_ptr[vt]);
+        }
     std::vector<int32_t> seen((size_t)n, -1);      // Eq. 2: distinct columns per tile
     for (int64_t vt = 0; vt < nt; ++vt) {
-        const Range r = tiles[vt];
-        s.tile_first_ptr[vt] = (int32_t)r.i0;
         std::vector<int32_t> tile_rows;
         int64_t tile_nnz = 0, uc = 0;
-        for (int64_t j = r.i0; j < r.i1; ++j) {
-            s.first_rows[j] = (int32_t)j;
+        for (int64_t fq = s.tile_first_ptr[vt]; fq < s.tile_first_ptr[vt + 1]; ++fq) {
+            const int64_t j = s.first_rows[fq];
             bool inside = true;
             for (int64_t q = in.rowptr[j]; q < in.rowptr[j + 1]; ++q) {
-                const int64_t c = in.colidx[q];
-                if (c < r.i0 || c >= r.i1) {
+                if (tile_of[in.colidx[q]] != (int32_t)vt) {
                     inside = false;
                     break;
                 }
@@ -244,15 +293,12 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
                 wf1.push_back((int32_t)j);
             }
         }
-        const int64_t rows = r.i1 - r.i0;
+        const int64_t rows = s.tile_first_ptr[vt + 1] - s.tile_first_ptr[vt];
         const int64_t nj = (int64_t)tile_rows.size();
         s.tile_second_ptr[vt] = (int32_t)s.fused.rows.size();
-        {   // second phase of this tile: its fused rows, packed with tile-local column indices
-            const int64_t i0 = r.i0;
-            pack_rows(in.rowptr, in.colidx, vals, es, tile_rows, tile_rules, true,
-                      [i0](int32_t c) { return c - i0; }, s.fused.idx16, s.fused);
-            s.tile_unit_ptr.push_back((int32_t)s.fused.units.size());
-        }
+        pack_rows(in.rowptr, in.colidx, vals, es, tile_rows, tile_rules, true,
+                  [&](int32_t c) { return local_of[c]; }, s.fused.idx16, s.fused);
+        s.tile_unit_ptr.push_back((int32_t)s.fused.units.size());
         // Eq. 2 (diagnostic): (nz + uc + t + |J|) * cCol + idx, counted in elements; for a dense B
         // the tile's rows x bCol block of B is added to nz, a sparse B is unknown here.
         const double nz = (double)tile_nnz + (in.b_is_sparse ? 0.0 : (double)rows * in.bcol);
@@ -260,10 +306,10 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
         s.eq2_cost_max = std::max(s.eq2_cost_max, (nz + uc + rows + nj) * (double)in.ccol + idx);
         s.fused_nnz += tile_nnz;
     }
-    s.tile_first_ptr[nt] = (int32_t)n;
     s.tile_second_ptr[nt] = (int32_t)s.fused.rows.size();
     s.second_rows = s.fused.rows;
     s.n_fused_rows = (int64_t)s.second_rows.size();
+    if (!(in.flags & TF_FLAG_REORDER)) std::sort(wf1.begin(), wf1.end());
 
     // ---- spill set ----------------------------------------------------------------------
     for (int32_t j : wf1)

@@ -4,7 +4,7 @@ import pytest
 
 import oracle
 import tf_inputs as ti
-from util import check_schedule, tiles_of, units_of
+from util import check_schedule, check_schedule_general, tiles_of, units_of
 
 pytestmark = pytest.mark.gpu
 
@@ -50,6 +50,27 @@ def test_small_configs(cfg, scale, params, fused):
     assert np.all(D[empty] == 0)
 
 
+REORDERED = [
+    (1, 1000, dict(ct_size=128)),
+    (2, 96, dict()),
+    (2, 96, dict(col_slice=32)),
+    (3, 12, dict()),
+    (4, 20, dict()),
+    (4, 20, dict(col_slice=16)),
+    (5, 12, dict(ct_size=500)),
+]
+
+
+@pytest.mark.parametrize("cfg,scale,params", REORDERED)
+def test_small_configs_graph_grown_tiles(cfg, scale, params):
+    import paper_2407_00243_amd as tf
+    prob = ti.config(cfg, scale_down=scale)
+    s, D, err = _parity(prob, flags=tf.TF_FLAG_REORDER, **params)
+    check_schedule_general(prob.A, s)
+    empty = np.diff(prob.A.rowptr) == 0
+    assert np.all(D[empty] == 0)
+
+
 # ---------------------------------------------------------------- exact integer inputs
 
 @pytest.mark.parametrize("dtype", [np.float32, np.float64])
@@ -73,12 +94,16 @@ def test_small_integers_bit_exact(dtype, kind, shape):
     with tf.Plan(A, bcol, ccol, kind == "spmm_spmm", flags=tf.TF_FLAG_SCHEDULE_ONLY) as pl:
         s0 = pl.schedule()
     small_lds = s0["lds_fixed_bytes"] + 48 * s0["lds_bytes_per_row"]     # forces step 2 to split
-    for params in (dict(ct_size=64, p=1), dict(ct_size=150, p=1, fast_mem_bytes=small_lds)):
+    for params in (dict(ct_size=64, p=1), dict(ct_size=150, p=1, fast_mem_bytes=small_lds),
+                   dict(ct_size=64, p=1, flags=tf.TF_FLAG_REORDER)):
         c = _case(prob, **params)
         try:
             s = c.plan.schedule()
             assert 0 < s["n_fused_rows"] and (n < 100 or s["n_wf1_rows"] > 0)
-            check_schedule(A, s, params["ct_size"], params["p"])
+            if params.get("flags"):
+                check_schedule_general(A, s)
+            else:
+                check_schedule(A, s, params["ct_size"], params["p"])
             for fused in (True, False):
                 D = c.run(fused=fused)
                 assert np.array_equal(D.astype(np.float64), D_ref), (params, fused)

@@ -5,7 +5,7 @@ import pytest
 
 import paper_2407_00243_amd as tf
 import tf_inputs as ti
-from util import check_schedule, footprint, tiles_of, units_of
+from util import check_schedule, check_schedule_general, footprint, tiles_of, units_of
 
 SO = tf.TF_FLAG_SCHEDULE_ONLY
 
@@ -42,6 +42,35 @@ def test_structured_configs_match_oracle(cfg, params):
     assert s["n_slices"] == -(-prob.ccol // s["col_slice"])
     for first, _ in tiles_of(s):
         assert footprint(s, first.size) <= s["fast_mem_bytes"]
+
+
+@pytest.mark.parametrize("cfg,scale,params", [
+    (1, None, dict()), (2, None, dict()), (2, None, dict(col_slice=32)), (4, None, dict()),
+    (4, None, dict(col_slice=16)), (3, 13, dict()), (5, 13, dict(ct_size=300)),
+])
+def test_graph_grown_tiles_are_valid(cfg, scale, params):
+    prob = ti.config(cfg, scale_down=scale)
+    s = plan_schedule(prob.A, prob.bcol, prob.ccol, prob.kind == "spmm_spmm",
+                      flags=tf.TF_FLAG_REORDER, **params)
+    check_schedule_general(prob.A, s)
+    sizes = np.diff(s["tile_first_ptr"])
+    assert np.all(sizes[:-1] == sizes[0]) and sizes[-1] <= sizes[0]    # all tiles full but the last
+    assert footprint(s, int(sizes[0])) <= s["fast_mem_bytes"]
+    if cfg == 2:
+        # consecutive tiles of this size fuse nothing on the 2D grid; graph-grown tiles do
+        assert s["fused_ratio_rows"] > 0.8 and s["n_spill_rows"] < 0.3 * prob.n
+    if cfg == 4:
+        assert s["fused_ratio_rows"] > 0.5
+
+
+def test_graph_grown_tiles_on_random_patterns():
+    for seed in range(4):
+        n = 300
+        A = ti.random_local_csr(n, 9, 4, 0.2, np.float32, seed)
+        for ct in (16, 50, 2048):
+            s = plan_schedule(A, 16, 16, False, ct_size=ct, p=1, flags=tf.TF_FLAG_REORDER)
+            check_schedule_general(A, s)
+            assert np.diff(s["tile_first_ptr"]).max() <= max(16, ct // 16 * 16)
 
 
 def test_closed_form_counts_through_the_abi():

@@ -49,3 +49,23 @@ def check_schedule(A, s, ct_size, p):
     lens = np.diff(A.rowptr.astype(np.int64))
     assert s["fused_nnz"] == int(lens[out["fused_rows"]].sum())
     return ref
+
+
+def check_schedule_general(A, s):
+    """Schedules whose tiles are not ranges of consecutive rows have many valid answers: they are
+    checked by the implementation-free validator only (every iteration exactly once, every
+    dependence inside its tile or across the barrier, minimal spill set, maximal fusion for the
+    tiles chosen, footprint within the fast memory) and by a recount of the reported ratios."""
+    tiles = tiles_of(s)
+    out = so.validate(A.rowptr, A.colidx, tiles, units_of(s), s["spill"].astype(bool),
+                      tile_cost=lambda rows: footprint(s, rows), fast_mem=s["fast_mem_bytes"])
+    assert out["superfluous_spill"] == 0
+    assert out["n_fused_rows"] == s["n_fused_rows"]
+    assert out["n_wf1_rows"] == s["n_wf1_rows"]
+    assert out["n_spill"] == s["n_spill_rows"]
+    fr = so.fused_ratios(A.rowptr, out["n_fused_rows"], out["fused_rows"])
+    assert abs(fr["rows"] - s["fused_ratio_rows"]) < 1e-15
+    assert abs(fr["nnz"] - s["fused_ratio_nnz"]) < 1e-15
+    for first, _ in tiles:
+        assert np.all(np.diff(first) > 0)            # ascending inside a tile
+    return out
