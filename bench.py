@@ -60,6 +60,9 @@ def parse():
     ap.add_argument("--col-slice", type=int, default=None)
     ap.add_argument("--fast-mem", type=int, default=None)
     ap.add_argument("--reorder", type=int, default=None, help="1: graph-grown tiles, 0: consecutive")
+    ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
+                    help="instead of the benchmark, run 10 plain device copies of MIB MiB (for "
+                         "scaling the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     return ap.parse_args()
 
 
@@ -72,6 +75,17 @@ def main():
 
     import numpy as np
     import torch
+
+    if args.calibrate_copy:
+        torch.cuda.set_device(0)
+        nel = args.calibrate_copy * 1024 * 1024 // 4
+        src = torch.ones(nel, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_mib": args.calibrate_copy, "copies": 10}))
+        return
 
     import paper_2407_00243_amd as tf
     import tf_inputs as ti
