@@ -64,7 +64,7 @@ struct tf_plan {
             return d;
         }
     };
-    DevBuf tile_first_ptr, first_rows_enc, tile_unit_ptr;
+    DevBuf tile_first_ptr, first_rows_enc, tile_unit_ptr, tile_spill_ptr, spill_local, spill_row;
     PackBufs fused, wf1, all;
     DevBuf d1;
 };
@@ -115,6 +115,9 @@ tf::FusedLaunch fused_args(const tf_plan *p, const void *C, void *D) {
     a.tile_first_ptr = static_cast<const int32_t *>(p->tile_first_ptr.p);
     a.first_rows_enc = static_cast<const int32_t *>(p->first_rows_enc.p);
     a.tile_unit_ptr = static_cast<const int32_t *>(p->tile_unit_ptr.p);
+    a.tile_spill_ptr = static_cast<const int32_t *>(p->tile_spill_ptr.p);
+    a.spill_local = static_cast<const int32_t *>(p->spill_local.p);
+    a.spill_row = static_cast<const int32_t *>(p->spill_row.p);
     a.second = p->fused.dev();
     a.C = C;
     a.D = D;
@@ -280,6 +283,9 @@ tf_status tf_plan_create(const tf_csr *A, int64_t bCol, int64_t cCol, int32_t b_
         ok(up(p->tile_first_ptr, p->s.tile_first_ptr));
         ok(up(p->first_rows_enc, enc));
         ok(up(p->tile_unit_ptr, p->s.tile_unit_ptr));
+        ok(up(p->tile_spill_ptr, p->s.tile_spill_ptr));
+        ok(up(p->spill_local, p->s.spill_local));
+        ok(up(p->spill_row, p->s.spill_row));
         ok(upload_pack(p->fused, p->s.fused));
         ok(upload_pack(p->wf1, p->s.wf1));
         ok(upload_pack(p->all, p->s.all));

@@ -315,6 +315,16 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
     for (int32_t j : wf1)
         for (int64_t q = in.rowptr[j]; q < in.rowptr[j + 1]; ++q) s.spill[in.colidx[q]] = 1;
     s.n_spill_rows = std::accumulate(s.spill.begin(), s.spill.end(), (int64_t)0);
+    s.tile_spill_ptr.assign(1, 0);
+    for (int64_t vt = 0; vt < nt; ++vt) {
+        for (int64_t q = s.tile_first_ptr[vt]; q < s.tile_first_ptr[vt + 1]; ++q) {
+            if (s.spill[s.first_rows[q]]) {
+                s.spill_local.push_back((int32_t)(q - s.tile_first_ptr[vt]));
+                s.spill_row.push_back(s.first_rows[q]);
+            }
+        }
+        s.tile_spill_ptr.push_back((int32_t)s.spill_local.size());
+    }
 
     // ---- balance: units of the second wavefront, and of the unfused baseline ------------
     const int vv = in.ccol % v == 0 ? v : 1;

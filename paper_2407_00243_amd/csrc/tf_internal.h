@@ -94,6 +94,7 @@ struct Schedule {
     std::vector<uint8_t> spill;
     RowPack fused;                 // second_rows re-packed with tile-local column indices
     std::vector<int32_t> tile_unit_ptr;                   // units of `fused` per tile
+    std::vector<int32_t> tile_spill_ptr, spill_local, spill_row;   // spilled rows per tile
     RowPack wf1;                   // wf1_rows re-packed
     RowPack all;                   // all rows re-packed (unfused baseline)
     int64_t n_fused_rows = 0, n_spill_rows = 0, fused_nnz = 0;
@@ -141,6 +142,8 @@ struct FusedLaunch {
     int32_t max_tile_rows;            // largest tile, in rows
     int64_t lds_bytes;                // dynamic LDS of the launch
     const int32_t *tile_first_ptr, *first_rows_enc;   // first_rows with kSpillBit
+    const int32_t *tile_spill_ptr;    // per tile: its spilled rows, as (tile-local index, row id)
+    const int32_t *spill_local, *spill_row;
     const int32_t *tile_unit_ptr;     // second phase: units of `second` per tile
     PackDev second;                   // uint16 tile-local indices
     const void *B;                    // dense B (gemm) or nullptr

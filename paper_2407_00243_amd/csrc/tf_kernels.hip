@@ -16,6 +16,7 @@
 // groups across the rest of the wave.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <type_traits>
 
 #include "tf_internal.h"
@@ -445,14 +446,89 @@ __device__ __forceinline__ void mfma_frag(typename Tr<T>::Acc (&acc)[NB], const 
                 acc[nb] = mfma16(Cl[((s * V + q) * NB + nb) * 64 + lane], f.v[s][q], acc[nb]);
 }
 
-// First wavefront, dense B.  KS > 0: bCol = 4 V KS exactly, the B rows of the next 16-row block
-// are fetched while the current block is multiplied; KS = 0: any bCol, no prefetch.
+// The same with the lane's C operands already in registers (creg[(s V + q) NB + nb]).
+template <typename T, int NB, int KS>
+__device__ __forceinline__ void mfma_frag_reg(typename Tr<T>::Acc (&acc)[NB],
+                                              const T (&creg)[KS * Tr<T>::V * NB],
+                                              const BFrag<T, KS> &f) {
+    constexpr int V = Tr<T>::V;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) acc[nb] = typename Tr<T>::Acc{0, 0, 0, 0};
+#pragma unroll
+    for (int s = 0; s < KS; ++s)
+#pragma unroll
+        for (int q = 0; q < V; ++q)
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+                acc[nb] = mfma16(creg[(s * V + q) * NB + nb], f.v[s][q], acc[nb]);
+}
+
+// Whether a wave keeps its C operands in registers: shallow k and at most 64 VGPRs' worth
+// (32 for fp64, whose prefetch buffers are twice as large).
+template <typename T, int NB, int KS> constexpr bool c_in_registers() {
+    return KS > 0 && KS <= 4 && KS * Tr<T>::V * NB * (int)(sizeof(T) / 4) <= (sizeof(T) == 4 ? 64 : 32);
+}
+
+// Which tiles a fused workgroup works on.  Workgroups are persistent: workgroup b sits on XCD
+// b % 8 (consecutive ids are dealt round-robin to the XCDs), keeps one column slice for its
+// whole life (so the C slice is staged once) and walks through that XCD's contiguous range of
+// tiles with a fixed stride.  The slices of a tile belong to neighbouring workgroups of one XCD.
+struct TileWalk {
+    int slice, tile, tile_end, step;
+};
+__device__ __forceinline__ TileWalk tile_walk(int n_tiles, int n_slices) {
+    const int per = (n_tiles + 7) >> 3;
+    const int k = blockIdx.x >> 3, wg_per_xcd = gridDim.x >> 3;
+    TileWalk t;
+    t.slice = k % n_slices;
+    t.step = wg_per_xcd / n_slices;
+    t.tile = (blockIdx.x & 7) * per + k / n_slices;
+    t.tile_end = min(n_tiles, ((int)(blockIdx.x & 7) + 1) * per);
+    return t;
+}
+
+// Spilled rows of a tile: copied from the LDS tile to the D1 workspace, whole rows at a time.
+template <typename T, int VV>
+__device__ __forceinline__ void spill_rows(const FusedLaunch &a, const T *tileD1, int ldl, int tile,
+                                           int c0, int gl, int grp, int ngrp) {
+    const int s0 = a.tile_spill_ptr[tile], ns = a.tile_spill_ptr[tile + 1] - s0;
+    const int32_t *__restrict__ sl = a.spill_local + s0;
+    const int32_t *__restrict__ sr = a.spill_row + s0;
+    T *__restrict__ D1 = static_cast<T *>(a.D1);
+    constexpr int R = 4;
+    for (int i0 = grp; i0 < ns; i0 += ngrp * R) {
+        int lr[R];
+        int64_t row[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int i = i0 + r * ngrp < ns ? i0 + r * ngrp : i0;
+            lr[r] = sl[i];
+            row[r] = sr[i];
+        }
+        T x[R][VV];
+#pragma unroll
+        for (int r = 0; r < R; ++r) load_pack<T, VV>(x[r], tileD1 + lr[r] * ldl + VV * gl);
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            if (i0 + r * ngrp < ns) store_pack<T, VV>(D1 + row[r] * a.ccol + c0 + VV * gl, x[r]);
+    }
+}
+
+// First wavefront, dense B.  Per tile: phase 1 multiplies the tile's rows of B by the C slice
+// with MFMA into the LDS tile; after a barrier phase 2 copies the spilled rows to the D1
+// workspace and computes the tile's fused rows of D out of LDS.
+// KS > 0: bCol = 4 V KS exactly, and the B rows of the next 16-row block (also the first block
+// of the workgroup's next tile) are in flight while the current block is multiplied;
+// KS = 0: any bCol, no prefetch.
 template <typename T, int NB, int KS, bool FAST>
 __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLaunch a) {
     constexpr int V = Tr<T>::V, KC = 4 * V;
-    int tile, slice;
-    if (!tile_and_slice(blockIdx.x, a.n_tiles, a.n_slices, tile, slice)) return;
-    const int c0 = slice * a.cs;
+    constexpr int VV = FAST ? V : 1;
+    constexpr int KSF = KS > 0 ? KS : 1;
+    constexpr bool CREG = c_in_registers<T, NB, KS>();
+    TileWalk tw = tile_walk(a.n_tiles, a.n_slices);
+    if (tw.tile >= tw.tile_end) return;
+    const int c0 = tw.slice * a.cs;
     const int w = min(a.cs, a.ccol - c0);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
     const int g = lane >> 4, r = lane & 15;
@@ -461,62 +537,83 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
     const int ldl = csv + V;
     T *Cl = reinterpret_cast<T *>(tf_smem);
     T *tileD1 = Cl + (int64_t)bcol_pad * 16 * NB;
+    const T *__restrict__ B = static_cast<const T *>(a.B);
+    const int G = pow2_at_least((a.cs + VV - 1) / VV);
+    const int gl = threadIdx.x % G, grp = threadIdx.x / G, ngrp = blockDim.x / G;
 
+    // this lane's row (and spill flag, unused here) in block lb of a tile; padding lanes and
+    // blocks past the end name the tile's last row, so that every load is unconditional
+    auto row_of = [&](const int32_t *__restrict__ first, int rows, int lb) -> int64_t {
+        const int lr = lb * 16 + r;
+        return (int64_t)((uint32_t)first[lr < rows ? lr : rows - 1] & ~kSpillBit);
+    };
+
+    int fp0 = a.tile_first_ptr[tw.tile];
+    int rows = a.tile_first_ptr[tw.tile + 1] - fp0;
+    BFrag<T, KSF> cur, nxt;
+    int64_t row_nxt = 0;
+    if constexpr (KS > 0) {
+        // first block of the first tile: on its way while the C slice is staged
+        load_b_frag<T, KSF>(cur, B + row_of(a.first_rows_enc + fp0, rows, wave) * a.bcol, g);
+        row_nxt = row_of(a.first_rows_enc + fp0, rows, wave + nwaves);
+    }
     stage_c_slice<T, NB>(Cl, static_cast<const T *>(a.C), a.bcol, a.ccol, c0, w);
     __syncthreads();
-
-    const int fp0 = a.tile_first_ptr[tile];
-    const int rows = a.tile_first_ptr[tile + 1] - fp0;
-    const int nblk = (rows + 15) >> 4;
-    const T *__restrict__ B = static_cast<const T *>(a.B);
-    T *__restrict__ D1 = static_cast<T *>(a.D1);
-    const int32_t *__restrict__ first = a.first_rows_enc + fp0;
-    // Row id and spill flag of this lane's row in block lb.  Padding lanes and blocks past the
-    // end name the tile's last row (so that every load below is unconditional) and are marked
-    // by `valid_of`.
-    auto enc_of = [&](int lb) -> uint32_t {
-        const int lr = lb * 16 + r;
-        return (uint32_t)first[lr < rows ? lr : rows - 1];
-    };
-    auto valid_of = [&](int lb) -> bool { return lb * 16 + r < rows; };
-    auto write_block = [&](int lb, uint32_t enc, typename Tr<T>::Acc(&acc)[NB]) {
-        const int lr = lb * 16 + r;
-        const int64_t row = enc & ~kSpillBit;
-        const bool spill = valid_of(lb) && (enc & kSpillBit);
+    T creg[CREG ? KSF * V * NB : 1];
+    if constexpr (CREG) {
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            const int col = 16 * nb + 4 * g;
-            store_acc4<T, true>(tileD1 + (int64_t)lr * ldl + col, acc[nb], col, csv);
-            if (spill) store_acc4<T, FAST>(D1 + row * a.ccol + c0 + col, acc[nb], col, w);
-        }
-    };
-    if constexpr (KS > 0) {
-        constexpr int KSF = KS;
-        BFrag<T, KSF> cur, nxt;
-        uint32_t enc_cur = enc_of(wave), enc_nxt = enc_of(wave + nwaves);
-        load_b_frag<T, KSF>(cur, B + (int64_t)(enc_cur & ~kSpillBit) * a.bcol, g);
-        for (int lb = wave; lb < nblk; lb += nwaves) {
-            const uint32_t enc_nn = enc_of(lb + 2 * nwaves);
-            load_b_frag<T, KSF>(nxt, B + (int64_t)(enc_nxt & ~kSpillBit) * a.bcol, g);
-            __builtin_amdgcn_sched_barrier(0);      // keep the prefetch ahead of the MFMAs
-            typename Tr<T>::Acc acc[NB];
-            mfma_frag<T, NB, KSF>(acc, Cl, cur, lane);
-            write_block(lb, enc_cur, acc);
-            cur = nxt;
-            enc_cur = enc_nxt;
-            enc_nxt = enc_nn;
-        }
-    } else {
-        for (int lb = wave; lb < nblk; lb += nwaves) {
-            const uint32_t enc = enc_of(lb);
-            typename Tr<T>::Acc acc[NB];
-            mfma_row_block<T, NB, FAST>(acc, Cl, B + (int64_t)(enc & ~kSpillBit) * a.bcol, true,
-                                        a.bcol, lane);
-            write_block(lb, enc, acc);
-        }
+        for (int i = 0; i < KSF * V * NB; ++i) creg[i] = Cl[i * 64 + lane];
     }
-    __syncthreads();
-    fused_second_phase<T, FAST>(a, tileD1, ldl, tile, c0, w);
+
+    for (; tw.tile < tw.tile_end; tw.tile += tw.step) {
+        const int32_t *__restrict__ first = a.first_rows_enc + fp0;
+        const int nblk = (rows + 15) >> 4;
+        // the workgroup's next tile (if any): its first block is prefetched at the end of phase 1
+        const int ntile = tw.tile + tw.step;
+        const bool has_next = ntile < tw.tile_end;
+        const int nfp0 = has_next ? a.tile_first_ptr[ntile] : fp0;
+        const int nrows = has_next ? a.tile_first_ptr[ntile + 1] - nfp0 : rows;
+
+        auto write_block = [&](int lb, typename Tr<T>::Acc(&acc)[NB]) {
+            const int lr = lb * 16 + r;
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                const int col = 16 * nb + 4 * g;
+                store_acc4<T, true>(tileD1 + (int64_t)lr * ldl + col, acc[nb], col, csv);
+            }
+        };
+        if constexpr (KS > 0) {
+            for (int lb = wave; lb < nblk; lb += nwaves) {
+                const int64_t row_nn = row_of(first, rows, lb + 2 * nwaves);
+                load_b_frag<T, KSF>(nxt, B + row_nxt * a.bcol, g);
+                __builtin_amdgcn_sched_barrier(0);      // keep the prefetch ahead of the MFMAs
+                typename Tr<T>::Acc acc[NB];
+                if constexpr (CREG) mfma_frag_reg<T, NB, KSF>(acc, creg, cur);
+                else mfma_frag<T, NB, KSF>(acc, Cl, cur, lane);
+                write_block(lb, acc);
+                cur = nxt;
+                row_nxt = row_nn;
+            }
+            if (has_next) {
+                // first block of the next tile: on its way during this tile's second phase
+                load_b_frag<T, KSF>(cur, B + row_of(a.first_rows_enc + nfp0, nrows, wave) * a.bcol, g);
+                row_nxt = row_of(a.first_rows_enc + nfp0, nrows, wave + nwaves);
+            }
+        } else {
+            for (int lb = wave; lb < nblk; lb += nwaves) {
+                typename Tr<T>::Acc acc[NB];
+                mfma_row_block<T, NB, FAST>(acc, Cl, B + row_of(first, rows, lb) * a.bcol, true,
+                                            a.bcol, lane);
+                write_block(lb, acc);
+            }
+        }
+        __syncthreads();
+        if (VV * gl < w) spill_rows<T, VV>(a, tileD1, ldl, tw.tile, c0, gl, grp, ngrp);
+        fused_second_phase<T, FAST>(a, tileD1, ldl, tw.tile, c0, w);
+        if (has_next) __syncthreads();      // the LDS tile is rewritten by the next tile
+        fp0 = nfp0;
+        rows = nrows;
+    }
 }
 
 template <typename T, bool FAST>
@@ -734,7 +831,13 @@ int run_fused_gemm(const FusedLaunch &a, hipStream_t st) {
         if (e) return e;
         raised = a.lds_bytes;
     }
-    const int64_t grid = (int64_t)((a.n_tiles + 7) / 8) * 8 * a.n_slices;
+    // persistent workgroups: as many per XCD as its 32 CUs hold at once (one or two per CU by
+    // LDS), a multiple of the number of slices, and no more than there are (tile, slice) pairs
+    const int64_t per = (a.n_tiles + 7) / 8;
+    const int64_t occ = a.lds_bytes * 2 <= 160 * 1024 ? 2 : 1;
+    int64_t wg_per_xcd = std::min<int64_t>(per * a.n_slices, 32 * occ);
+    wg_per_xcd = std::max<int64_t>(a.n_slices, wg_per_xcd / a.n_slices * a.n_slices);
+    const int64_t grid = 8 * wg_per_xcd;
     k_fused_gemm_spmm<T, NB, KS, FAST><<<dim3((unsigned)grid), dim3(kFusedThreads), a.lds_bytes, st>>>(a);
     return (int)hipGetLastError();
 }
