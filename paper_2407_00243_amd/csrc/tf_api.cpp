@@ -48,6 +48,7 @@ struct tf_plan {
     int64_t n = 0, nnz = 0, bcol = 0, ccol = 0;
     int32_t dtype = 0, b_is_sparse = 0;
     int device = 0;
+    int64_t lds_per_cu = 160 * 1024;
     bool schedule_only = false;
     tf::Schedule s;
     double plan_seconds = 0.0;
@@ -64,8 +65,8 @@ struct tf_plan {
             return d;
         }
     };
-    DevBuf tile_first_ptr, first_rows_enc, tile_unit_ptr, tile_spill_ptr, spill_local, spill_row;
-    PackBufs fused, wf1, all;
+    DevBuf tile_desc, tile_meta;
+    PackBufs wf1, all;
     DevBuf d1;
 };
 
@@ -109,16 +110,13 @@ tf::FusedLaunch fused_args(const tf_plan *p, const void *C, void *D) {
     a.cs = p->s.col_slice;
     a.ccol = (int32_t)p->ccol;
     a.bcol = (int32_t)p->bcol;
-    a.max_tile_rows = (int32_t)p->s.max_tile_rows;
-    a.lds_bytes = p->s.lds_fixed_bytes +
-                  tf::round_up(p->s.max_tile_rows, p->s.lds_row_granule) * p->s.lds_bytes_per_row;
-    a.tile_first_ptr = static_cast<const int32_t *>(p->tile_first_ptr.p);
-    a.first_rows_enc = static_cast<const int32_t *>(p->first_rows_enc.p);
-    a.tile_unit_ptr = static_cast<const int32_t *>(p->tile_unit_ptr.p);
-    a.tile_spill_ptr = static_cast<const int32_t *>(p->tile_spill_ptr.p);
-    a.spill_local = static_cast<const int32_t *>(p->spill_local.p);
-    a.spill_row = static_cast<const int32_t *>(p->spill_row.p);
-    a.second = p->fused.dev();
+    a.rows_cap = (int32_t)tf::round_up(p->s.max_tile_rows, 16);
+    a.s_cap = (int32_t)p->s.second_block_cap;
+    a.s_in_lds = p->s.second_block_in_lds ? 1 : 0;
+    a.lds_bytes = tf::fused_lds_bytes(p->dtype, p->b_is_sparse, a.bcol, a.ccol, a.cs, a.rows_cap,
+                                      a.s_in_lds ? a.s_cap : 0);
+    a.tile_desc = static_cast<const tf::TileDesc *>(p->tile_desc.p);
+    a.tile_meta = static_cast<const unsigned char *>(p->tile_meta.p);
     a.C = C;
     a.D = D;
     a.D1 = p->d1.p;
@@ -270,23 +268,14 @@ tf_status tf_plan_create(const tf_csr *A, int64_t bCol, int64_t cCol, int32_t b_
             *out = p;
             return TF_OK;
         }
-        // first_rows with the spill flag folded into the top bit
-        std::vector<int32_t> enc(p->s.first_rows.size());
-        for (size_t i = 0; i < enc.size(); ++i) {
-            const int32_t r = p->s.first_rows[i];
-            enc[i] = (int32_t)((uint32_t)r | (p->s.spill[r] ? tf::kSpillBit : 0u));
-        }
+        p->lds_per_cu = lds_limit;
         hipError_t e = hipSuccess;
         auto ok = [&](hipError_t r) {
             if (e == hipSuccess) e = r;
         };
-        ok(up(p->tile_first_ptr, p->s.tile_first_ptr));
-        ok(up(p->first_rows_enc, enc));
-        ok(up(p->tile_unit_ptr, p->s.tile_unit_ptr));
-        ok(up(p->tile_spill_ptr, p->s.tile_spill_ptr));
-        ok(up(p->spill_local, p->s.spill_local));
-        ok(up(p->spill_row, p->s.spill_row));
-        ok(upload_pack(p->fused, p->s.fused));
+        ok(up(p->tile_desc, p->s.tile_desc));
+        ok(up(p->tile_meta, p->s.tile_meta));
+        std::vector<unsigned char>().swap(p->s.tile_meta);
         ok(upload_pack(p->wf1, p->s.wf1));
         ok(upload_pack(p->all, p->s.all));
         ok(p->d1.alloc((size_t)n * cCol * es));

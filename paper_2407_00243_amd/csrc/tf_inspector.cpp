@@ -136,6 +136,79 @@ void pack_rows(const int32_t *rowptr, const int32_t *colidx, const unsigned char
 
 }  // namespace
 
+namespace {
+
+// Second-phase block of one tile (see TileDesc): the fused rows, longest first, cut into units
+// of one padded length each.  A unit ends when the next row is shorter and the unit already
+// has 64 rows, or when the next row would be padded by more than a quarter.  The padded length
+// (stride) is even so that index pairs and value pairs are aligned; padding entries repeat the
+// row's last column with value 0.
+struct TileBlock {
+    std::vector<unsigned char> bytes;
+    std::vector<int32_t> rows;      // fused rows in block order
+    int32_t n_units = 0, n_entries = 0;
+};
+
+template <typename LocalFn>
+TileBlock pack_tile(const int32_t *rowptr, const int32_t *colidx, const unsigned char *vals, int es,
+                    std::vector<int32_t> list, LocalFn local) {
+    auto len = [&](int32_t j) { return (int64_t)rowptr[j + 1] - rowptr[j]; };
+    auto align16 = [](size_t x) { return (x + 15) / 16 * 16; };
+    TileBlock tb;
+    std::stable_sort(list.begin(), list.end(), [&](int32_t a, int32_t b) { return len(a) > len(b); });
+    tb.rows = list;
+    std::vector<TileUnit> units;
+    std::vector<uint16_t> idx;
+    std::vector<unsigned char> val;
+    const int64_t count = (int64_t)list.size();
+    int64_t pos = 0;
+    while (pos < count) {
+        const int64_t L = len(list[pos]);
+        const int64_t stride = (L + 1) / 2 * 2;
+        int64_t take = 1;
+        while (pos + take < count) {
+            const int64_t ln = len(list[pos + take]);
+            if (ln == L) {
+                ++take;
+                continue;
+            }
+            if (take >= 64 || ln * 4 < L * 3 || ln == 0) break;
+            ++take;
+        }
+        TileUnit u{};
+        u.entry_base = (int32_t)idx.size();
+        u.row_begin = (int32_t)pos;
+        u.n_rows = (int32_t)take;
+        u.slots = (int32_t)(stride | (L << 16));
+        for (int64_t q = pos; q < pos + take; ++q) {
+            const int32_t j = list[q];
+            const int64_t k0 = rowptr[j], ln = len(j);
+            for (int64_t sl = 0; sl < stride; ++sl) {
+                const int64_t k = k0 + (sl < ln ? sl : ln - 1);
+                idx.push_back((uint16_t)local(colidx[k]));
+                const size_t at = val.size();
+                val.resize(at + es, 0);
+                if (sl < ln) std::memcpy(&val[at], vals + (size_t)k * es, es);
+            }
+        }
+        units.push_back(u);
+        pos += take;
+    }
+    const size_t off_rows2 = align16(units.size() * sizeof(TileUnit));
+    const size_t off_idx = align16(off_rows2 + list.size() * 4);
+    const size_t off_val = align16(off_idx + idx.size() * 2);
+    tb.bytes.assign(align16(off_val + val.size()), 0);
+    if (!units.empty()) std::memcpy(tb.bytes.data(), units.data(), units.size() * sizeof(TileUnit));
+    if (!list.empty()) std::memcpy(tb.bytes.data() + off_rows2, list.data(), list.size() * 4);
+    if (!idx.empty()) std::memcpy(tb.bytes.data() + off_idx, idx.data(), idx.size() * 2);
+    if (!val.empty()) std::memcpy(tb.bytes.data() + off_val, val.data(), val.size());
+    tb.n_units = (int32_t)units.size();
+    tb.n_entries = (int32_t)idx.size();
+    return tb;
+}
+
+}  // namespace
+
 tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err) {
     const int64_t n = in.n;
     const int es = elem_size(in.dtype);
@@ -168,8 +241,16 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
     s.n_slices = (int32_t)((in.ccol + cs - 1) / cs);
 
     // ---- fast-memory model --------------------------------------------------------------
-    s.lds_fixed_bytes = lds_fixed_bytes(in.dtype, in.b_is_sparse, (int)in.bcol, (int)cs);
-    s.lds_bytes_per_row = lds_ldl(in.dtype, in.b_is_sparse, (int)cs) * es;
+    // Per D1 row: the row itself, its id in two buffers (this tile's and the next one's), and an
+    // estimate of its share of the second-phase block (row id, packed entries of an average row).
+    // The C slice of a dense B takes LDS for good only when the waves read their operands from it.
+    const bool c_regs = !in.b_is_sparse &&
+                        c_in_registers(in.dtype, mfma_blocks((int)cs),
+                                       mfma_ksteps_special(in.dtype, (int)in.bcol, (int)in.ccol, (int)cs));
+    const int64_t avg_nnz = n > 0 ? (in.nnz + n - 1) / n : 0;
+    s.lds_meta_bytes_per_row = 8 + 4 + avg_nnz * (2 + es);
+    s.lds_fixed_bytes = (c_regs ? 0 : lds_fixed_bytes(in.dtype, in.b_is_sparse, (int)in.bcol, (int)cs)) + 256;
+    s.lds_bytes_per_row = lds_ldl(in.dtype, in.b_is_sparse, (int)cs) * es + s.lds_meta_bytes_per_row;
     s.lds_row_granule = lds_row_granule(in.b_is_sparse);
     s.fast_mem_bytes = in.fast_mem_bytes;
     if (tile_footprint(s, 1) > s.fast_mem_bytes) {
@@ -255,10 +336,9 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
     // ---- classification: a row is fused when every column it refers to is produced by the
     // tile that produces its own row; fused rows are packed with tile-local column indices ----
     s.tile_second_ptr.resize(nt + 1);
-    s.tile_unit_ptr.assign(1, 0);
     s.spill.assign((size_t)n, 0);
     const unsigned char *vals = static_cast<const unsigned char *>(in.vals);
-    const PackRules tile_rules{kTileUnitRows, (int64_t)kTileUnitRows * 64, 0};
+    std::vector<TileBlock> blocks((size_t)nt);
     std::vector<int32_t> wf1;
     std::vector<int32_t> tile_of((size_t)n), local_of((size_t)n);
     for (int64_t vt = 0; vt < nt; ++vt)
@@ -272,8 +352,10 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
         int64_t tile_nnz = 0, uc = 0;
         for (int64_t fq = s.tile_first_ptr[vt]; fq < s.tile_first_ptr[vt + 1]; ++fq) {
             const int64_t j = s.first_rows[fq];
-            bool inside = true;
-            for (int64_t q = in.rowptr[j]; q < in.rowptr[j + 1]; ++q) {
+            // (a row of 32768 entries or more, possible only with duplicates, is left to the second
+            // wavefront: the tile units store lengths in 15 bits)
+            bool inside = in.rowptr[j + 1] - in.rowptr[j] < 32768;
+            for (int64_t q = in.rowptr[j]; inside && q < in.rowptr[j + 1]; ++q) {
                 if (tile_of[in.colidx[q]] != (int32_t)vt) {
                     inside = false;
                     break;
@@ -295,10 +377,11 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
         }
         const int64_t rows = s.tile_first_ptr[vt + 1] - s.tile_first_ptr[vt];
         const int64_t nj = (int64_t)tile_rows.size();
-        s.tile_second_ptr[vt] = (int32_t)s.fused.rows.size();
-        pack_rows(in.rowptr, in.colidx, vals, es, tile_rows, tile_rules, true,
-                  [&](int32_t c) { return local_of[c]; }, s.fused.idx16, s.fused);
-        s.tile_unit_ptr.push_back((int32_t)s.fused.units.size());
+        s.tile_second_ptr[vt] = (int32_t)s.second_rows.size();
+        blocks[(size_t)vt] = pack_tile(in.rowptr, in.colidx, vals, es, tile_rows,
+                                       [&](int32_t c) { return local_of[c]; });
+        s.second_rows.insert(s.second_rows.end(), blocks[(size_t)vt].rows.begin(),
+                             blocks[(size_t)vt].rows.end());
         // Eq. 2 (diagnostic): (nz + uc + t + |J|) * cCol + idx, counted in elements; for a dense B
         // the tile's rows x bCol block of B is added to nz, a sparse B is unknown here.
         const double nz = (double)tile_nnz + (in.b_is_sparse ? 0.0 : (double)rows * in.bcol);
@@ -306,8 +389,7 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
         s.eq2_cost_max = std::max(s.eq2_cost_max, (nz + uc + rows + nj) * (double)in.ccol + idx);
         s.fused_nnz += tile_nnz;
     }
-    s.tile_second_ptr[nt] = (int32_t)s.fused.rows.size();
-    s.second_rows = s.fused.rows;
+    s.tile_second_ptr[nt] = (int32_t)s.second_rows.size();
     s.n_fused_rows = (int64_t)s.second_rows.size();
     if (!(in.flags & TF_FLAG_REORDER)) std::sort(wf1.begin(), wf1.end());
 
@@ -315,15 +397,39 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
     for (int32_t j : wf1)
         for (int64_t q = in.rowptr[j]; q < in.rowptr[j + 1]; ++q) s.spill[in.colidx[q]] = 1;
     s.n_spill_rows = std::accumulate(s.spill.begin(), s.spill.end(), (int64_t)0);
-    s.tile_spill_ptr.assign(1, 0);
+    // ---- per-tile blocks (see TileDesc) ---------------------------------------------------
+    s.tile_desc.resize((size_t)nt);
     for (int64_t vt = 0; vt < nt; ++vt) {
-        for (int64_t q = s.tile_first_ptr[vt]; q < s.tile_first_ptr[vt + 1]; ++q) {
-            if (s.spill[s.first_rows[q]]) {
-                s.spill_local.push_back((int32_t)(q - s.tile_first_ptr[vt]));
-                s.spill_row.push_back(s.first_rows[q]);
-            }
+        const int64_t f0 = s.tile_first_ptr[vt], f1 = s.tile_first_ptr[vt + 1];
+        TileBlock &tb = blocks[(size_t)vt];
+        const size_t first_bytes = (size_t)round_up(f1 - f0, 16) * 4;
+        TileDesc &d = s.tile_desc[(size_t)vt];
+        d.meta_off = (int64_t)s.tile_meta.size();
+        d.n_rows = (int32_t)(f1 - f0);
+        d.n_units = tb.n_units;
+        d.n_second = (int32_t)tb.rows.size();
+        d.n_entries = tb.n_entries;
+        d.s_bytes = (int32_t)tb.bytes.size();
+        d.reserved = 0;
+        s.tile_meta.resize(s.tile_meta.size() + first_bytes + tb.bytes.size(), 0);
+        unsigned char *m = s.tile_meta.data() + d.meta_off;
+        int32_t *first = reinterpret_cast<int32_t *>(m);
+        for (int64_t q = f0; q < f1; ++q) {
+            const int32_t row = s.first_rows[q];
+            first[q - f0] = (int32_t)((uint32_t)row | (s.spill[row] ? kSpillBit : 0u));
         }
-        s.tile_spill_ptr.push_back((int32_t)s.spill_local.size());
+        for (int64_t q = f1 - f0; q < (int64_t)(first_bytes / 4); ++q) first[q] = s.first_rows[f1 - 1];
+        if (!tb.bytes.empty()) std::memcpy(m + first_bytes, tb.bytes.data(), tb.bytes.size());
+        s.second_block_cap = std::max<int64_t>(s.second_block_cap, (int64_t)tb.bytes.size());
+        TileBlock().bytes.swap(tb.bytes);
+    }
+    s.tile_meta.resize(s.tile_meta.size() + 64, 0);      // the kernels may read one piece past an empty block
+    {
+        // LDS actually needed with the second-phase blocks staged: everything but the estimate
+        const int64_t rows_cap = round_up(s.max_tile_rows, s.lds_row_granule);
+        const int64_t need = s.lds_fixed_bytes + s.second_block_cap +
+                             rows_cap * (s.lds_bytes_per_row - s.lds_meta_bytes_per_row + 8);
+        s.second_block_in_lds = need <= s.fast_mem_bytes;
     }
 
     // ---- balance: units of the second wavefront, and of the unfused baseline ------------

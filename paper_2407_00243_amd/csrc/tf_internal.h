@@ -17,7 +17,6 @@ constexpr int kUnitRows = 64;            // most rows in one unit of a packed ro
 constexpr int kUnitSlots = 4096;         // most padded entries (rows x slots) in one such unit
 constexpr int kSplitMinSlots = 128;      // rows at least this long are split over several lane groups
 constexpr int kSplitPartSlots = 96;      // target slots per part of a split row
-constexpr int kTileUnitRows = 128;       // most rows in one unit of a fused tile's second phase
 constexpr uint32_t kSpillBit = 0x80000000u;
 
 // Lanes that share one row in the gather kernels: each lane owns vv columns (vv = elements per
@@ -58,6 +57,74 @@ inline int64_t lds_fixed_bytes(int dtype, int b_is_sparse, int bcol, int cs) {
 }
 inline int lds_row_granule(int b_is_sparse) { return b_is_sparse ? 1 : kRowGranuleDense; }
 
+// Whether a wave of the dense-B kernels keeps its operands of the C slice in registers: only for
+// the specialised shallow depths (ks = bCol / (4 * elements per 16 bytes) steps, nb accumulator
+// blocks) and at most 64 registers' worth (32 for fp64, whose B buffers are twice as large).
+// The C slice then needs no LDS.
+constexpr bool c_in_registers(int dtype, int nb, int ks) {
+    return (ks == 2 || ks == 4) &&
+           ks * (dtype == TF_F64 ? 2 : 4) * nb * (dtype == TF_F64 ? 2 : 1) <= (dtype == TF_F64 ? 32 : 64);
+}
+// ks as the kernels specialise it: 0 = generic loop over k.
+inline int mfma_ksteps_special(int dtype, int bcol, int ccol, int cs) {
+    const int v = dtype == TF_F64 ? 2 : 4;
+    if (bcol % v || ccol % v || cs % v || bcol % (4 * v)) return 0;
+    const int ks = bcol / (4 * v);
+    return (ks == 2 || ks == 4 || ks == 8 || ks == 16) ? ks : 0;
+}
+
+// What a fused workgroup needs to know about one tile, as one contiguous block of bytes in
+// device memory plus this fixed-size descriptor, so that nothing in the tile waits for a chain
+// of dependent loads (row list -> unit -> entries).  The block, 16-byte aligned, holds
+//   int32    first[round_up(n_rows, 16)]   row ids of the tile's D1 rows, bit 31 = spill;
+//                                          padding repeats the last row without the bit
+// followed by the second-phase block of s_bytes bytes (each array padded to 16 bytes):
+//   TileUnit units[n_units]
+//   int32    rows2[n_second]               row ids of the fused rows of D, unit after unit
+//   uint16   idx[n_entries]                tile-local column index of every packed entry
+//   T        val[n_entries]
+struct TileDesc {
+    int64_t meta_off;      // byte offset of the block
+    int32_t n_rows;        // D1 rows the tile produces
+    int32_t n_units;
+    int32_t n_second;      // fused rows of D
+    int32_t n_entries;     // padded entries over all units
+    int32_t s_bytes;       // size of the second-phase block
+    int32_t reserved;
+};
+struct TileUnit {          // n_rows rows of `stride` entry slots each, from entry_base on
+    int32_t entry_base;    // even
+    int32_t row_begin;     // position of the unit's first row in rows2
+    int32_t n_rows;
+    int32_t slots;         // stride (even, low 16 bits) | real length of the longest row (high 16 bits)
+};
+
+// Dynamic LDS of a fused workgroup: two buffers of row ids (this tile's and the next one's),
+// the staged second-phase block (s_lds bytes, 0 when it is read in place), the C slice unless
+// the waves hold it in registers, the D1 tile.
+struct FusedLdsLayout {
+    int64_t first0, first1, second, cslice, tile, total;
+};
+inline FusedLdsLayout fused_lds_layout(int dtype, int b_is_sparse, int bcol, int ccol, int cs,
+                                       int rows_cap, int s_lds) {
+    FusedLdsLayout l{};
+    const int es = elem_size(dtype);
+    l.first0 = 0;
+    l.first1 = (int64_t)rows_cap * 4;
+    l.second = 2 * (int64_t)rows_cap * 4;
+    l.cslice = l.second + round_up(s_lds, 16);
+    const int64_t cbytes = lds_fixed_bytes(dtype, b_is_sparse, bcol, cs);
+    const bool c_regs = !b_is_sparse && c_in_registers(dtype, mfma_blocks(cs),
+                                                       mfma_ksteps_special(dtype, bcol, ccol, cs));
+    l.tile = l.cslice + (c_regs ? 0 : cbytes);
+    l.total = l.tile + (int64_t)rows_cap * lds_ldl(dtype, b_is_sparse, cs) * es;
+    return l;
+}
+inline int64_t fused_lds_bytes(int dtype, int b_is_sparse, int bcol, int ccol, int cs, int rows_cap,
+                               int s_lds) {
+    return fused_lds_layout(dtype, b_is_sparse, bcol, ccol, cs, rows_cap, s_lds).total;
+}
+
 // One unit of a packed row list: n_rows rows, all padded to `slots` entries, stored row after
 // row from entry_base on.  split > 1: every row is shared by `split` lane groups, each summing
 // a contiguous part of the slots.
@@ -92,9 +159,11 @@ struct Schedule {
     std::vector<int32_t> tile_second_ptr, second_rows;
     std::vector<int32_t> wf1_unit_ptr, wf1_rows;
     std::vector<uint8_t> spill;
-    RowPack fused;                 // second_rows re-packed with tile-local column indices
-    std::vector<int32_t> tile_unit_ptr;                   // units of `fused` per tile
-    std::vector<int32_t> tile_spill_ptr, spill_local, spill_row;   // spilled rows per tile
+    std::vector<TileDesc> tile_desc;                      // one per tile, see TileDesc
+    std::vector<unsigned char> tile_meta;                 // the tiles' blocks, back to back
+    int64_t second_block_cap = 0;                         // largest second-phase block, bytes
+    bool second_block_in_lds = true;                      // it fits beside the largest tile
+    int64_t lds_meta_bytes_per_row = 0;                   // part of lds_bytes_per_row: row ids + estimate of the second-phase block
     RowPack wf1;                   // wf1_rows re-packed
     RowPack all;                   // all rows re-packed (unfused baseline)
     int64_t n_fused_rows = 0, n_spill_rows = 0, fused_nnz = 0;
@@ -139,13 +208,12 @@ struct PackDev {
 struct FusedLaunch {
     int32_t dtype;
     int32_t n_tiles, n_slices, cs, ccol, bcol;
-    int32_t max_tile_rows;            // largest tile, in rows
+    int32_t rows_cap;                 // largest tile, in rows, rounded up to the row granule
+    int32_t s_cap;                    // largest second-phase block, bytes (multiple of 16)
+    int32_t s_in_lds;                 // 1: second-phase blocks are staged in LDS, 0: read in place
     int64_t lds_bytes;                // dynamic LDS of the launch
-    const int32_t *tile_first_ptr, *first_rows_enc;   // first_rows with kSpillBit
-    const int32_t *tile_spill_ptr;    // per tile: its spilled rows, as (tile-local index, row id)
-    const int32_t *spill_local, *spill_row;
-    const int32_t *tile_unit_ptr;     // second phase: units of `second` per tile
-    PackDev second;                   // uint16 tile-local indices
+    const TileDesc *tile_desc;
+    const unsigned char *tile_meta;
     const void *B;                    // dense B (gemm) or nullptr
     CsrDev Bs;                        // sparse B (spmm)
     const void *C;

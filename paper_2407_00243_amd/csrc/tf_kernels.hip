@@ -17,6 +17,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cstdlib>
 #include <type_traits>
 
 #include "tf_internal.h"
@@ -144,14 +145,43 @@ __device__ __forceinline__ void stage_c_slice(T *Cl, const T *__restrict__ C, in
     constexpr int V = Tr<T>::V, KC = 4 * V;
     const int ksteps = (bcol + KC - 1) / KC;
     const int total = ksteps * V * NB * 64;
-    for (int e = threadIdx.x; e < total; e += blockDim.x) {
-        const int l = e & 63;
-        const int rest = e >> 6;
-        const int nb = rest % NB;
-        const int sq = rest / NB;
-        const int k = KC * (sq / V) + V * (l >> 4) + (sq % V);
-        const int col = 16 * nb + Tr<T>::col_of_m(l & 15);
-        Cl[e] = (k < bcol && col < w) ? C[(int64_t)k * ccol + c0 + col] : T(0);
+    constexpr int U = 8;                                  // loads in flight per thread
+    for (int e0 = threadIdx.x; e0 < total; e0 += U * (int)blockDim.x) {
+        T tmp[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int e = e0 + u * (int)blockDim.x;
+            const int l = e & 63;
+            const int rest = e >> 6;
+            const int nb = rest % NB;
+            const int sq = rest / NB;
+            const int k = KC * (sq / V) + V * (l >> 4) + (sq % V);
+            const int col = 16 * nb + Tr<T>::col_of_m(l & 15);
+            const bool in = e < total && k < bcol && col < w;
+            tmp[u] = C[in ? (int64_t)k * ccol + c0 + col : 0];
+            if (!in) tmp[u] = T(0);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int e = e0 + u * (int)blockDim.x;
+            if (e < total) Cl[e] = tmp[u];
+        }
+    }
+}
+
+// The operands of the C slice that one lane feeds to the MFMAs, straight from device memory
+// (what stage_c_slice would put at Cl[i * 64 + lane]); bCol = KC * KS exactly.
+template <typename T, int NB, int KS>
+__device__ __forceinline__ void load_c_regs(T (&creg)[KS * Tr<T>::V * NB], const T *__restrict__ C,
+                                            int ccol, int c0, int w, int lane) {
+    constexpr int V = Tr<T>::V, KC = 4 * V;
+#pragma unroll
+    for (int i = 0; i < KS * V * NB; ++i) {
+        const int nb = i % NB, sq = i / NB;
+        const int k = KC * (sq / V) + V * (lane >> 4) + (sq % V);
+        const int col = 16 * nb + Tr<T>::col_of_m(lane & 15);
+        creg[i] = C[col < w ? (int64_t)k * ccol + c0 + col : 0];
+        if (col >= w) creg[i] = T(0);
     }
 }
 
@@ -391,30 +421,6 @@ __device__ __forceinline__ void unit_rows(const UnitDesc d, const int32_t *__res
     }
 }
 
-// Second phase of a fused tile: rows of D whose D1 operands all sit in the LDS tile.
-template <typename T, bool FAST>
-__device__ __forceinline__ void fused_second_phase(const FusedLaunch &a, const T *tileD1, int ldl,
-                                                   int tile, int c0, int w) {
-    constexpr int VV = FAST ? Tr<T>::V : 1;
-    const int G = pow2_at_least((a.cs + VV - 1) / VV);
-    const int gl = threadIdx.x % G, grp = threadIdx.x / G, ngrp = blockDim.x / G;
-    if (VV * gl >= w) return;
-    const UnitDesc *__restrict__ units = a.second.units;
-    const int32_t *__restrict__ rows = a.second.rows;
-    const uint16_t *__restrict__ idx = static_cast<const uint16_t *>(a.second.idx);
-    const T *__restrict__ val = static_cast<const T *>(a.second.vals);
-    T *__restrict__ D = static_cast<T *>(a.D);
-    const int ccol = a.ccol;
-    const int u1 = a.tile_unit_ptr[tile + 1];
-    for (int u = a.tile_unit_ptr[tile]; u < u1; ++u) {
-        unit_rows<T, VV, uint16_t, kRowsPerPass, kEntriesPerPass, false>(
-            units[u], rows, idx, val, tileD1, (uint32_t)ldl, (uint32_t)(VV * gl), grp, ngrp,
-            [&](int32_t j, const T(&acc)[VV]) {
-                store_pack<T, VV>(D + (int64_t)j * ccol + c0 + VV * gl, acc);
-            });
-    }
-}
-
 extern __shared__ __align__(16) unsigned char tf_smem[];
 
 // B operand of one 16-row block, all k: KS vectors of V elements per lane.
@@ -463,11 +469,7 @@ __device__ __forceinline__ void mfma_frag_reg(typename Tr<T>::Acc (&acc)[NB],
                 acc[nb] = mfma16(creg[(s * V + q) * NB + nb], f.v[s][q], acc[nb]);
 }
 
-// Whether a wave keeps its C operands in registers: shallow k and at most 64 VGPRs' worth
-// (32 for fp64, whose prefetch buffers are twice as large).
-template <typename T, int NB, int KS> constexpr bool c_in_registers() {
-    return KS > 0 && KS <= 4 && KS * Tr<T>::V * NB * (int)(sizeof(T) / 4) <= (sizeof(T) == 4 ? 64 : 32);
-}
+template <typename T> constexpr int dtype_of() { return sizeof(T) == 8 ? TF_F64 : TF_F32; }
 
 // Which tiles a fused workgroup works on.  Workgroups are persistent: workgroup b sits on XCD
 // b % 8 (consecutive ids are dealt round-robin to the XCDs), keeps one column slice for its
@@ -487,92 +489,262 @@ __device__ __forceinline__ TileWalk tile_walk(int n_tiles, int n_slices) {
     return t;
 }
 
-// Spilled rows of a tile: copied from the LDS tile to the D1 workspace, whole rows at a time.
+// LDS of a fused workgroup, as laid out by fused_lds_layout.
+struct FusedSmem {
+    int32_t *first[2];            // row ids (bit 31 = spill) of the current and of the next tile
+    unsigned char *second;        // staged second-phase block (or unused)
+    unsigned char *cslice;
+    unsigned char *tile;
+};
+__device__ __forceinline__ FusedSmem fused_smem(const FusedLaunch &a, bool c_regs, int64_t cbytes) {
+    FusedSmem m;
+    m.first[0] = reinterpret_cast<int32_t *>(tf_smem);
+    m.first[1] = m.first[0] + a.rows_cap;
+    m.second = tf_smem + 2 * (int64_t)a.rows_cap * 4;
+    m.cslice = m.second + (a.s_in_lds ? a.s_cap : 0);
+    m.tile = m.cslice + (c_regs ? 0 : cbytes);
+    return m;
+}
+
+// Copies of a tile's block on their way from device memory to LDS: issued early, written late.
+// NS 16-byte pieces per thread cover 16 NS bytes per thread of the workgroup; what is beyond that is
+// copied by a plain loop at the time of writing.
+typedef Pack<int32_t, 4> Piece;
+template <int NS> struct Staged {
+    Piece v[NS];
+};
+template <int NS>
+__device__ __forceinline__ void stage_issue(Staged<NS> &st, const unsigned char *src, int bytes) {
+    const Piece *p = reinterpret_cast<const Piece *>(src);
+    const int n = bytes >> 4;
+#pragma unroll
+    for (int i = 0; i < NS; ++i) {
+        const int e = threadIdx.x + i * (int)blockDim.x;
+        st.v[i] = p[e < n ? e : 0];          // unconditional: the values stay in registers
+    }
+}
+template <int NS>
+__device__ __forceinline__ void stage_write(const Staged<NS> &st, unsigned char *dst,
+                                            const unsigned char *src, int bytes) {
+    Piece *q = reinterpret_cast<Piece *>(dst);
+    const Piece *p = reinterpret_cast<const Piece *>(src);
+    const int n = bytes >> 4;
+#pragma unroll
+    for (int i = 0; i < NS; ++i) {
+        const int e = threadIdx.x + i * (int)blockDim.x;
+        if (e < n) q[e] = st.v[i];
+    }
+    for (int e = threadIdx.x + NS * (int)blockDim.x; e < n; e += (int)blockDim.x) q[e] = p[e];
+}
+
+// The arrays of a second-phase block.
+template <typename T> struct SecondBlock {
+    const TileUnit *units;
+    const int32_t *rows2;
+    const uint16_t *idx;
+    const T *val;
+};
+template <typename T>
+__device__ __forceinline__ SecondBlock<T> second_block(const unsigned char *sb, const TileDesc &d) {
+    SecondBlock<T> b;
+    const int off_rows2 = (d.n_units * (int)sizeof(TileUnit) + 15) & ~15;
+    const int off_idx = (off_rows2 + d.n_second * 4 + 15) & ~15;
+    const int off_val = (off_idx + d.n_entries * 2 + 15) & ~15;
+    b.units = reinterpret_cast<const TileUnit *>(sb);
+    b.rows2 = reinterpret_cast<const int32_t *>(sb + off_rows2);
+    b.idx = reinterpret_cast<const uint16_t *>(sb + off_idx);
+    b.val = reinterpret_cast<const T *>(sb + off_val);
+    return b;
+}
+
+// After the tile's D1 rows are complete in LDS: copies the spilled rows to the D1 workspace
+// and computes the tile's fused rows of D, all operands out of LDS.  Lane group grp of ngrp owns
+// the rows grp, grp + ngrp, ...; lane gl of the group owns VV columns from VV gl on.
+//
+// A unit's rows all have `stride` entry slots (even; the real length `len` may be one less)
+// and are walked R rows at a time, two slots per step.  Nothing but LDS latency limits this
+// loop, so the entries (index pair, value pair) of the next step are read while the operands of
+// the current step are on their way.
 template <typename T, int VV>
-__device__ __forceinline__ void spill_rows(const FusedLaunch &a, const T *tileD1, int ldl, int tile,
-                                           int c0, int gl, int grp, int ngrp) {
-    const int s0 = a.tile_spill_ptr[tile], ns = a.tile_spill_ptr[tile + 1] - s0;
-    const int32_t *__restrict__ sl = a.spill_local + s0;
-    const int32_t *__restrict__ sr = a.spill_row + s0;
-    T *__restrict__ D1 = static_cast<T *>(a.D1);
-    constexpr int R = 4;
-    for (int i0 = grp; i0 < ns; i0 += ngrp * R) {
-        int lr[R];
-        int64_t row[R];
+__device__ __forceinline__ void fused_tail(const FusedLaunch &a, const TileDesc &d,
+                                           const int32_t *first, const unsigned char *sb,
+                                           const T *tileD1, int ldl, int c0, int gl, int grp,
+                                           int ngrp) {
+    const int ccol = a.ccol;
+    const uint32_t lane_off = (uint32_t)(VV * gl);
+    {
+        constexpr int RS = 8;
+        T *__restrict__ D1 = static_cast<T *>(a.D1);
+        const int rows = d.n_rows;
+        for (int i0 = grp; i0 < rows; i0 += ngrp * RS) {
+            uint32_t enc[RS];
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const int i = i0 + r * ngrp < ns ? i0 + r * ngrp : i0;
-            lr[r] = sl[i];
-            row[r] = sr[i];
+            for (int r = 0; r < RS; ++r) {
+                const int i = i0 + r * ngrp;
+                enc[r] = i < rows ? (uint32_t)first[i] : 0u;
+            }
+            T x[RS][VV];
+#pragma unroll
+            for (int r = 0; r < RS; ++r)
+                if (enc[r] & kSpillBit) load_pack<T, VV>(x[r], tileD1 + (i0 + r * ngrp) * ldl + lane_off);
+#pragma unroll
+            for (int r = 0; r < RS; ++r)
+                if (enc[r] & kSpillBit)
+                    store_pack<T, VV>(D1 + (int64_t)(enc[r] & ~kSpillBit) * ccol + c0 + lane_off, x[r]);
         }
-        T x[R][VV];
+    }
+    constexpr int R = 4;
+    const SecondBlock<T> b = second_block<T>(sb, d);
+    T *__restrict__ D = static_cast<T *>(a.D);
+    typedef Pack<uint16_t, 2> IdxPair;
+    typedef Pack<T, 2> ValPair;
+    for (int u = 0; u < d.n_units; ++u) {
+        const TileUnit un = b.units[u];
+        const int stride = un.slots & 0xffff, len = un.slots >> 16;
+        const int S = stride >> 1;                                   // steps per row
+        const int KB = (un.n_rows + ngrp * R - 1) / (ngrp * R);      // row blocks, wave-uniform
+        const IdxPair *ip = reinterpret_cast<const IdxPair *>(b.idx + un.entry_base);
+        const ValPair *vp = reinterpret_cast<const ValPair *>(b.val + un.entry_base);
+        // entry pair of row block kb, step sp; rows past the unit's end re-read its last row
+        auto row_at = [&](int kb, int r) {
+            const int i = grp + (kb * R + r) * ngrp;
+            return i < un.n_rows ? i : un.n_rows - 1;
+        };
+        IdxPair cn[R];
+        ValPair vn[R];
+        auto read_entries = [&](int kb, int sp) {
 #pragma unroll
-        for (int r = 0; r < R; ++r) load_pack<T, VV>(x[r], tileD1 + lr[r] * ldl + VV * gl);
+            for (int r = 0; r < R; ++r) {
+                const int at = row_at(kb, r) * S + sp;
+                cn[r] = ip[at];
+                vn[r] = vp[at];
+            }
+        };
+        if (S > 0) read_entries(0, 0);
+        for (int kb = 0; kb < KB; ++kb) {
+            int32_t rid[R];
 #pragma unroll
-        for (int r = 0; r < R; ++r)
-            if (i0 + r * ngrp < ns) store_pack<T, VV>(D1 + row[r] * a.ccol + c0 + VV * gl, x[r]);
+            for (int r = 0; r < R; ++r) rid[r] = b.rows2[un.row_begin + row_at(kb, r)];
+            T acc[R][VV];
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int i = 0; i < VV; ++i) acc[r][i] = T(0);
+            for (int sp = 0; sp < S; ++sp) {
+                IdxPair c[R];
+                ValPair v[R];
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    c[r] = cn[r];
+                    v[r] = vn[r];
+                }
+                const bool two = 2 * sp + 1 < len;
+                T x[R][2][VV];
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    load_pack<T, VV>(x[r][0], tileD1 + (uint32_t)c[r].x[0] * (uint32_t)ldl + lane_off);
+                    if (two) load_pack<T, VV>(x[r][1], tileD1 + (uint32_t)c[r].x[1] * (uint32_t)ldl + lane_off);
+                }
+                // next step of this row block, or the first step of the next one
+                int nsp = sp + 1, nkb = kb;
+                if (nsp == S) {
+                    nsp = 0;
+                    nkb = kb + 1;
+                }
+                if (nkb < KB) read_entries(nkb, nsp);
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+#pragma unroll
+                    for (int i = 0; i < VV; ++i) acc[r][i] += v[r].x[0] * x[r][0][i];
+                    if (two) {
+#pragma unroll
+                        for (int i = 0; i < VV; ++i) acc[r][i] += v[r].x[1] * x[r][1][i];
+                    }
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+                if (grp + (kb * R + r) * ngrp < un.n_rows)
+                    store_pack<T, VV>(D + (int64_t)rid[r] * ccol + c0 + lane_off, acc[r]);
+        }
     }
 }
 
-// First wavefront, dense B.  Per tile: phase 1 multiplies the tile's rows of B by the C slice
-// with MFMA into the LDS tile; after a barrier phase 2 copies the spilled rows to the D1
-// workspace and computes the tile's fused rows of D out of LDS.
-// KS > 0: bCol = 4 V KS exactly, and the B rows of the next 16-row block (also the first block
-// of the workgroup's next tile) are in flight while the current block is multiplied;
-// KS = 0: any bCol, no prefetch.
-template <typename T, int NB, int KS, bool FAST>
+constexpr int kStagePieces = 3;     // 16-byte pieces of a second-phase block in flight per thread
+
+// First wavefront, dense B.  A workgroup walks through its tiles; per tile
+//   phase 1  multiplies the tile's rows of B by the C slice with MFMA into the LDS tile, while
+//            the tile's second-phase block and the next tile's row ids travel to LDS;
+//   barrier;
+//   phase 2  starts the loads of the next tile's first rows of B, copies the spilled rows to
+//            the D1 workspace and computes the tile's fused rows of D out of LDS;
+//   barrier (the LDS tile is rewritten by the next tile).
+// KS > 0: bCol = 4 V KS exactly and the B rows of the next two 16-row blocks of a wave are in
+// flight while the current block is multiplied; KS = 0: any bCol, no prefetch.
+// SLDS: the second-phase blocks are staged in LDS (else they are read where they are).
+template <typename T, int NB, int KS, bool FAST, bool SLDS>
 __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLaunch a) {
     constexpr int V = Tr<T>::V, KC = 4 * V;
     constexpr int VV = FAST ? V : 1;
     constexpr int KSF = KS > 0 ? KS : 1;
-    constexpr bool CREG = c_in_registers<T, NB, KS>();
+    constexpr bool CREG = c_in_registers(dtype_of<T>(), NB, KS);
     TileWalk tw = tile_walk(a.n_tiles, a.n_slices);
     if (tw.tile >= tw.tile_end) return;
     const int c0 = tw.slice * a.cs;
     const int w = min(a.cs, a.ccol - c0);
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int nwaves = (int)blockDim.x >> 6;
     const int g = lane >> 4, r = lane & 15;
     const int bcol_pad = (a.bcol + KC - 1) / KC * KC;
     const int csv = (a.cs + V - 1) / V * V;
     const int ldl = csv + V;
-    T *Cl = reinterpret_cast<T *>(tf_smem);
-    T *tileD1 = Cl + (int64_t)bcol_pad * 16 * NB;
+    const FusedSmem sm = fused_smem(a, CREG, (int64_t)bcol_pad * 16 * NB * (int64_t)sizeof(T));
+    T *Cl = reinterpret_cast<T *>(sm.cslice);
+    T *tileD1 = reinterpret_cast<T *>(sm.tile);
     const T *__restrict__ B = static_cast<const T *>(a.B);
     const int G = pow2_at_least((a.cs + VV - 1) / VV);
-    const int gl = threadIdx.x % G, grp = threadIdx.x / G, ngrp = blockDim.x / G;
+    const int gl = threadIdx.x % G, grp = threadIdx.x / G, ngrp = (int)blockDim.x / G;
 
-    // this lane's row (and spill flag, unused here) in block lb of a tile; padding lanes and
-    // blocks past the end name the tile's last row, so that every load is unconditional
-    auto row_of = [&](const int32_t *__restrict__ first, int rows, int lb) -> int64_t {
+    // row of B behind lane r of block lb; blocks past the end of the tile name its last row, so
+    // that every load is unconditional (first[] is padded to a multiple of 16 rows)
+    auto row_of = [&](const int32_t *first, int rows, int lb) -> int64_t {
         const int lr = lb * 16 + r;
         return (int64_t)((uint32_t)first[lr < rows ? lr : rows - 1] & ~kSpillBit);
     };
 
-    int fp0 = a.tile_first_ptr[tw.tile];
-    int rows = a.tile_first_ptr[tw.tile + 1] - fp0;
-    BFrag<T, KSF> cur, nxt;
-    int64_t row_nxt = 0;
-    if constexpr (KS > 0) {
-        // first block of the first tile: on its way while the C slice is staged
-        load_b_frag<T, KSF>(cur, B + row_of(a.first_rows_enc + fp0, rows, wave) * a.bcol, g);
-        row_nxt = row_of(a.first_rows_enc + fp0, rows, wave + nwaves);
+    TileDesc d = a.tile_desc[tw.tile];
+    int par = 0;
+    {
+        // row ids of the first tile
+        const int n16 = (d.n_rows + 15) & ~15;
+        const int32_t *src = reinterpret_cast<const int32_t *>(a.tile_meta + d.meta_off);
+        for (int e = threadIdx.x; e < n16; e += (int)blockDim.x) sm.first[0][e] = src[e];
     }
-    stage_c_slice<T, NB>(Cl, static_cast<const T *>(a.C), a.bcol, a.ccol, c0, w);
-    __syncthreads();
     T creg[CREG ? KSF * V * NB : 1];
-    if constexpr (CREG) {
-#pragma unroll
-        for (int i = 0; i < KSF * V * NB; ++i) creg[i] = Cl[i * 64 + lane];
+    if constexpr (CREG) load_c_regs<T, NB, KSF>(creg, static_cast<const T *>(a.C), a.ccol, c0, w, lane);
+    else stage_c_slice<T, NB>(Cl, static_cast<const T *>(a.C), a.bcol, a.ccol, c0, w);
+    __syncthreads();
+    BFrag<T, KSF> f0, f1, f2;
+    if constexpr (KS > 0) {
+        load_b_frag<T, KSF>(f0, B + row_of(sm.first[0], d.n_rows, wave) * a.bcol, g);
+        load_b_frag<T, KSF>(f1, B + row_of(sm.first[0], d.n_rows, wave + nwaves) * a.bcol, g);
     }
 
-    for (; tw.tile < tw.tile_end; tw.tile += tw.step) {
-        const int32_t *__restrict__ first = a.first_rows_enc + fp0;
+    for (;;) {
+        const int rows = d.n_rows;
+        const int32_t *first = sm.first[0] + par * a.rows_cap;
         const int nblk = (rows + 15) >> 4;
-        // the workgroup's next tile (if any): its first block is prefetched at the end of phase 1
         const int ntile = tw.tile + tw.step;
         const bool has_next = ntile < tw.tile_end;
-        const int nfp0 = has_next ? a.tile_first_ptr[ntile] : fp0;
-        const int nrows = has_next ? a.tile_first_ptr[ntile + 1] - nfp0 : rows;
+        const TileDesc nd = a.tile_desc[has_next ? ntile : tw.tile];
+        const unsigned char *blk = a.tile_meta + d.meta_off + (((int64_t)rows + 15) & ~15) * 4;
+
+        // on their way during phase 1: this tile's second-phase block, the next tile's row ids
+        Staged<kStagePieces> st;
+        const int nfirst_pieces = has_next ? ((nd.n_rows + 15) >> 4) * 4 : 0;
+        if constexpr (SLDS) stage_issue<kStagePieces>(st, blk, d.s_bytes);
+        const Piece nfirst = reinterpret_cast<const Piece *>(
+            a.tile_meta + nd.meta_off)[(int)threadIdx.x < nfirst_pieces ? threadIdx.x : 0];
 
         auto write_block = [&](int lb, typename Tr<T>::Acc(&acc)[NB]) {
             const int lr = lb * 16 + r;
@@ -584,20 +756,14 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
         };
         if constexpr (KS > 0) {
             for (int lb = wave; lb < nblk; lb += nwaves) {
-                const int64_t row_nn = row_of(first, rows, lb + 2 * nwaves);
-                load_b_frag<T, KSF>(nxt, B + row_nxt * a.bcol, g);
+                load_b_frag<T, KSF>(f2, B + row_of(first, rows, lb + 2 * nwaves) * a.bcol, g);
                 __builtin_amdgcn_sched_barrier(0);      // keep the prefetch ahead of the MFMAs
                 typename Tr<T>::Acc acc[NB];
-                if constexpr (CREG) mfma_frag_reg<T, NB, KSF>(acc, creg, cur);
-                else mfma_frag<T, NB, KSF>(acc, Cl, cur, lane);
+                if constexpr (CREG) mfma_frag_reg<T, NB, KSF>(acc, creg, f0);
+                else mfma_frag<T, NB, KSF>(acc, Cl, f0, lane);
                 write_block(lb, acc);
-                cur = nxt;
-                row_nxt = row_nn;
-            }
-            if (has_next) {
-                // first block of the next tile: on its way during this tile's second phase
-                load_b_frag<T, KSF>(cur, B + row_of(a.first_rows_enc + nfp0, nrows, wave) * a.bcol, g);
-                row_nxt = row_of(a.first_rows_enc + nfp0, nrows, wave + nwaves);
+                f0 = f1;
+                f1 = f2;
             }
         } else {
             for (int lb = wave; lb < nblk; lb += nwaves) {
@@ -607,44 +773,90 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
                 write_block(lb, acc);
             }
         }
+        if constexpr (SLDS) stage_write<kStagePieces>(st, sm.second, blk, d.s_bytes);
+        if ((int)threadIdx.x < nfirst_pieces)
+            reinterpret_cast<Piece *>((sm.first[0] + (par ^ 1) * a.rows_cap))[threadIdx.x] = nfirst;
+        for (int e = (int)blockDim.x + threadIdx.x; e < nfirst_pieces; e += (int)blockDim.x)
+            reinterpret_cast<Piece *>((sm.first[0] + (par ^ 1) * a.rows_cap))[e] =
+                reinterpret_cast<const Piece *>(a.tile_meta + nd.meta_off)[e];
         __syncthreads();
-        if (VV * gl < w) spill_rows<T, VV>(a, tileD1, ldl, tw.tile, c0, gl, grp, ngrp);
-        fused_second_phase<T, FAST>(a, tileD1, ldl, tw.tile, c0, w);
-        if (has_next) __syncthreads();      // the LDS tile is rewritten by the next tile
-        fp0 = nfp0;
-        rows = nrows;
+        if constexpr (KS > 0) {
+            if (has_next) {
+                // first two blocks of the next tile: on their way during this tile's second phase
+                load_b_frag<T, KSF>(f0, B + row_of((sm.first[0] + (par ^ 1) * a.rows_cap), nd.n_rows, wave) * a.bcol, g);
+                load_b_frag<T, KSF>(f1, B + row_of((sm.first[0] + (par ^ 1) * a.rows_cap), nd.n_rows, wave + nwaves) * a.bcol, g);
+            }
+        }
+        if (VV * gl < w)
+            fused_tail<T, VV>(a, d, first, SLDS ? sm.second : blk, tileD1, ldl, c0, gl, grp, ngrp);
+        if (!has_next) break;
+        __syncthreads();
+        d = nd;
+        tw.tile = ntile;
+        par ^= 1;
     }
 }
 
-template <typename T, bool FAST>
+// First wavefront, CSR B: phase 1 gathers rows of C for the tile's rows of B into the LDS tile.
+template <typename T, bool FAST, bool SLDS>
 __global__ __launch_bounds__(kFusedThreads) void k_fused_spmm_spmm(const FusedLaunch a) {
     constexpr int VV = FAST ? Tr<T>::V : 1;
-    int tile, slice;
-    if (!tile_and_slice(blockIdx.x, a.n_tiles, a.n_slices, tile, slice)) return;
-    const int c0 = slice * a.cs;
+    TileWalk tw = tile_walk(a.n_tiles, a.n_slices);
+    if (tw.tile >= tw.tile_end) return;
+    const int c0 = tw.slice * a.cs;
     const int w = min(a.cs, a.ccol - c0);
     const int ldl = (a.cs + Tr<T>::V - 1) / Tr<T>::V * Tr<T>::V;
-    T *tileD1 = reinterpret_cast<T *>(tf_smem);
-
+    const FusedSmem sm = fused_smem(a, true, 0);
+    T *tileD1 = reinterpret_cast<T *>(sm.tile);
     const int G = pow2_at_least((a.cs + VV - 1) / VV);
-    const int gl = threadIdx.x % G, grp = threadIdx.x / G, ngrp = blockDim.x / G;
-    const int fp0 = a.tile_first_ptr[tile];
-    const int rows = a.tile_first_ptr[tile + 1] - fp0;
+    const int gl = threadIdx.x % G, grp = threadIdx.x / G, ngrp = (int)blockDim.x / G;
     const T *__restrict__ bvals = static_cast<const T *>(a.Bs.vals);
     const T *__restrict__ C = static_cast<const T *>(a.C);
-    T *__restrict__ D1 = static_cast<T *>(a.D1);
-    const int32_t *__restrict__ first = a.first_rows_enc + fp0;
     const int ccol = a.ccol;
-    gather_rows<T, VV, int32_t, kRowsPerPass, kEntriesPerPass>(
-        grp, rows, ngrp, a.Bs.rowptr, a.Bs.colidx, bvals, C + c0 + VV * gl, ccol, VV * gl < w,
-        [&](int pos) { return (int32_t)((uint32_t)first[pos] & ~kSpillBit); },
-        [&](int pos, int64_t row, const T(&acc)[VV]) {
-            store_pack<T, VV>(tileD1 + (int64_t)pos * ldl + VV * gl, acc);
-            if ((uint32_t)first[pos] & kSpillBit)
-                store_pack<T, VV>(D1 + row * ccol + c0 + VV * gl, acc);
-        });
+
+    TileDesc d = a.tile_desc[tw.tile];
+    int par = 0;
+    {
+        const int n16 = (d.n_rows + 15) & ~15;
+        const int32_t *src = reinterpret_cast<const int32_t *>(a.tile_meta + d.meta_off);
+        for (int e = threadIdx.x; e < n16; e += (int)blockDim.x) sm.first[0][e] = src[e];
+    }
     __syncthreads();
-    fused_second_phase<T, FAST>(a, tileD1, ldl, tile, c0, w);
+    for (;;) {
+        const int rows = d.n_rows;
+        const int32_t *first = sm.first[0] + par * a.rows_cap;
+        const int ntile = tw.tile + tw.step;
+        const bool has_next = ntile < tw.tile_end;
+        const TileDesc nd = a.tile_desc[has_next ? ntile : tw.tile];
+        const unsigned char *blk = a.tile_meta + d.meta_off + (((int64_t)rows + 15) & ~15) * 4;
+        Staged<kStagePieces> st;
+        const int nfirst_pieces = has_next ? ((nd.n_rows + 15) >> 4) * 4 : 0;
+        if constexpr (SLDS) stage_issue<kStagePieces>(st, blk, d.s_bytes);
+        const Piece nfirst = reinterpret_cast<const Piece *>(
+            a.tile_meta + nd.meta_off)[(int)threadIdx.x < nfirst_pieces ? threadIdx.x : 0];
+
+        gather_rows<T, VV, int32_t, kRowsPerPass, kEntriesPerPass>(
+            grp, rows, ngrp, a.Bs.rowptr, a.Bs.colidx, bvals, C + c0 + VV * gl, ccol, VV * gl < w,
+            [&](int pos) { return (int32_t)((uint32_t)first[pos] & ~kSpillBit); },
+            [&](int pos, int64_t, const T(&acc)[VV]) {
+                store_pack<T, VV>(tileD1 + (int64_t)pos * ldl + VV * gl, acc);
+            });
+
+        if constexpr (SLDS) stage_write<kStagePieces>(st, sm.second, blk, d.s_bytes);
+        if ((int)threadIdx.x < nfirst_pieces)
+            reinterpret_cast<Piece *>((sm.first[0] + (par ^ 1) * a.rows_cap))[threadIdx.x] = nfirst;
+        for (int e = (int)blockDim.x + threadIdx.x; e < nfirst_pieces; e += (int)blockDim.x)
+            reinterpret_cast<Piece *>((sm.first[0] + (par ^ 1) * a.rows_cap))[e] =
+                reinterpret_cast<const Piece *>(a.tile_meta + nd.meta_off)[e];
+        __syncthreads();
+        if (VV * gl < w)
+            fused_tail<T, VV>(a, d, first, SLDS ? sm.second : blk, tileD1, ldl, c0, gl, grp, ngrp);
+        if (!has_next) break;
+        __syncthreads();
+        d = nd;
+        tw.tile = ntile;
+        par ^= 1;
+    }
 }
 
 // Packed-row SpMM: Y[row][:] = sum over the row's packed entries of val * X[idx][:], one unit per
@@ -823,35 +1035,83 @@ template <typename K> int raise_lds_limit(K kernel, int64_t bytes) {
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
 }
 
-template <typename T, int NB, int KS, bool FAST>
-int run_fused_gemm(const FusedLaunch &a, hipStream_t st) {
-    static int64_t raised = -1;
-    if (a.lds_bytes > raised) {
-        int e = raise_lds_limit(k_fused_gemm_spmm<T, NB, KS, FAST>, a.lds_bytes);
-        if (e) return e;
-        raised = a.lds_bytes;
-    }
-    // persistent workgroups: as many per XCD as its 32 CUs hold at once (one or two per CU by
-    // LDS), a multiple of the number of slices, and no more than there are (tile, slice) pairs
-    const int64_t per = (a.n_tiles + 7) / 8;
-    const int64_t occ = a.lds_bytes * 2 <= 160 * 1024 ? 2 : 1;
-    int64_t wg_per_xcd = std::min<int64_t>(per * a.n_slices, 32 * occ);
-    wg_per_xcd = std::max<int64_t>(a.n_slices, wg_per_xcd / a.n_slices * a.n_slices);
-    const int64_t grid = 8 * wg_per_xcd;
-    k_fused_gemm_spmm<T, NB, KS, FAST><<<dim3((unsigned)grid), dim3(kFusedThreads), a.lds_bytes, st>>>(a);
-    return (int)hipGetLastError();
+// Workgroups of a fused kernel that one compute unit holds at once (registers and LDS), 1..4.
+template <typename K> int resident_per_cu(K kernel, int threads, int64_t lds_bytes) {
+    int nb = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, reinterpret_cast<const void *>(kernel),
+                                                     threads, (size_t)lds_bytes) != hipSuccess)
+        nb = 1;
+    return nb < 1 ? 1 : (nb > 4 ? 4 : nb);
 }
 
-template <typename T, bool FAST> int run_fused_spmm(const FusedLaunch &a, hipStream_t st) {
+// Launch shape of a fused kernel.  The two phases of a tile use different parts of the machine
+// (phase 1 reads B and runs the matrix cores, phase 2 reads LDS and writes D), so two workgroups
+// per compute unit in different phases keep both busy: when the tiles are small enough for two
+// workgroups' LDS, the kernel runs with half-size workgroups, two to a compute unit.
+struct FusedShape {
+    int threads = kFusedThreads, wg_per_cu = 1;
+};
+template <typename K> FusedShape fused_shape(K kernel, int64_t lds_bytes) {
+    FusedShape s;
+    const char *force = getenv("TF_FUSED_THREADS");     // experiments only
+    if (force) s.threads = atoi(force);
+    else if (resident_per_cu(kernel, kFusedThreads / 2, lds_bytes) >= 2) s.threads = kFusedThreads / 2;
+    s.wg_per_cu = resident_per_cu(kernel, s.threads, lds_bytes);
+    return s;
+}
+
+// Persistent workgroups of the fused kernels: as many per XCD as its 32 CUs hold at once (one or
+// two per CU, by LDS), a multiple of the number of slices, no more than there are (tile, slice) pairs.
+int64_t fused_grid(const FusedLaunch &a, int wg_per_cu) {
+    const int64_t per = (a.n_tiles + 7) / 8;
+    int64_t wg_per_xcd = std::min<int64_t>(per * a.n_slices, 32 * (int64_t)wg_per_cu);
+    wg_per_xcd = std::max<int64_t>(a.n_slices, wg_per_xcd / a.n_slices * a.n_slices);
+    return 8 * wg_per_xcd;
+}
+
+template <typename T, int NB, int KS, bool FAST, bool SLDS>
+int run_fused_gemm2(const FusedLaunch &a, hipStream_t st) {
     static int64_t raised = -1;
     if (a.lds_bytes > raised) {
-        int e = raise_lds_limit(k_fused_spmm_spmm<T, FAST>, a.lds_bytes);
+        int e = raise_lds_limit(k_fused_gemm_spmm<T, NB, KS, FAST, SLDS>, a.lds_bytes);
         if (e) return e;
         raised = a.lds_bytes;
     }
-    const int64_t grid = (int64_t)((a.n_tiles + 7) / 8) * 8 * a.n_slices;
-    k_fused_spmm_spmm<T, FAST><<<dim3((unsigned)grid), dim3(kFusedThreads), a.lds_bytes, st>>>(a);
+    static int64_t occ_lds = -1;
+    static FusedShape shape;
+    if (a.lds_bytes != occ_lds) {
+        shape = fused_shape(k_fused_gemm_spmm<T, NB, KS, FAST, SLDS>, a.lds_bytes);
+        occ_lds = a.lds_bytes;
+    }
+    k_fused_gemm_spmm<T, NB, KS, FAST, SLDS>
+        <<<dim3((unsigned)fused_grid(a, shape.wg_per_cu)), dim3(shape.threads), a.lds_bytes, st>>>(a);
     return (int)hipGetLastError();
+}
+template <typename T, int NB, int KS, bool FAST>
+int run_fused_gemm(const FusedLaunch &a, hipStream_t st) {
+    return a.s_in_lds ? run_fused_gemm2<T, NB, KS, FAST, true>(a, st)
+                      : run_fused_gemm2<T, NB, KS, FAST, false>(a, st);
+}
+
+template <typename T, bool FAST, bool SLDS> int run_fused_spmm2(const FusedLaunch &a, hipStream_t st) {
+    static int64_t raised = -1;
+    if (a.lds_bytes > raised) {
+        int e = raise_lds_limit(k_fused_spmm_spmm<T, FAST, SLDS>, a.lds_bytes);
+        if (e) return e;
+        raised = a.lds_bytes;
+    }
+    static int64_t occ_lds = -1;
+    static FusedShape shape;
+    if (a.lds_bytes != occ_lds) {
+        shape = fused_shape(k_fused_spmm_spmm<T, FAST, SLDS>, a.lds_bytes);
+        occ_lds = a.lds_bytes;
+    }
+    k_fused_spmm_spmm<T, FAST, SLDS>
+        <<<dim3((unsigned)fused_grid(a, shape.wg_per_cu)), dim3(shape.threads), a.lds_bytes, st>>>(a);
+    return (int)hipGetLastError();
+}
+template <typename T, bool FAST> int run_fused_spmm(const FusedLaunch &a, hipStream_t st) {
+    return a.s_in_lds ? run_fused_spmm2<T, FAST, true>(a, st) : run_fused_spmm2<T, FAST, false>(a, st);
 }
 
 template <typename T, int NB, int KS, bool FAST> int run_gemm(const GemmLaunch &a, hipStream_t st) {
