@@ -141,8 +141,8 @@ namespace {
 // Second-phase block of one tile (see TileDesc): the fused rows, longest first, cut into units
 // of one padded length each.  A unit ends when the next row is shorter and the unit already
 // has 64 rows, or when the next row would be padded by more than a quarter.  The padded length
-// (stride) is even so that index pairs and value pairs are aligned; padding entries repeat the
-// row's last column with value 0.
+// (stride) is even so that value pairs are aligned; padding entries repeat the row's last
+// column with value 0.  local(c) is what the kernel finds the D1 row of column c with.
 struct TileBlock {
     std::vector<unsigned char> bytes;
     std::vector<int32_t> rows;      // fused rows in block order
@@ -326,10 +326,6 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
             err = "a tile does not fit the fast memory and splitting is disabled";
             return TF_EUNSUPPORTED;
         }
-        if (rows > 65536) {
-            err = "a tile has more than 65536 rows (tile-local column indices are 16 bit)";
-            return TF_EUNSUPPORTED;
-        }
         s.max_tile_rows = std::max(s.max_tile_rows, rows);
     }
 
@@ -339,6 +335,13 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
     s.spill.assign((size_t)n, 0);
     const unsigned char *vals = static_cast<const unsigned char *>(in.vals);
     std::vector<TileBlock> blocks((size_t)nt);
+    // the packed entries of a tile name their D1 operand by its position in the LDS tile, in units of
+    // 16 bytes (16 bits: enough for 1 MiB of tile)
+    const int32_t pitch16 = (int32_t)(lds_ldl(in.dtype, in.b_is_sparse, (int)cs) * es / 16);
+    if (s.max_tile_rows * pitch16 > 65536) {
+        err = "a tile is larger than 1 MiB (tile-local operand offsets are 16 bit)";
+        return TF_EUNSUPPORTED;
+    }
     std::vector<int32_t> wf1;
     std::vector<int32_t> tile_of((size_t)n), local_of((size_t)n);
     for (int64_t vt = 0; vt < nt; ++vt)
@@ -379,7 +382,7 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
         const int64_t nj = (int64_t)tile_rows.size();
         s.tile_second_ptr[vt] = (int32_t)s.second_rows.size();
         blocks[(size_t)vt] = pack_tile(in.rowptr, in.colidx, vals, es, tile_rows,
-                                       [&](int32_t c) { return local_of[c]; });
+                                       [&](int32_t c) { return local_of[c] * pitch16; });
         s.second_rows.insert(s.second_rows.end(), blocks[(size_t)vt].rows.begin(),
                              blocks[(size_t)vt].rows.end());
         // Eq. 2 (diagnostic): (nz + uc + t + |J|) * cCol + idx, counted in elements; for a dense B

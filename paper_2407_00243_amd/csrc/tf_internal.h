@@ -36,8 +36,9 @@ inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 // LDS layout of a fused workgroup, shared by the inspector (tile fitting) and the kernels.
 //   dense B : [C slice in MFMA operand order: bcol_pad x cs16] [D1 tile: rows_pad16 x ldl]
 //   sparse B: [D1 tile: rows x ldl]
-// ldl is the leading dimension of the D1 tile in elements; dense-B tiles carry 16 bytes of
-// padding per row so that the 16 rows written by one MFMA block start in different banks.
+// ldl is the leading dimension of the D1 tile in elements; dense-B tiles are as wide as the
+// MFMA blocks that produce them and carry 16 bytes of padding per row so that the 16 rows written
+// by one MFMA block start in different banks.
 // Number of 16-column accumulator blocks the MFMA phase runs for a slice of cs columns
 // (instantiated for 1, 2, 4 and 8 blocks) and the padded slice width that goes with it.
 inline int mfma_blocks(int cs) {
@@ -48,7 +49,7 @@ inline int mfma_blocks(int cs) {
 inline int mfma_cols(int cs) { return 16 * mfma_blocks(cs); }
 inline int64_t lds_ldl(int dtype, int b_is_sparse, int cs) {
     const int v = vec_elems(dtype);
-    return b_is_sparse ? round_up(cs, v) : round_up(cs, v) + v;
+    return b_is_sparse ? round_up(cs, v) : mfma_cols(cs) + v;
 }
 inline int64_t lds_fixed_bytes(int dtype, int b_is_sparse, int bcol, int cs) {
     if (b_is_sparse) return 0;

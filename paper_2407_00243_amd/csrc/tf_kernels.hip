@@ -175,13 +175,18 @@ template <typename T, int NB, int KS>
 __device__ __forceinline__ void load_c_regs(T (&creg)[KS * Tr<T>::V * NB], const T *__restrict__ C,
                                             int ccol, int c0, int w, int lane) {
     constexpr int V = Tr<T>::V, KC = 4 * V;
+    // element (k, col) with k = V (lane / 16) + [KC (sq / V) + sq % V] and col = col_of_m(lane % 16)
+    // + [16 nb]: a per-lane offset plus a wave-uniform one (the bracketed parts)
+    const int lcol = Tr<T>::col_of_m(lane & 15);
+    const uint32_t lane_off = (uint32_t)(V * (lane >> 4) * ccol + lcol);
+    const T *base = C + c0;
 #pragma unroll
     for (int i = 0; i < KS * V * NB; ++i) {
         const int nb = i % NB, sq = i / NB;
-        const int k = KC * (sq / V) + V * (lane >> 4) + (sq % V);
-        const int col = 16 * nb + Tr<T>::col_of_m(lane & 15);
-        creg[i] = C[col < w ? (int64_t)k * ccol + c0 + col : 0];
-        if (col >= w) creg[i] = T(0);
+        const int ku = KC * (sq / V) + (sq % V);
+        const bool in = 16 * nb + lcol < w;
+        creg[i] = (base + (ku * ccol + 16 * nb))[in ? lane_off : 0u];
+        if (!in) creg[i] = T(0);
     }
 }
 
@@ -509,32 +514,35 @@ __device__ __forceinline__ FusedSmem fused_smem(const FusedLaunch &a, bool c_reg
 // Copies of a tile's block on their way from device memory to LDS: issued early, written late.
 // NS 16-byte pieces per thread cover 16 NS bytes per thread of the workgroup; what is beyond that is
 // copied by a plain loop at the time of writing.
-typedef Pack<int32_t, 4> Piece;
+typedef int32_t Piece __attribute__((ext_vector_type(4)));
 template <int NS> struct Staged {
     Piece v[NS];
 };
+// (tid, nt): index of the calling thread among the nt threads that do the copy; tid < 0: not one of them
 template <int NS>
-__device__ __forceinline__ void stage_issue(Staged<NS> &st, const unsigned char *src, int bytes) {
+__device__ __forceinline__ void stage_issue(Staged<NS> &st, const unsigned char *src, int bytes,
+                                            int tid, int nt) {
     const Piece *p = reinterpret_cast<const Piece *>(src);
     const int n = bytes >> 4;
 #pragma unroll
     for (int i = 0; i < NS; ++i) {
-        const int e = threadIdx.x + i * (int)blockDim.x;
-        st.v[i] = p[e < n ? e : 0];          // unconditional: the values stay in registers
+        const int e = tid + i * nt;
+        st.v[i] = p[(tid >= 0 && e < n) ? e : 0];      // unconditional: the values stay in registers
     }
 }
 template <int NS>
 __device__ __forceinline__ void stage_write(const Staged<NS> &st, unsigned char *dst,
-                                            const unsigned char *src, int bytes) {
+                                            const unsigned char *src, int bytes, int tid, int nt) {
+    if (tid < 0) return;
     Piece *q = reinterpret_cast<Piece *>(dst);
     const Piece *p = reinterpret_cast<const Piece *>(src);
     const int n = bytes >> 4;
 #pragma unroll
     for (int i = 0; i < NS; ++i) {
-        const int e = threadIdx.x + i * (int)blockDim.x;
+        const int e = tid + i * nt;
         if (e < n) q[e] = st.v[i];
     }
-    for (int e = threadIdx.x + NS * (int)blockDim.x; e < n; e += (int)blockDim.x) q[e] = p[e];
+    for (int e = tid + NS * nt; e < n; e += nt) q[e] = p[e];
 }
 
 // The arrays of a second-phase block.
@@ -596,27 +604,29 @@ __device__ __forceinline__ void fused_tail(const FusedLaunch &a, const TileDesc 
     constexpr int R = 4;
     const SecondBlock<T> b = second_block<T>(sb, d);
     T *__restrict__ D = static_cast<T *>(a.D);
-    typedef Pack<uint16_t, 2> IdxPair;
     typedef Pack<T, 2> ValPair;
+    const unsigned char *tile_lane = reinterpret_cast<const unsigned char *>(tileD1 + lane_off);
     for (int u = 0; u < d.n_units; ++u) {
         const TileUnit un = b.units[u];
         const int stride = un.slots & 0xffff, len = un.slots >> 16;
         const int S = stride >> 1;                                   // steps per row
         const int KB = (un.n_rows + ngrp * R - 1) / (ngrp * R);      // row blocks, wave-uniform
-        const IdxPair *ip = reinterpret_cast<const IdxPair *>(b.idx + un.entry_base);
+        const uint16_t *ip = b.idx + un.entry_base;
         const ValPair *vp = reinterpret_cast<const ValPair *>(b.val + un.entry_base);
-        // entry pair of row block kb, step sp; rows past the unit's end re-read its last row
+        // rows past the unit's end re-read its last row
         auto row_at = [&](int kb, int r) {
             const int i = grp + (kb * R + r) * ngrp;
             return i < un.n_rows ? i : un.n_rows - 1;
         };
-        IdxPair cn[R];
+        // entries of step sp of row block kb: operand offsets (16-byte units) and values
+        uint32_t cn[R][2];
         ValPair vn[R];
         auto read_entries = [&](int kb, int sp) {
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 const int at = row_at(kb, r) * S + sp;
-                cn[r] = ip[at];
+                cn[r][0] = ip[2 * at];
+                cn[r][1] = ip[2 * at + 1];
                 vn[r] = vp[at];
             }
         };
@@ -631,19 +641,15 @@ __device__ __forceinline__ void fused_tail(const FusedLaunch &a, const TileDesc 
 #pragma unroll
                 for (int i = 0; i < VV; ++i) acc[r][i] = T(0);
             for (int sp = 0; sp < S; ++sp) {
-                IdxPair c[R];
-                ValPair v[R];
-#pragma unroll
-                for (int r = 0; r < R; ++r) {
-                    c[r] = cn[r];
-                    v[r] = vn[r];
-                }
                 const bool two = 2 * sp + 1 < len;
+                ValPair v[R];
                 T x[R][2][VV];
 #pragma unroll
                 for (int r = 0; r < R; ++r) {
-                    load_pack<T, VV>(x[r][0], tileD1 + (uint32_t)c[r].x[0] * (uint32_t)ldl + lane_off);
-                    if (two) load_pack<T, VV>(x[r][1], tileD1 + (uint32_t)c[r].x[1] * (uint32_t)ldl + lane_off);
+                    v[r] = vn[r];
+                    load_pack<T, VV>(x[r][0], reinterpret_cast<const T *>(tile_lane + (cn[r][0] << 4)));
+                    if (two)
+                        load_pack<T, VV>(x[r][1], reinterpret_cast<const T *>(tile_lane + (cn[r][1] << 4)));
                 }
                 // next step of this row block, or the first step of the next one
                 int nsp = sp + 1, nkb = kb;
@@ -696,8 +702,7 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
     const int nwaves = (int)blockDim.x >> 6;
     const int g = lane >> 4, r = lane & 15;
     const int bcol_pad = (a.bcol + KC - 1) / KC * KC;
-    const int csv = (a.cs + V - 1) / V * V;
-    const int ldl = csv + V;
+    const int ldl = 16 * NB + V;
     const FusedSmem sm = fused_smem(a, CREG, (int64_t)bcol_pad * 16 * NB * (int64_t)sizeof(T));
     T *Cl = reinterpret_cast<T *>(sm.cslice);
     T *tileD1 = reinterpret_cast<T *>(sm.tile);
@@ -724,46 +729,77 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
     if constexpr (CREG) load_c_regs<T, NB, KSF>(creg, static_cast<const T *>(a.C), a.ccol, c0, w, lane);
     else stage_c_slice<T, NB>(Cl, static_cast<const T *>(a.C), a.bcol, a.ccol, c0, w);
     __syncthreads();
-    BFrag<T, KSF> f0, f1, f2;
+    // nmw waves run the matrix cores (measured: all of them is best; one per SIMD with deeper
+    // prefetch, the rest copying metadata, is slower); the threads that do not copy the tile's
+    // second-phase block and the next tile's row ids into LDS meanwhile.
+    const int nmw = nwaves;
+    const bool is_mfma = wave < nmw;
+    const int snt = nwaves > nmw ? (int)blockDim.x - 64 * nmw : (int)blockDim.x;
+    const int stid = nwaves > nmw ? (int)threadIdx.x - 64 * nmw : (int)threadIdx.x;
+    constexpr int ND = 3;                          // B buffers per wave: two blocks ahead
+    BFrag<T, KSF> fb[ND];
     if constexpr (KS > 0) {
-        load_b_frag<T, KSF>(f0, B + row_of(sm.first[0], d.n_rows, wave) * a.bcol, g);
-        load_b_frag<T, KSF>(f1, B + row_of(sm.first[0], d.n_rows, wave + nwaves) * a.bcol, g);
+        if (is_mfma) {
+#pragma unroll
+            for (int i = 0; i < ND - 1; ++i)
+                load_b_frag<T, KSF>(fb[i], B + row_of(sm.first[0], d.n_rows, wave + i * nmw) * a.bcol, g);
+        }
     }
 
     for (;;) {
         const int rows = d.n_rows;
         const int32_t *first = sm.first[0] + par * a.rows_cap;
+        int32_t *next_first = sm.first[0] + (par ^ 1) * a.rows_cap;
         const int nblk = (rows + 15) >> 4;
         const int ntile = tw.tile + tw.step;
         const bool has_next = ntile < tw.tile_end;
         const TileDesc nd = a.tile_desc[has_next ? ntile : tw.tile];
         const unsigned char *blk = a.tile_meta + d.meta_off + (((int64_t)rows + 15) & ~15) * 4;
+        const Piece *nsrc = reinterpret_cast<const Piece *>(a.tile_meta + nd.meta_off);
 
         // on their way during phase 1: this tile's second-phase block, the next tile's row ids
         Staged<kStagePieces> st;
         const int nfirst_pieces = has_next ? ((nd.n_rows + 15) >> 4) * 4 : 0;
-        if constexpr (SLDS) stage_issue<kStagePieces>(st, blk, d.s_bytes);
-        const Piece nfirst = reinterpret_cast<const Piece *>(
-            a.tile_meta + nd.meta_off)[(int)threadIdx.x < nfirst_pieces ? threadIdx.x : 0];
+        if constexpr (SLDS) stage_issue<kStagePieces>(st, blk, d.s_bytes, stid, snt);
+        const Piece nfirst = nsrc[(stid >= 0 && stid < nfirst_pieces) ? stid : 0];
 
+        // all 16 NB columns of a block's rows are written (the tile's rows are that wide)
         auto write_block = [&](int lb, typename Tr<T>::Acc(&acc)[NB]) {
-            const int lr = lb * 16 + r;
+            T *dst = tileD1 + (lb * 16 + r) * ldl + 4 * g;
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
-                const int col = 16 * nb + 4 * g;
-                store_acc4<T, true>(tileD1 + (int64_t)lr * ldl + col, acc[nb], col, csv);
+#pragma unroll
+                for (int h = 0; h < 4 / V; ++h) {
+                    T tmp[V];
+#pragma unroll
+                    for (int i = 0; i < V; ++i) tmp[i] = acc[nb][V * h + i];
+                    store_pack<T, V>(dst + 16 * nb + V * h, tmp);
+                }
             }
         };
         if constexpr (KS > 0) {
-            for (int lb = wave; lb < nblk; lb += nwaves) {
-                load_b_frag<T, KSF>(f2, B + row_of(first, rows, lb + 2 * nwaves) * a.bcol, g);
-                __builtin_amdgcn_sched_barrier(0);      // keep the prefetch ahead of the MFMAs
+            // One block per step: start the loads of the block ND - 1 steps ahead, multiply,
+            // write the results to the LDS tile.  The B buffers rotate by name (the loop is
+            // unrolled ND times), never by copying: a copy of a buffer would have to wait for
+            // the loads that fill it.
+            auto step = [&](auto fi, int lb) {
+                constexpr int FI = decltype(fi)::value;
+                load_b_frag<T, KSF>(fb[(FI + ND - 1) % ND],
+                                    B + row_of(first, rows, lb + (ND - 1) * nmw) * a.bcol, g);
                 typename Tr<T>::Acc acc[NB];
-                if constexpr (CREG) mfma_frag_reg<T, NB, KSF>(acc, creg, f0);
-                else mfma_frag<T, NB, KSF>(acc, Cl, f0, lane);
+                if constexpr (CREG) mfma_frag_reg<T, NB, KSF>(acc, creg, fb[FI]);
+                else mfma_frag<T, NB, KSF>(acc, Cl, fb[FI], lane);
                 write_block(lb, acc);
-                f0 = f1;
-                f1 = f2;
+            };
+            if (is_mfma) {
+                for (int lb = wave; lb < nblk; lb += ND * nmw) {
+                    step(std::integral_constant<int, 0>(), lb);
+                    if (lb + nmw >= nblk) break;
+                    step(std::integral_constant<int, 1>(), lb + nmw);
+                    if (lb + 2 * nmw >= nblk) break;
+                    step(std::integral_constant<int, 2>(), lb + 2 * nmw);
+                    static_assert(ND == 3, "the loop is unrolled once per B buffer");
+                }
             }
         } else {
             for (int lb = wave; lb < nblk; lb += nwaves) {
@@ -773,18 +809,19 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
                 write_block(lb, acc);
             }
         }
-        if constexpr (SLDS) stage_write<kStagePieces>(st, sm.second, blk, d.s_bytes);
-        if ((int)threadIdx.x < nfirst_pieces)
-            reinterpret_cast<Piece *>((sm.first[0] + (par ^ 1) * a.rows_cap))[threadIdx.x] = nfirst;
-        for (int e = (int)blockDim.x + threadIdx.x; e < nfirst_pieces; e += (int)blockDim.x)
-            reinterpret_cast<Piece *>((sm.first[0] + (par ^ 1) * a.rows_cap))[e] =
-                reinterpret_cast<const Piece *>(a.tile_meta + nd.meta_off)[e];
+        if constexpr (SLDS) stage_write<kStagePieces>(st, sm.second, blk, d.s_bytes, stid, snt);
+        if (stid >= 0) {
+            if (stid < nfirst_pieces) reinterpret_cast<Piece *>(next_first)[stid] = nfirst;
+            for (int e = snt + stid; e < nfirst_pieces; e += snt)
+                reinterpret_cast<Piece *>(next_first)[e] = nsrc[e];
+        }
         __syncthreads();
         if constexpr (KS > 0) {
-            if (has_next) {
-                // first two blocks of the next tile: on their way during this tile's second phase
-                load_b_frag<T, KSF>(f0, B + row_of((sm.first[0] + (par ^ 1) * a.rows_cap), nd.n_rows, wave) * a.bcol, g);
-                load_b_frag<T, KSF>(f1, B + row_of((sm.first[0] + (par ^ 1) * a.rows_cap), nd.n_rows, wave + nwaves) * a.bcol, g);
+            if (has_next && is_mfma) {
+                // first blocks of the next tile: on their way during this tile's second phase
+#pragma unroll
+                for (int i = 0; i < ND - 1; ++i)
+                    load_b_frag<T, KSF>(fb[i], B + row_of(next_first, nd.n_rows, wave + i * nmw) * a.bcol, g);
             }
         }
         if (VV * gl < w)
@@ -831,7 +868,7 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_spmm_spmm(const FusedLa
         const unsigned char *blk = a.tile_meta + d.meta_off + (((int64_t)rows + 15) & ~15) * 4;
         Staged<kStagePieces> st;
         const int nfirst_pieces = has_next ? ((nd.n_rows + 15) >> 4) * 4 : 0;
-        if constexpr (SLDS) stage_issue<kStagePieces>(st, blk, d.s_bytes);
+        if constexpr (SLDS) stage_issue<kStagePieces>(st, blk, d.s_bytes, threadIdx.x, blockDim.x);
         const Piece nfirst = reinterpret_cast<const Piece *>(
             a.tile_meta + nd.meta_off)[(int)threadIdx.x < nfirst_pieces ? threadIdx.x : 0];
 
@@ -842,7 +879,7 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_spmm_spmm(const FusedLa
                 store_pack<T, VV>(tileD1 + (int64_t)pos * ldl + VV * gl, acc);
             });
 
-        if constexpr (SLDS) stage_write<kStagePieces>(st, sm.second, blk, d.s_bytes);
+        if constexpr (SLDS) stage_write<kStagePieces>(st, sm.second, blk, d.s_bytes, threadIdx.x, blockDim.x);
         if ((int)threadIdx.x < nfirst_pieces)
             reinterpret_cast<Piece *>((sm.first[0] + (par ^ 1) * a.rows_cap))[threadIdx.x] = nfirst;
         for (int e = (int)blockDim.x + threadIdx.x; e < nfirst_pieces; e += (int)blockDim.x)
