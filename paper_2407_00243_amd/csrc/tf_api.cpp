@@ -110,11 +110,11 @@ tf::FusedLaunch fused_args(const tf_plan *p, const void *C, void *D) {
     a.cs = p->s.col_slice;
     a.ccol = (int32_t)p->ccol;
     a.bcol = (int32_t)p->bcol;
-    a.rows_cap = (int32_t)tf::round_up(p->s.max_tile_rows, 16);
+    a.rows_cap = (int32_t)tf::round_up(p->s.max_tile_rows, 16);     // size of a row id buffer
     a.s_cap = (int32_t)p->s.second_block_cap;
     a.s_in_lds = p->s.second_block_in_lds ? 1 : 0;
-    a.lds_bytes = tf::fused_lds_bytes(p->dtype, p->b_is_sparse, a.bcol, a.ccol, a.cs, a.rows_cap,
-                                      a.s_in_lds ? a.s_cap : 0);
+    a.lds_bytes = tf::fused_lds_bytes(p->dtype, p->b_is_sparse, a.bcol, a.ccol, a.cs,
+                                      (int)p->s.max_tile_rows, a.s_in_lds ? a.s_cap : 0);
     a.tile_desc = static_cast<const tf::TileDesc *>(p->tile_desc.p);
     a.tile_meta = static_cast<const unsigned char *>(p->tile_meta.p);
     a.C = C;
@@ -269,6 +269,15 @@ tf_status tf_plan_create(const tf_csr *A, int64_t bCol, int64_t cCol, int32_t b_
             return TF_OK;
         }
         p->lds_per_cu = lds_limit;
+        // the launch must fit the device whatever the schedule's own estimate said
+        auto launch_lds = [&]() {
+            return tf::fused_lds_bytes(p->dtype, p->b_is_sparse, (int)bCol, (int)cCol, p->s.col_slice,
+                                       (int)p->s.max_tile_rows,
+                                       p->s.second_block_in_lds ? (int)p->s.second_block_cap : 0);
+        };
+        if (launch_lds() > lds_limit) p->s.second_block_in_lds = false;
+        if (launch_lds() > lds_limit)
+            return fail(TF_EUNSUPPORTED, "a tile does not fit the LDS of this device");
         hipError_t e = hipSuccess;
         auto ok = [&](hipError_t r) {
             if (e == hipSuccess) e = r;

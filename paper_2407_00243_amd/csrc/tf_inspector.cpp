@@ -131,6 +131,16 @@ void pack_rows(const int32_t *rowptr, const int32_t *colidx, const unsigned char
         }
         out.units.push_back(u);
         pos += take;
+        // every unit starts at a multiple of four entries (16-byte aligned pieces for the kernels'
+        // bulk copies, which may also read up to three entries past a unit's end)
+        while (idx_out.size() % 4) {
+            idx_out.push_back(0);
+            out.vals.resize(out.vals.size() + es, 0);
+        }
+    }
+    for (int i = 0; i < 4; ++i) {
+        idx_out.push_back(0);
+        out.vals.resize(out.vals.size() + es, 0);
     }
 }
 

@@ -14,7 +14,7 @@ constexpr int kRowGranuleDense = 16;     // dense-B tiles are produced in blocks
 constexpr int kFusedThreads = 512;       // workgroup size of the fused kernels
 constexpr int kSpmmThreads = 256;        // workgroup size of the row-list SpMM kernel
 constexpr int kUnitRows = 64;            // most rows in one unit of a packed row list
-constexpr int kUnitSlots = 4096;         // most padded entries (rows x slots) in one such unit
+constexpr int kUnitSlots = 2048;         // most padded entries (rows x slots) in one such unit (they are staged in LDS)
 constexpr int kSplitMinSlots = 128;      // rows at least this long are split over several lane groups
 constexpr int kSplitPartSlots = 96;      // target slots per part of a split row
 constexpr uint32_t kSpillBit = 0x80000000u;
@@ -107,23 +107,25 @@ struct FusedLdsLayout {
     int64_t first0, first1, second, cslice, tile, total;
 };
 inline FusedLdsLayout fused_lds_layout(int dtype, int b_is_sparse, int bcol, int ccol, int cs,
-                                       int rows_cap, int s_lds) {
+                                       int max_tile_rows, int s_lds) {
     FusedLdsLayout l{};
     const int es = elem_size(dtype);
+    const int64_t rows16 = round_up(max_tile_rows, 16);       // the row id buffers are padded
+    const int64_t rows_cap = round_up(max_tile_rows, lds_row_granule(b_is_sparse));
     l.first0 = 0;
-    l.first1 = (int64_t)rows_cap * 4;
-    l.second = 2 * (int64_t)rows_cap * 4;
+    l.first1 = rows16 * 4;
+    l.second = 2 * rows16 * 4;
     l.cslice = l.second + round_up(s_lds, 16);
     const int64_t cbytes = lds_fixed_bytes(dtype, b_is_sparse, bcol, cs);
     const bool c_regs = !b_is_sparse && c_in_registers(dtype, mfma_blocks(cs),
                                                        mfma_ksteps_special(dtype, bcol, ccol, cs));
     l.tile = l.cslice + (c_regs ? 0 : cbytes);
-    l.total = l.tile + (int64_t)rows_cap * lds_ldl(dtype, b_is_sparse, cs) * es;
+    l.total = l.tile + rows_cap * lds_ldl(dtype, b_is_sparse, cs) * es;
     return l;
 }
-inline int64_t fused_lds_bytes(int dtype, int b_is_sparse, int bcol, int ccol, int cs, int rows_cap,
-                               int s_lds) {
-    return fused_lds_layout(dtype, b_is_sparse, bcol, ccol, cs, rows_cap, s_lds).total;
+inline int64_t fused_lds_bytes(int dtype, int b_is_sparse, int bcol, int ccol, int cs,
+                               int max_tile_rows, int s_lds) {
+    return fused_lds_layout(dtype, b_is_sparse, bcol, ccol, cs, max_tile_rows, s_lds).total;
 }
 
 // One unit of a packed row list: n_rows rows, all padded to `slots` entries, stored row after
@@ -209,7 +211,7 @@ struct PackDev {
 struct FusedLaunch {
     int32_t dtype;
     int32_t n_tiles, n_slices, cs, ccol, bcol;
-    int32_t rows_cap;                 // largest tile, in rows, rounded up to the row granule
+    int32_t rows_cap;                 // largest tile, in rows, rounded up to 16
     int32_t s_cap;                    // largest second-phase block, bytes (multiple of 16)
     int32_t s_in_lds;                 // 1: second-phase blocks are staged in LDS, 0: read in place
     int64_t lds_bytes;                // dynamic LDS of the launch

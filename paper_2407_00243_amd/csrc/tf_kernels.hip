@@ -897,12 +897,19 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_spmm_spmm(const FusedLa
 }
 
 // Packed-row SpMM: Y[row][:] = sum over the row's packed entries of val * X[idx][:], one unit per
-// workgroup (second wavefront, and the second operation of the unfused baseline).  Units whose
-// rows are split hand their partial sums through LDS and add them in a fixed order.
+// workgroup (second wavefront, and the second operation of the unfused baseline).
+// The entries of a unit are contiguous (n_rows x slots): the workgroup first copies them to LDS
+// with coalesced 16-byte loads, then every lane group reads the entries of its rows from there
+// (an LDS broadcast) instead of fetching each index and value through the vector memory path
+// once per lane.  Units whose rows are split hand their partial sums through LDS and add them
+// in a fixed order.
 template <typename T, bool FAST, bool WIDE>
 __global__ __launch_bounds__(kSpmmThreads) void k_packed_spmm(const PackedSpmmLaunch a) {
     constexpr int VV = FAST ? Tr<T>::V : 1;
-    __shared__ T red[kSpmmThreads * VV];
+    constexpr int R = kRowsPerPass, E = kEntriesPerPass;
+    __shared__ __align__(16) int32_t idx_s[kUnitSlots + 4];
+    __shared__ __align__(16) T val_s[kUnitSlots + 4];
+    T *red = val_s;                                     // split units do not stage their entries
     const int64_t u = a.contiguous ? xcd_contiguous(blockIdx.x, a.n_units) : (int64_t)blockIdx.x;
     if (u >= a.n_units) return;
     const UnitDesc d = a.pack.units[u];
@@ -914,19 +921,107 @@ __global__ __launch_bounds__(kSpmmThreads) void k_packed_spmm(const PackedSpmmLa
     const T *__restrict__ val = static_cast<const T *>(a.pack.vals);
     const T *__restrict__ X = static_cast<const T *>(a.X);
     T *__restrict__ Y = static_cast<T *>(a.Y);
+    if (d.split <= 1) {
+        const int n_ent = d.n_rows * d.slots;
+        {
+            // unit bases are multiples of four entries; the copy may run up to three entries over
+            const Piece *src_i = reinterpret_cast<const Piece *>(idx + d.entry_base);
+            Piece *dst_i = reinterpret_cast<Piece *>(idx_s);
+            for (int e = threadIdx.x; e < (n_ent + 3) / 4; e += blockDim.x) dst_i[e] = src_i[e];
+            constexpr int PV = 16 / (int)sizeof(T);
+            const Piece *src_v = reinterpret_cast<const Piece *>(val + d.entry_base);
+            Piece *dst_v = reinterpret_cast<Piece *>(val_s);
+            for (int e = threadIdx.x; e < (n_ent + PV - 1) / PV; e += blockDim.x) dst_v[e] = src_v[e];
+        }
+        int32_t rid[R];
+        {
+            // row ids of this group's first rows, on their way while the entries are copied
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int i = grp + r * ngrp;
+                rid[r] = rows[d.row_begin + (i < d.n_rows ? i : 0)];
+            }
+        }
+        __syncthreads();
+        const int L = d.slots;
+        for (int cb = 0; cb < ccol; cb += G * VV) {
+            const int col = cb + VV * gl;
+            const bool active = col < ccol;
+            const uint32_t lane_off = active ? (uint32_t)col : 0u;      // idle lanes read column 0
+            for (int i0 = grp; i0 < d.n_rows; i0 += ngrp * R) {
+                int at[R];
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    const int i = i0 + r * ngrp;
+                    at[r] = (i < d.n_rows ? i : i0) * L;
+                }
+                if (i0 != grp || cb != 0) {
+#pragma unroll
+                    for (int r = 0; r < R; ++r) {
+                        const int i = i0 + r * ngrp;
+                        rid[r] = rows[d.row_begin + (i < d.n_rows ? i : i0)];
+                    }
+                }
+                T acc[R][VV];
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+#pragma unroll
+                    for (int i = 0; i < VV; ++i) acc[r][i] = T(0);
+                int sl = 0;
+                for (; sl + E <= L; sl += E) {
+                    uint32_t c[R][E];
+                    T v[R][E];
+                    T x[R][E][VV];
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int e = 0; e < E; ++e) {
+                            c[r][e] = (uint32_t)idx_s[at[r] + sl + e];
+                            v[r][e] = val_s[at[r] + sl + e];
+                        }
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int e = 0; e < E; ++e)
+                            load_x<T, VV, WIDE>(x[r][e], X, c[r][e], (uint32_t)ccol, lane_off);
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int e = 0; e < E; ++e)
+#pragma unroll
+                            for (int i = 0; i < VV; ++i) acc[r][i] += v[r][e] * x[r][e][i];
+                }
+                for (; sl < L; ++sl) {
+                    uint32_t c[R];
+                    T v[R];
+                    T x[R][VV];
+#pragma unroll
+                    for (int r = 0; r < R; ++r) {
+                        c[r] = (uint32_t)idx_s[at[r] + sl];
+                        v[r] = val_s[at[r] + sl];
+                    }
+#pragma unroll
+                    for (int r = 0; r < R; ++r) load_x<T, VV, WIDE>(x[r], X, c[r], (uint32_t)ccol, lane_off);
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+#pragma unroll
+                        for (int i = 0; i < VV; ++i) acc[r][i] += v[r] * x[r][i];
+                }
+                if (active) {
+#pragma unroll
+                    for (int r = 0; r < R; ++r)
+                        if (i0 + r * ngrp < d.n_rows)
+                            store_pack<T, VV>(Y + (int64_t)rid[r] * ccol + col, acc[r]);
+                }
+            }
+        }
+        return;
+    }
     for (int cb = 0; cb < ccol; cb += G * VV) {
         const int col = cb + VV * gl;
         const bool active = col < ccol;
         const uint32_t lane_off = active ? (uint32_t)col : 0u;      // idle lanes read column 0
-        if (d.split <= 1) {
-            if (active) {
-                unit_rows<T, VV, int32_t, kRowsPerPass, kEntriesPerPass, WIDE>(
-                    d, rows, idx, val, X, (uint32_t)ccol, lane_off, grp, ngrp,
-                    [&](int32_t j, const T(&acc)[VV]) {
-                        store_pack<T, VV>(Y + (int64_t)j * ccol + col, acc);
-                    });
-            }
-        } else {
+        {
             // group -> (row, part); `split` groups share a row, each takes a range of the slots
             const int row_i = grp / d.split, part = grp % d.split;
             const int chunk = (d.slots + d.split - 1) / d.split;
