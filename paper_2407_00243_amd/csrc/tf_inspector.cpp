@@ -447,7 +447,14 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
 
     // ---- balance: units of the second wavefront, and of the unfused baseline ------------
     const int vv = in.ccol % v == 0 ? v : 1;
-    PackRules wf1_rules{kUnitRows, kUnitSlots, kSpmmThreads / lane_group((int)in.ccol, vv)};
+    // a unit is one workgroup: short lists are cut into smaller units (down to one row per lane
+    // group) so that they still spread over the machine
+    const int groups = kSpmmThreads / lane_group((int)in.ccol, vv);
+    auto unit_rows_for = [&](int64_t count) {
+        const int64_t want = (count + 1023) / 1024;
+        return (int)std::min<int64_t>(kUnitRows, std::max<int64_t>(groups, want));
+    };
+    PackRules wf1_rules{unit_rows_for((int64_t)wf1.size()), kUnitSlots, groups};
     auto ident = [](int32_t c) { return c; };
     pack_rows(in.rowptr, in.colidx, vals, es, wf1, wf1_rules, true, ident, s.wf1.idx32, s.wf1);
     s.wf1_rows = s.wf1.rows;
@@ -456,7 +463,8 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
     s.wf1_unit_ptr.push_back((int32_t)s.wf1_rows.size());
     std::vector<int32_t> all((size_t)n);
     std::iota(all.begin(), all.end(), 0);
-    pack_rows(in.rowptr, in.colidx, vals, es, all, wf1_rules, true, ident, s.all.idx32, s.all);
+    const PackRules all_rules{unit_rows_for(n), kUnitSlots, groups};
+    pack_rows(in.rowptr, in.colidx, vals, es, all, all_rules, true, ident, s.all.idx32, s.all);
     return TF_OK;
 }
 

@@ -573,7 +573,7 @@ __device__ __forceinline__ SecondBlock<T> second_block(const unsigned char *sb, 
 // and are walked R rows at a time, two slots per step.  Nothing but LDS latency limits this
 // loop, so the entries (index pair, value pair) of the next step are read while the operands of
 // the current step are on their way.
-template <typename T, int VV>
+template <typename T, int VV, int R, int RS>
 __device__ __forceinline__ void fused_tail(const FusedLaunch &a, const TileDesc &d,
                                            const int32_t *first, const unsigned char *sb,
                                            const T *tileD1, int ldl, int c0, int gl, int grp,
@@ -581,7 +581,6 @@ __device__ __forceinline__ void fused_tail(const FusedLaunch &a, const TileDesc 
     const int ccol = a.ccol;
     const uint32_t lane_off = (uint32_t)(VV * gl);
     {
-        constexpr int RS = 8;
         T *__restrict__ D1 = static_cast<T *>(a.D1);
         const int rows = d.n_rows;
         for (int i0 = grp; i0 < rows; i0 += ngrp * RS) {
@@ -601,7 +600,6 @@ __device__ __forceinline__ void fused_tail(const FusedLaunch &a, const TileDesc 
                     store_pack<T, VV>(D1 + (int64_t)(enc[r] & ~kSpillBit) * ccol + c0 + lane_off, x[r]);
         }
     }
-    constexpr int R = 4;
     const SecondBlock<T> b = second_block<T>(sb, d);
     T *__restrict__ D = static_cast<T *>(a.D);
     typedef Pack<T, 2> ValPair;
@@ -825,7 +823,7 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
             }
         }
         if (VV * gl < w)
-            fused_tail<T, VV>(a, d, first, SLDS ? sm.second : blk, tileD1, ldl, c0, gl, grp, ngrp);
+            fused_tail<T, VV, 4, 8>(a, d, first, SLDS ? sm.second : blk, tileD1, ldl, c0, gl, grp, ngrp);
         if (!has_next) break;
         __syncthreads();
         d = nd;
@@ -835,8 +833,12 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
 }
 
 // First wavefront, CSR B: phase 1 gathers rows of C for the tile's rows of B into the LDS tile.
+// Gathers hide their latency with waves: the workgroup is as large as the machine allows (16
+// waves) and each lane group keeps fewer rows in flight, so that a wave fits 128 registers.
+constexpr int kFusedSparseThreads = 1024;
+constexpr int kSparseRowsPerPass = 2;
 template <typename T, bool FAST, bool SLDS>
-__global__ __launch_bounds__(kFusedThreads) void k_fused_spmm_spmm(const FusedLaunch a) {
+__global__ __launch_bounds__(kFusedSparseThreads) void k_fused_spmm_spmm(const FusedLaunch a) {
     constexpr int VV = FAST ? Tr<T>::V : 1;
     TileWalk tw = tile_walk(a.n_tiles, a.n_slices);
     if (tw.tile >= tw.tile_end) return;
@@ -872,7 +874,7 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_spmm_spmm(const FusedLa
         const Piece nfirst = reinterpret_cast<const Piece *>(
             a.tile_meta + nd.meta_off)[(int)threadIdx.x < nfirst_pieces ? threadIdx.x : 0];
 
-        gather_rows<T, VV, int32_t, kRowsPerPass, kEntriesPerPass>(
+        gather_rows<T, VV, int32_t, kSparseRowsPerPass, kEntriesPerPass>(
             grp, rows, ngrp, a.Bs.rowptr, a.Bs.colidx, bvals, C + c0 + VV * gl, ccol, VV * gl < w,
             [&](int pos) { return (int32_t)((uint32_t)first[pos] & ~kSpillBit); },
             [&](int pos, int64_t, const T(&acc)[VV]) {
@@ -887,7 +889,7 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_spmm_spmm(const FusedLa
                 reinterpret_cast<const Piece *>(a.tile_meta + nd.meta_off)[e];
         __syncthreads();
         if (VV * gl < w)
-            fused_tail<T, VV>(a, d, first, SLDS ? sm.second : blk, tileD1, ldl, c0, gl, grp, ngrp);
+            fused_tail<T, VV, 2, 4>(a, d, first, SLDS ? sm.second : blk, tileD1, ldl, c0, gl, grp, ngrp);
         if (!has_next) break;
         __syncthreads();
         d = nd;
@@ -1183,11 +1185,12 @@ template <typename K> int resident_per_cu(K kernel, int threads, int64_t lds_byt
 struct FusedShape {
     int threads = kFusedThreads, wg_per_cu = 1;
 };
-template <typename K> FusedShape fused_shape(K kernel, int64_t lds_bytes) {
+template <typename K> FusedShape fused_shape(K kernel, int64_t lds_bytes, int max_threads) {
     FusedShape s;
+    s.threads = max_threads;
     const char *force = getenv("TF_FUSED_THREADS");     // experiments only
     if (force) s.threads = atoi(force);
-    else if (resident_per_cu(kernel, kFusedThreads / 2, lds_bytes) >= 2) s.threads = kFusedThreads / 2;
+    else if (resident_per_cu(kernel, max_threads / 2, lds_bytes) >= 2) s.threads = max_threads / 2;
     s.wg_per_cu = resident_per_cu(kernel, s.threads, lds_bytes);
     return s;
 }
@@ -1212,7 +1215,7 @@ int run_fused_gemm2(const FusedLaunch &a, hipStream_t st) {
     static int64_t occ_lds = -1;
     static FusedShape shape;
     if (a.lds_bytes != occ_lds) {
-        shape = fused_shape(k_fused_gemm_spmm<T, NB, KS, FAST, SLDS>, a.lds_bytes);
+        shape = fused_shape(k_fused_gemm_spmm<T, NB, KS, FAST, SLDS>, a.lds_bytes, kFusedThreads);
         occ_lds = a.lds_bytes;
     }
     k_fused_gemm_spmm<T, NB, KS, FAST, SLDS>
@@ -1235,7 +1238,7 @@ template <typename T, bool FAST, bool SLDS> int run_fused_spmm2(const FusedLaunc
     static int64_t occ_lds = -1;
     static FusedShape shape;
     if (a.lds_bytes != occ_lds) {
-        shape = fused_shape(k_fused_spmm_spmm<T, FAST, SLDS>, a.lds_bytes);
+        shape = fused_shape(k_fused_spmm_spmm<T, FAST, SLDS>, a.lds_bytes, kFusedSparseThreads);
         occ_lds = a.lds_bytes;
     }
     k_fused_spmm_spmm<T, FAST, SLDS>
