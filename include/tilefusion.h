@@ -118,13 +118,17 @@ typedef struct tf_schedule_view {
     double fused_ratio_nnz;     /* share of the second operation's work done in wavefront 0    */
     int64_t fast_mem_bytes;     /* the budget the tiles were fitted to                         */
     int64_t lds_fixed_bytes;    /* LDS a fused workgroup uses besides its D1 tile              */
-    int64_t lds_bytes_per_row;  /* LDS per D1 row of a tile; footprint = fixed + rows_pad*this */
+    int64_t lds_bytes_per_row;  /* LDS per D1 row of a tile (the row, its id twice, an estimate of
+                                   its packed entries); footprint = fixed + rows_pad * this    */
     int32_t lds_row_granule;    /* rows_pad = rows rounded up to a multiple of this            */
-    int32_t reserved1;
+    int32_t second_block_in_lds; /* 1: the packed entries of a tile's fused rows are staged in LDS;
+                                   0: they did not fit beside the largest tile and are read in place */
     double eq2_cost_max;        /* largest Eq. 2 data-movement cost over the tiles (elements)  */
     double plan_seconds;        /* host time spent building the schedule                       */
     int64_t alg_bytes;          /* algorithmic HBM bytes of one fused execution                */
     int64_t alg_bytes_unfused;  /* the same for the unfused two-kernel execution               */
+    int64_t second_block_bytes; /* largest per-tile block of packed entries (fused rows)       */
+    int64_t lds_launch_bytes;   /* LDS one fused workgroup is launched with (0: schedule only) */
 } tf_schedule_view;
 
 /* Inspector: builds the fused schedule for the pattern of A (Algorithm 1: step 1, coarse tile

@@ -64,9 +64,10 @@ class tf_schedule_view(ctypes.Structure):
                 ("fused_ratio_nnz", ctypes.c_double),
                 ("fast_mem_bytes", ctypes.c_int64), ("lds_fixed_bytes", ctypes.c_int64),
                 ("lds_bytes_per_row", ctypes.c_int64), ("lds_row_granule", ctypes.c_int32),
-                ("reserved1", ctypes.c_int32),
+                ("second_block_in_lds", ctypes.c_int32),
                 ("eq2_cost_max", ctypes.c_double), ("plan_seconds", ctypes.c_double),
-                ("alg_bytes", ctypes.c_int64), ("alg_bytes_unfused", ctypes.c_int64)]
+                ("alg_bytes", ctypes.c_int64), ("alg_bytes_unfused", ctypes.c_int64),
+                ("second_block_bytes", ctypes.c_int64), ("lds_launch_bytes", ctypes.c_int64)]
 
 
 EXPORTS = ["tf_plan_create", "tf_plan_destroy", "tf_plan_schedule", "tf_plan_workspace",

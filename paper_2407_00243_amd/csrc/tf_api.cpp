@@ -345,6 +345,13 @@ tf_status tf_plan_schedule(const tf_plan *p, tf_schedule_view *v) {
     const int64_t d_bytes = p->n * p->ccol * es;
     v->alg_bytes = a_bytes + b_bytes + c_bytes + d_bytes + 2 * s.n_spill_rows * p->ccol * es;
     v->alg_bytes_unfused = a_bytes + b_bytes + c_bytes + 3 * d_bytes;
+    v->second_block_in_lds = s.second_block_in_lds ? 1 : 0;
+    v->second_block_bytes = s.second_block_cap;
+    v->lds_launch_bytes =
+        p->schedule_only
+            ? 0
+            : tf::fused_lds_bytes(p->dtype, p->b_is_sparse, (int)p->bcol, (int)p->ccol, s.col_slice,
+                                  (int)s.max_tile_rows, s.second_block_in_lds ? (int)s.second_block_cap : 0);
     return TF_OK;
 }
 

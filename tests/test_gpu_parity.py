@@ -111,6 +111,40 @@ def test_small_integers_bit_exact(dtype, kind, shape):
             c.close()
 
 
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("kind", ["gemm_spmm", "spmm_spmm"])
+def test_packed_entries_too_large_for_lds_are_read_in_place(dtype, kind):
+    """One tile holds a dense 64 x 64 block of A (64 fused rows of 64 entries) while the average
+    row has 5 entries: the tile's packed entries exceed what the schedule set aside beside the
+    D1 tile, so the kernels read them from device memory instead of staging them in LDS."""
+    import paper_2407_00243_amd as tf
+    n, bcol, ccol = 1024, 16, 16
+    rng = np.random.default_rng(77)
+    rows = [np.arange(64) if j < 64 else np.array([j]) for j in range(n)]
+    rowptr = np.zeros(n + 1, dtype=np.int32)
+    rowptr[1:] = np.cumsum([r.size for r in rows])
+    colidx = np.concatenate(rows).astype(np.int32)
+    A = ti.Csr(n, n, rowptr, colidx, rng.integers(-2, 3, colidx.size).astype(dtype))
+    if kind == "gemm_spmm":
+        B = ti.dense_small_int(n, bcol, dtype, 78)
+    else:
+        B = ti.random_pattern_csr(n, bcol, 0.3, dtype, 78, int_values=True)
+    C = ti.dense_small_int(bcol, ccol, dtype, 79)
+    prob = ti.Problem("dense block", kind, np.dtype(dtype), A, B, C)
+    D_ref, _ = oracle.chain(A, B, C)
+    for fast_mem, staged in ((16 * 1024, 0), (0, 1)):
+        c = _case(prob, ct_size=64, p=1, fast_mem_bytes=fast_mem)
+        try:
+            s = c.plan.schedule()
+            assert s["second_block_in_lds"] == staged
+            assert s["second_block_bytes"] >= 64 * 64 * (2 + np.dtype(dtype).itemsize)
+            assert s["lds_launch_bytes"] <= 160 * 1024
+            assert s["n_fused_rows"] == n
+            assert np.array_equal(c.run().astype(np.float64), D_ref)
+        finally:
+            c.close()
+
+
 # ---------------------------------------------------------------- invariants on the GPU
 
 def test_identity_a_returns_bc():
