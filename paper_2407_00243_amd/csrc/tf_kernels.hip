@@ -734,7 +734,7 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
     const bool is_mfma = wave < nmw;
     const int snt = nwaves > nmw ? (int)blockDim.x - 64 * nmw : (int)blockDim.x;
     const int stid = nwaves > nmw ? (int)threadIdx.x - 64 * nmw : (int)threadIdx.x;
-    constexpr int ND = 3;                          // B buffers per wave: two blocks ahead
+    constexpr int ND = 3;                          // B buffers per wave: ND - 1 blocks ahead (measured: better than 4)
     BFrag<T, KSF> fb[ND];
     if constexpr (KS > 0) {
         if (is_mfma) {
@@ -785,8 +785,14 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
                 load_b_frag<T, KSF>(fb[(FI + ND - 1) % ND],
                                     B + row_of(first, rows, lb + (ND - 1) * nmw) * a.bcol, g);
                 typename Tr<T>::Acc acc[NB];
-                if constexpr (CREG) mfma_frag_reg<T, NB, KSF>(acc, creg, fb[FI]);
-                else mfma_frag<T, NB, KSF>(acc, Cl, fb[FI], lane);
+                if constexpr (CREG) {
+                    mfma_frag_reg<T, NB, KSF>(acc, creg, fb[FI]);
+                } else {
+                    // the C slice is loop invariant: without this the compiler keeps all of it
+                    // in registers, which the rest of the kernel cannot spare
+                    asm volatile("" ::: "memory");
+                    mfma_frag<T, NB, KSF>(acc, Cl, fb[FI], lane);
+                }
                 write_block(lb, acc);
             };
             if (is_mfma) {
@@ -796,7 +802,11 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
                     step(std::integral_constant<int, 1>(), lb + nmw);
                     if (lb + 2 * nmw >= nblk) break;
                     step(std::integral_constant<int, 2>(), lb + 2 * nmw);
-                    static_assert(ND == 3, "the loop is unrolled once per B buffer");
+                    static_assert(ND == 3 || ND == 4, "the loop is unrolled once per B buffer");
+                    if constexpr (ND == 4) {
+                        if (lb + 3 * nmw >= nblk) break;
+                        step(std::integral_constant<int, 3>(), lb + 3 * nmw);
+                    }
                 }
             }
         } else {
@@ -822,8 +832,10 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
                     load_b_frag<T, KSF>(fb[i], B + row_of(next_first, nd.n_rows, wave + i * nmw) * a.bcol, g);
             }
         }
+        // (three rows per lane group at a time: with four the kernel no longer fits the 256
+        // registers of a wave at this occupancy and spills)
         if (VV * gl < w)
-            fused_tail<T, VV, 4, 8>(a, d, first, SLDS ? sm.second : blk, tileD1, ldl, c0, gl, grp, ngrp);
+            fused_tail<T, VV, 3, 4>(a, d, first, SLDS ? sm.second : blk, tileD1, ldl, c0, gl, grp, ngrp);
         if (!has_next) break;
         __syncthreads();
         d = nd;
