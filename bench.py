@@ -40,7 +40,10 @@ TILE_PARAMS = {
 # HBM traffic per launch of the dominant kernel from rocprofv3 --pmc runs (FETCH_SIZE and
 # WRITE_SIZE, scaled by what the same counters read for a plain copy), keyed by workload;
 # None until measured.  See profiles/.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    # profiles/k_fused_gemm_spmm_cfg2_2dlaplacian.md: FETCH_SIZE 37927.7 KiB x 2.000 + WRITE_SIZE 73448.2 KiB
+    "cfg2 GeMM-SpMM fp32 2D Laplacian n=262144 64->64": int((2.0 * 37927.7 + 73448.2) * 1024),
+}
 
 
 def log(*a):
