@@ -717,16 +717,6 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
 
     TileDesc d = a.tile_desc[tw.tile];
     int par = 0;
-    {
-        // row ids of the first tile
-        const int n16 = (d.n_rows + 15) & ~15;
-        const int32_t *src = reinterpret_cast<const int32_t *>(a.tile_meta + d.meta_off);
-        for (int e = threadIdx.x; e < n16; e += (int)blockDim.x) sm.first[0][e] = src[e];
-    }
-    T creg[CREG ? KSF * V * NB : 1];
-    if constexpr (CREG) load_c_regs<T, NB, KSF>(creg, static_cast<const T *>(a.C), a.ccol, c0, w, lane);
-    else stage_c_slice<T, NB>(Cl, static_cast<const T *>(a.C), a.bcol, a.ccol, c0, w);
-    __syncthreads();
     // nmw waves run the matrix cores (measured: all of them is best; one per SIMD with deeper
     // prefetch, the rest copying metadata, is slower); the threads that do not copy the tile's
     // second-phase block and the next tile's row ids into LDS meanwhile.
@@ -736,12 +726,28 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
     const int stid = nwaves > nmw ? (int)threadIdx.x - 64 * nmw : (int)threadIdx.x;
     constexpr int ND = 3;                          // B buffers per wave: ND - 1 blocks ahead (measured: better than 4)
     BFrag<T, KSF> fb[ND];
-    if constexpr (KS > 0) {
-        if (is_mfma) {
+    T creg[CREG ? KSF * V * NB : 1];
+    {
+        // Start-up, ordered so that the longest chain (descriptor -> row ids -> rows of B) begins
+        // first: each lane fetches the ids of its own first rows straight from device memory, the
+        // C operands and the copy of all row ids to LDS follow, then the B loads go out.
+        const int32_t *src = reinterpret_cast<const int32_t *>(a.tile_meta + d.meta_off);
+        int64_t row0[ND - 1];
+        if constexpr (KS > 0) {
 #pragma unroll
-            for (int i = 0; i < ND - 1; ++i)
-                load_b_frag<T, KSF>(fb[i], B + row_of(sm.first[0], d.n_rows, wave + i * nmw) * a.bcol, g);
+            for (int i = 0; i < ND - 1; ++i) row0[i] = row_of(src, d.n_rows, wave + i * nmw);
         }
+        const int n16 = (d.n_rows + 15) & ~15;
+        for (int e = threadIdx.x; e < n16; e += (int)blockDim.x) sm.first[0][e] = src[e];
+        if constexpr (KS > 0) {
+            if (is_mfma) {
+#pragma unroll
+                for (int i = 0; i < ND - 1; ++i) load_b_frag<T, KSF>(fb[i], B + row0[i] * a.bcol, g);
+            }
+        }
+        if constexpr (CREG) load_c_regs<T, NB, KSF>(creg, static_cast<const T *>(a.C), a.ccol, c0, w, lane);
+        else stage_c_slice<T, NB>(Cl, static_cast<const T *>(a.C), a.bcol, a.ccol, c0, w);
+        __syncthreads();
     }
 
     for (;;) {
