@@ -228,7 +228,7 @@ def main():
     roofline["frac"] = roofline["achieved"] / roofline["peak"]
     roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get(workload)
     roofline["kernel"] = ("k_fused_" + ("spmm_spmm" if sparse else "gemm_spmm")) if dom_is_wf0 \
-        else "k_spmm_units"
+        else "k_packed_spmm"
     roofline["kernel_ms"] = dom_ms
     roofline["alg_bytes_per_launch"] = int(dom_q)
 

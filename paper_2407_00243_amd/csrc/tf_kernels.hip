@@ -2,7 +2,7 @@
 //
 //   k_fused_gemm_spmm   first wavefront, dense B   (paper Section 3.2, fused GeMM-SpMM listing)
 //   k_fused_spmm_spmm   first wavefront, CSR B     (Section 3.2, fused SpMM-SpMM listing)
-//   k_spmm_units        second wavefront (rows whose D1 rows come from device memory); also the
+//   k_packed_spmm       second wavefront (rows whose D1 rows come from device memory); also the
 //                       SpMM of the unfused baseline
 //   k_gemm              D1 = B C for all rows: the GeMM of the unfused baseline
 //
