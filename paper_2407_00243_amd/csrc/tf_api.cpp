@@ -430,7 +430,12 @@ tf_status tf_unfused_gemm_spmm(const tf_plan *p, const void *B, const void *C, v
     g.n = p->n;
     g.bcol = (int32_t)p->bcol;
     g.ccol = (int32_t)p->ccol;
+    // as wide as one wave's accumulators allow, narrowed until the C slice fits the LDS
     g.cs = p->ccol > tf::kMaxMfmaSliceCols ? tf::kMaxMfmaSliceCols : (int32_t)p->ccol;
+    while (g.cs > 16 && tf::lds_fixed_bytes(p->dtype, 0, g.bcol, g.cs) > p->lds_per_cu)
+        g.cs = (g.cs - 1) / 16 * 16;
+    if (tf::lds_fixed_bytes(p->dtype, 0, g.bcol, g.cs) > p->lds_per_cu)
+        return fail(TF_EUNSUPPORTED, "bCol is too large for the C slice of the unfused GeMM to fit LDS");
     g.n_slices = (int32_t)((p->ccol + g.cs - 1) / g.cs);
     g.B = B;
     g.C = C;

@@ -247,26 +247,35 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
         err = "col_slice must be a multiple of 16 bytes of elements";
         return TF_EINVAL;
     }
-    s.col_slice = (int32_t)cs;
-    s.n_slices = (int32_t)((in.ccol + cs - 1) / cs);
-
     // ---- fast-memory model --------------------------------------------------------------
     // Per D1 row: the row itself, its id in two buffers (this tile's and the next one's), and an
     // estimate of its share of the second-phase block (row id, packed entries of an average row).
     // The C slice of a dense B takes LDS for good only when the waves read their operands from it.
-    const bool c_regs = !in.b_is_sparse &&
-                        c_in_registers(in.dtype, mfma_blocks((int)cs),
-                                       mfma_ksteps_special(in.dtype, (int)in.bcol, (int)in.ccol, (int)cs));
     const int64_t avg_nnz = n > 0 ? (in.nnz + n - 1) / n : 0;
     s.lds_meta_bytes_per_row = 8 + 4 + avg_nnz * (2 + es);
-    s.lds_fixed_bytes = (c_regs ? 0 : lds_fixed_bytes(in.dtype, in.b_is_sparse, (int)in.bcol, (int)cs)) + 256;
-    s.lds_bytes_per_row = lds_ldl(in.dtype, in.b_is_sparse, (int)cs) * es + s.lds_meta_bytes_per_row;
     s.lds_row_granule = lds_row_granule(in.b_is_sparse);
     s.fast_mem_bytes = in.fast_mem_bytes;
+    auto model = [&](int64_t width) {
+        const bool c_regs = !in.b_is_sparse &&
+                            c_in_registers(in.dtype, mfma_blocks((int)width),
+                                           mfma_ksteps_special(in.dtype, (int)in.bcol, (int)in.ccol, (int)width));
+        s.lds_fixed_bytes =
+            (c_regs ? 0 : lds_fixed_bytes(in.dtype, in.b_is_sparse, (int)in.bcol, (int)width)) + 256;
+        s.lds_bytes_per_row = lds_ldl(in.dtype, in.b_is_sparse, (int)width) * es + s.lds_meta_bytes_per_row;
+    };
+    model(cs);
+    // a default slice is narrowed (in steps of 16 columns) until its C slice and a first block of
+    // D1 rows fit; a slice the caller asked for is taken as given
+    while (in.col_slice == 0 && !in.b_is_sparse && cs > 16 && tile_footprint(s, 1) > s.fast_mem_bytes) {
+        cs = (cs - 1) / 16 * 16;
+        model(cs);
+    }
     if (tile_footprint(s, 1) > s.fast_mem_bytes) {
         err = "fast_mem_bytes cannot hold one D1 row of the chosen column slice (plus the C slice)";
         return TF_EUNSUPPORTED;
     }
+    s.col_slice = (int32_t)cs;
+    s.n_slices = (int32_t)((in.ccol + cs - 1) / cs);
 
     // ---- step 1: tile size --------------------------------------------------------------
     const int64_t ct = in.ct_size > 0 ? in.ct_size : 2048;

@@ -112,6 +112,29 @@ def test_small_integers_bit_exact(dtype, kind, shape):
 
 
 @pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("bcol", [16, 32, 64, 128, 256])
+@pytest.mark.parametrize("ccol", [16, 32, 64, 128])
+def test_every_specialised_gemm_shape_bit_exact(dtype, bcol, ccol):
+    """The dense-B kernels are instantiated per depth of k (bCol / 16 or / 8 steps) and per number
+    of 16-column MFMA blocks, with the C operands in registers or in LDS: one exact case each, on
+    tiles of several 16-row blocks with a ragged last one, for the fused and the unfused path."""
+    n = 333
+    A = ti.random_local_csr(n, 5, 6, 0.1, dtype, 91, int_values=True)
+    B = ti.dense_small_int(n, bcol, dtype, 92)
+    C = ti.dense_small_int(bcol, ccol, dtype, 93)
+    prob = ti.Problem("shapes", "gemm_spmm", np.dtype(dtype), A, B, C)
+    D_ref, _ = oracle.chain(A, B, C)
+    c = _case(prob, ct_size=100, p=1)
+    try:
+        s = c.plan.schedule()
+        assert 0 < s["n_fused_rows"] < n
+        for fused in (True, False):
+            assert np.array_equal(c.run(fused=fused).astype(np.float64), D_ref), fused
+    finally:
+        c.close()
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
 @pytest.mark.parametrize("kind", ["gemm_spmm", "spmm_spmm"])
 def test_packed_entries_too_large_for_lds_are_read_in_place(dtype, kind):
     """One tile holds a dense 64 x 64 block of A (64 fused rows of 64 entries) while the average

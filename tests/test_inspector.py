@@ -111,6 +111,29 @@ def test_step2_splits_to_the_lds_budget():
     assert e.value.status_name == "TF_EUNSUPPORTED"
 
 
+def test_default_column_slice_narrows_until_the_c_slice_fits():
+    """fp64, bCol = 256, cCol = 128: a 128-column C slice is 256 KiB, more than the fast memory;
+    the default slice shrinks in steps of 16 columns, an explicit one is taken as given."""
+    A = ti.banded(512, 3, np.float64, 5)
+    s = plan_schedule(A, 256, 128, False, ct_size=64, p=1)
+    assert s["col_slice"] % 16 == 0 and 16 <= s["col_slice"] < 128
+    assert s["n_slices"] == -(-128 // s["col_slice"])
+    assert s["lds_fixed_bytes"] + s["lds_row_granule"] * s["lds_bytes_per_row"] <= s["fast_mem_bytes"]
+    check_schedule(A, s, 64, 1)
+    with pytest.raises(tf.TfError) as e:
+        plan_schedule(A, 256, 128, False, ct_size=64, p=1, col_slice=128)
+    assert e.value.status_name == "TF_EUNSUPPORTED"
+
+
+def test_schedule_view_reports_the_second_phase_blocks():
+    prob = ti.config(2, scale_down=128)
+    s = plan_schedule(prob.A, 64, 64, False, ct_size=256, p=1)
+    # per fused row: a 4-byte id and, per padded entry slot, a 2-byte position and a 4-byte value
+    rows = np.diff(s["tile_second_ptr"]).max()
+    assert s["second_block_bytes"] >= rows * (4 + 4 * (2 + 4))
+    assert s["second_block_in_lds"] == 1 and s["lds_launch_bytes"] == 0      # schedule only
+
+
 def test_degenerate_inputs():
     empty = ti.Csr(0, 0, np.zeros(1, np.int32), np.zeros(0, np.int32), np.zeros(0, np.float32))
     s = plan_schedule(empty, 4, 4, False)
