@@ -210,7 +210,15 @@ TileBlock pack_tile(const int32_t *rowptr, const int32_t *colidx, const unsigned
     tb.bytes.assign(align16(off_val + val.size()), 0);
     if (!units.empty()) std::memcpy(tb.bytes.data(), units.data(), units.size() * sizeof(TileUnit));
     if (!list.empty()) std::memcpy(tb.bytes.data() + off_rows2, list.data(), list.size() * 4);
-    if (!idx.empty()) std::memcpy(tb.bytes.data() + off_idx, idx.data(), idx.size() * 2);
+    // operand positions: the even slots of all rows first, then the odd slots, so that the two
+    // positions of a pair come from different arrays, by two plain 16-bit reads (one 32-bit read
+    // of both would have to be taken apart again by the vector ALU, the scarce unit there)
+    uint16_t *ip = reinterpret_cast<uint16_t *>(tb.bytes.data() + off_idx);
+    const size_t pairs = idx.size() / 2;
+    for (size_t q = 0; q < pairs; ++q) {
+        ip[q] = idx[2 * q];
+        ip[pairs + q] = idx[2 * q + 1];
+    }
     if (!val.empty()) std::memcpy(tb.bytes.data() + off_val, val.data(), val.size());
     tb.n_units = (int32_t)units.size();
     tb.n_entries = (int32_t)idx.size();

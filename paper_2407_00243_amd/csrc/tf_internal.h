@@ -82,7 +82,9 @@ inline int mfma_ksteps_special(int dtype, int bcol, int ccol, int cs) {
 // followed by the second-phase block of s_bytes bytes (each array padded to 16 bytes):
 //   TileUnit units[n_units]
 //   int32    rows2[n_second]               row ids of the fused rows of D, unit after unit
-//   uint16   idx[n_entries]                tile-local column index of every packed entry
+//   uint16   idx[n_entries]                where the D1 row of every packed entry sits in the LDS tile,
+//                                          in units of 16 bytes: the even slots of all rows first
+//                                          (n_entries / 2 of them), then the odd slots
 //   T        val[n_entries]
 struct TileDesc {
     int64_t meta_off;      // byte offset of the block

@@ -549,7 +549,7 @@ __device__ __forceinline__ void stage_write(const Staged<NS> &st, unsigned char 
 template <typename T> struct SecondBlock {
     const TileUnit *units;
     const int32_t *rows2;
-    const uint16_t *idx;
+    const uint16_t *idx_a, *idx_b;      // operand positions of the even and of the odd slots, per pair
     const T *val;
 };
 template <typename T>
@@ -560,7 +560,8 @@ __device__ __forceinline__ SecondBlock<T> second_block(const unsigned char *sb, 
     const int off_val = (off_idx + d.n_entries * 2 + 15) & ~15;
     b.units = reinterpret_cast<const TileUnit *>(sb);
     b.rows2 = reinterpret_cast<const int32_t *>(sb + off_rows2);
-    b.idx = reinterpret_cast<const uint16_t *>(sb + off_idx);
+    b.idx_a = reinterpret_cast<const uint16_t *>(sb + off_idx);
+    b.idx_b = b.idx_a + (d.n_entries >> 1);
     b.val = reinterpret_cast<const T *>(sb + off_val);
     return b;
 }
@@ -573,6 +574,8 @@ __device__ __forceinline__ SecondBlock<T> second_block(const unsigned char *sb, 
 // and are walked R rows at a time, two slots per step.  Nothing but LDS latency limits this
 // loop, so the entries (index pair, value pair) of the next step are read while the operands of
 // the current step are on their way.
+// RS > 0: the spilled rows are copied here, RS rows per lane group at a time; RS = 0: the caller
+// has already stored them.
 template <typename T, int VV, int R, int RS>
 __device__ __forceinline__ void fused_tail(const FusedLaunch &a, const TileDesc &d,
                                            const int32_t *first, const unsigned char *sb,
@@ -580,17 +583,17 @@ __device__ __forceinline__ void fused_tail(const FusedLaunch &a, const TileDesc 
                                            int ngrp) {
     const int ccol = a.ccol;
     const uint32_t lane_off = (uint32_t)(VV * gl);
-    {
+    if constexpr (RS > 0) {
         T *__restrict__ D1 = static_cast<T *>(a.D1);
         const int rows = d.n_rows;
         for (int i0 = grp; i0 < rows; i0 += ngrp * RS) {
-            uint32_t enc[RS];
+            uint32_t enc[RS > 0 ? RS : 1];
 #pragma unroll
             for (int r = 0; r < RS; ++r) {
                 const int i = i0 + r * ngrp;
                 enc[r] = i < rows ? (uint32_t)first[i] : 0u;
             }
-            T x[RS][VV];
+            T x[RS > 0 ? RS : 1][VV];
 #pragma unroll
             for (int r = 0; r < RS; ++r)
                 if (enc[r] & kSpillBit) load_pack<T, VV>(x[r], tileD1 + (i0 + r * ngrp) * ldl + lane_off);
@@ -609,7 +612,7 @@ __device__ __forceinline__ void fused_tail(const FusedLaunch &a, const TileDesc 
         const int stride = un.slots & 0xffff, len = un.slots >> 16;
         const int S = stride >> 1;                                   // steps per row
         const int KB = (un.n_rows + ngrp * R - 1) / (ngrp * R);      // row blocks, wave-uniform
-        const uint16_t *ip = b.idx + un.entry_base;
+        const uint16_t *ia = b.idx_a + (un.entry_base >> 1), *ib = b.idx_b + (un.entry_base >> 1);
         const ValPair *vp = reinterpret_cast<const ValPair *>(b.val + un.entry_base);
         // rows past the unit's end re-read its last row
         auto row_at = [&](int kb, int r) {
@@ -623,8 +626,8 @@ __device__ __forceinline__ void fused_tail(const FusedLaunch &a, const TileDesc 
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 const int at = row_at(kb, r) * S + sp;
-                cn[r][0] = ip[2 * at];
-                cn[r][1] = ip[2 * at + 1];
+                cn[r][0] = ia[at];
+                cn[r][1] = ib[at];
                 vn[r] = vp[at];
             }
         };
@@ -781,6 +784,23 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
                 }
             }
         };
+        // The spilled rows of a block go to the D1 workspace as soon as the wave that produced
+        // them has written them to the tile (no barrier: it reads back its own writes), whole
+        // rows at a time; this mostly LDS and store work runs while other waves multiply.
+        auto spill_block = [&](int lb) {
+            T *__restrict__ D1 = static_cast<T *>(a.D1);
+            const int rpp = 64 / G;                         // rows per pass (G <= 64 lanes per row)
+            for (int p0 = 0; p0 < 16; p0 += rpp) {
+                const int i = lb * 16 + p0 + lane / G;
+                const uint32_t enc = i < rows ? (uint32_t)first[i] : 0u;
+                const int col = VV * (lane % G);
+                if ((enc & kSpillBit) && col < w) {
+                    T x[VV];
+                    load_pack<T, VV>(x, tileD1 + i * ldl + col);
+                    store_pack<T, VV>(D1 + (int64_t)(enc & ~kSpillBit) * a.ccol + c0 + col, x);
+                }
+            }
+        };
         if constexpr (KS > 0) {
             // One block per step: start the loads of the block ND - 1 steps ahead, multiply,
             // write the results to the LDS tile.  The B buffers rotate by name (the loop is
@@ -800,6 +820,7 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
                     mfma_frag<T, NB, KSF>(acc, Cl, fb[FI], lane);
                 }
                 write_block(lb, acc);
+                spill_block(lb);
             };
             if (is_mfma) {
                 for (int lb = wave; lb < nblk; lb += ND * nmw) {
@@ -821,6 +842,7 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
                 mfma_row_block<T, NB, FAST>(acc, Cl, B + row_of(first, rows, lb) * a.bcol, true,
                                             a.bcol, lane);
                 write_block(lb, acc);
+                spill_block(lb);
             }
         }
         if constexpr (SLDS) stage_write<kStagePieces>(st, sm.second, blk, d.s_bytes, stid, snt);
@@ -841,7 +863,7 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
         // (three rows per lane group at a time: with four the kernel no longer fits the 256
         // registers of a wave at this occupancy and spills)
         if (VV * gl < w)
-            fused_tail<T, VV, 3, 4>(a, d, first, SLDS ? sm.second : blk, tileD1, ldl, c0, gl, grp, ngrp);
+            fused_tail<T, VV, 3, 0>(a, d, first, SLDS ? sm.second : blk, tileD1, ldl, c0, gl, grp, ngrp);
         if (!has_next) break;
         __syncthreads();
         d = nd;
@@ -1217,7 +1239,9 @@ template <typename K> FusedShape fused_shape(K kernel, int64_t lds_bytes, int ma
 // two per CU, by LDS), a multiple of the number of slices, no more than there are (tile, slice) pairs.
 int64_t fused_grid(const FusedLaunch &a, int wg_per_cu) {
     const int64_t per = (a.n_tiles + 7) / 8;
-    int64_t wg_per_xcd = std::min<int64_t>(per * a.n_slices, 32 * (int64_t)wg_per_cu);
+    int64_t cus = 32;
+    if (const char *e = getenv("TF_CUS_PER_XCD")) cus = atoi(e);      // experiments only
+    int64_t wg_per_xcd = std::min<int64_t>(per * a.n_slices, cus * (int64_t)wg_per_cu);
     wg_per_xcd = std::max<int64_t>(a.n_slices, wg_per_xcd / a.n_slices * a.n_slices);
     return 8 * wg_per_xcd;
 }
