@@ -17,7 +17,6 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
-#include <cstdlib>
 #include <type_traits>
 
 #include "tf_internal.h"
@@ -1218,19 +1217,19 @@ template <typename K> int resident_per_cu(K kernel, int threads, int64_t lds_byt
     return nb < 1 ? 1 : (nb > 4 ? 4 : nb);
 }
 
-// Launch shape of a fused kernel.  The two phases of a tile use different parts of the machine
-// (phase 1 reads B and runs the matrix cores, phase 2 reads LDS and writes D), so two workgroups
-// per compute unit in different phases keep both busy: when the tiles are small enough for two
-// workgroups' LDS, the kernel runs with half-size workgroups, two to a compute unit.
+// Launch shape of a fused kernel: the number of waves per compute unit stays the same whatever
+// the tile size.  When the tiles are small enough for the LDS of two workgroups (or more), the
+// kernel runs with half-size workgroups, as many to a compute unit as fit, so that small tiles
+// do not leave half of the waves of a large workgroup without a 16-row block or a row to work on.
+// (Measured on config 2: two half-size workgroups on half-size tiles are as fast as one full one;
+// their phases do not overlap usefully because fp32 MFMA and vector ALU work of one SIMD serialise.)
 struct FusedShape {
     int threads = kFusedThreads, wg_per_cu = 1;
 };
 template <typename K> FusedShape fused_shape(K kernel, int64_t lds_bytes, int max_threads) {
     FusedShape s;
     s.threads = max_threads;
-    const char *force = getenv("TF_FUSED_THREADS");     // experiments only
-    if (force) s.threads = atoi(force);
-    else if (resident_per_cu(kernel, max_threads / 2, lds_bytes) >= 2) s.threads = max_threads / 2;
+    if (resident_per_cu(kernel, max_threads / 2, lds_bytes) >= 2) s.threads = max_threads / 2;
     s.wg_per_cu = resident_per_cu(kernel, s.threads, lds_bytes);
     return s;
 }
@@ -1239,9 +1238,7 @@ template <typename K> FusedShape fused_shape(K kernel, int64_t lds_bytes, int ma
 // two per CU, by LDS), a multiple of the number of slices, no more than there are (tile, slice) pairs.
 int64_t fused_grid(const FusedLaunch &a, int wg_per_cu) {
     const int64_t per = (a.n_tiles + 7) / 8;
-    int64_t cus = 32;
-    if (const char *e = getenv("TF_CUS_PER_XCD")) cus = atoi(e);      // experiments only
-    int64_t wg_per_xcd = std::min<int64_t>(per * a.n_slices, cus * (int64_t)wg_per_cu);
+    int64_t wg_per_xcd = std::min<int64_t>(per * a.n_slices, 32 * (int64_t)wg_per_cu);
     wg_per_xcd = std::max<int64_t>(a.n_slices, wg_per_xcd / a.n_slices * a.n_slices);
     return 8 * wg_per_xcd;
 }
