@@ -79,6 +79,12 @@ typedef struct tf_tile_params {
  * rows depend on far-away rows (stencils in natural ordering) consecutive tiles small enough
  * for LDS fuse nothing, while graph-grown tiles do. */
 #define TF_FLAG_REORDER 4u
+/* The chain with the transpose of C (Section 3.2 notes that the fused code also covers it):
+ * D = A (B C^T).  The dense-B calls on such a plan take C as a cCol x bCol row-major array, so
+ * that element (k, c) of the multiplier is C[c * bCol + k]; everything else is unchanged.  Only
+ * plans for a dense B accept the flag (a sparse B gathers whole rows of C; plan creation fails
+ * with TF_EUNSUPPORTED). */
+#define TF_FLAG_C_TRANSPOSED 8u
 
 typedef struct tf_plan tf_plan; /* opaque, library-owned */
 

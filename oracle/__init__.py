@@ -13,7 +13,8 @@ splitting) and an implementation-free validator of any fused schedule.
 
 Pins (tests/test_oracle_*.py): dense brute force in extended precision, A = I, associativity,
 exact small-integer inputs, closed forms for banded / Laplacian / GCN matrices, scipy.sparse
-on special cases, closed-form fused-row counts.  The data-movement cost of Eq. 2 and the worked
+on special cases, closed-form fused-row counts; the transposed-C first operation against a
+hand-worked 1 x 2 example and against the pinned plain one on an explicitly transposed array.  The data-movement cost of Eq. 2 and the worked
 example around Figures 2 and 3 cannot be replayed (the figures are not available and the
 example contradicts the tile-size rule of Algorithm 1): parity unpinned for those two items.
 """
@@ -49,6 +50,8 @@ def _load():
         lib = ctypes.CDLL(_LIB)
         i64, vp = ctypes.c_int64, ctypes.c_void_p
         lib.orc_gemm.argtypes = [i64, i64, i64, vp, vp, vp, vp, i64]
+        lib.orc_gemm_ct.argtypes = [i64, i64, i64, vp, vp, vp, vp, i64]
+        lib.orc_gemm_ct.restype = None
         lib.orc_spmm.argtypes = [i64, vp, vp, vp, i64, vp, vp, vp, i64]
         lib.orc_gemm_par.argtypes = [i64, i64, i64, vp, vp, vp]
         lib.orc_spmm_par.argtypes = [i64, vp, vp, vp, i64, vp, vp]
@@ -94,6 +97,34 @@ def gemm(B, C, rows: Optional[Sequence[int]] = None, out: Optional[np.ndarray] =
         lib.orc_gemm(n, bcol, ccol, _ptr(B), _ptr(C), _ptr(out), _ptr(r),
                      0 if r is None else r.size)
     return out
+
+
+def gemm_ct(B, Ct, rows: Optional[Sequence[int]] = None, out: Optional[np.ndarray] = None
+            ) -> np.ndarray:
+    """D1 = B Ct^T in fp64 (k ascending) for Ct given as cCol x bCol: the first operation of the
+    chain with the transpose of C (Section 3.2)."""
+    B = _f64(B)
+    Ct = _f64(Ct)
+    n, bcol = B.shape
+    assert Ct.shape[1] == bcol
+    ccol = Ct.shape[0]
+    if out is None:
+        out = np.zeros((n, ccol), dtype=np.float64)
+    r = None if rows is None else np.ascontiguousarray(rows, dtype=np.int64)
+    _load().orc_gemm_ct(n, bcol, ccol, _ptr(B), _ptr(Ct), _ptr(out), _ptr(r),
+                        0 if r is None else r.size)
+    return out
+
+
+def chain_ct(A, B, Ct, with_scale: bool = True) -> Tuple[np.ndarray, Optional[np.ndarray]]:
+    """D = A (B Ct^T) for a dense B and Ct given as cCol x bCol, and optionally
+    W = |A| (|B| |Ct|^T); both fp64, full size."""
+    D = spmm(A.rowptr, A.colidx, A.vals, gemm_ct(B, Ct))
+    W = None
+    if with_scale:
+        W1 = gemm_ct(np.abs(_f64(B)), np.abs(_f64(Ct)))
+        W = spmm(A.rowptr, A.colidx, np.abs(_f64(A.vals)), W1)
+    return D, W
 
 
 def spmm(rowptr, colidx, vals, X, rows: Optional[Sequence[int]] = None,

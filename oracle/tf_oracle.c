@@ -12,6 +12,10 @@
  *   CSR   B :  D1[i][c] = sum_{q = Bp[i] .. Bp[i+1]-1, storage} Bx[q]     * C[Bi[q]][c]
  *   second  :  D [j][c] = sum_{q = Ap[j] .. Ap[j+1]-1, storage} Ax[q]     * D1[Ai[q]][c]
  *
+ * and, for the variant with the transpose of C that Section 3.2 mentions (Ct is cCol x bCol),
+ *
+ *   dense B :  D1[i][c] = sum_{k = 0 .. bCol-1, ascending}      B[i][k]   * Ct[c][k]
+ *
  * Everything is scalar fp64 with a separate multiply and add (compile with -ffp-contract=off),
  * each output element accumulated in one fixed order.  Single-precision problems are promoted
  * to fp64 by the caller (exactly) and D1 is kept in fp64.  Outputs are overwritten (the
@@ -45,6 +49,20 @@ static void gemm_row(int64_t i, int64_t bcol, int64_t ccol,
     }
 }
 
+/* D1[i][:] = B[i][:] * Ct^T for one row i.  B is n x bcol, Ct is ccol x bcol, D1 is n x ccol. */
+static void gemm_ct_row(int64_t i, int64_t bcol, int64_t ccol,
+                        const double *B, const double *Ct, double *D1)
+{
+    for (int64_t c = 0; c < ccol; ++c) {
+        double acc = 0.0;
+        for (int64_t k = 0; k < bcol; ++k) {
+            double prod = B[i * bcol + k] * Ct[c * bcol + k];
+            acc = acc + prod;
+        }
+        D1[i * ccol + c] = acc;
+    }
+}
+
 /* Y[j][:] = sum over stored entries of row j of  vals * X[col][:].  X and Y have ccol columns. */
 static void spmm_row(int64_t j, const int32_t *rowptr, const int32_t *colidx,
                      const double *vals, int64_t ccol, const double *X, double *Y)
@@ -66,6 +84,16 @@ void orc_gemm(int64_t n, int64_t bcol, int64_t ccol, const double *B, const doub
         for (int64_t r = 0; r < n_rows_listed; ++r) gemm_row(rows[r], bcol, ccol, B, C, D1);
     } else {
         for (int64_t i = 0; i < n; ++i) gemm_row(i, bcol, ccol, B, C, D1);
+    }
+}
+
+void orc_gemm_ct(int64_t n, int64_t bcol, int64_t ccol, const double *B, const double *Ct,
+                 double *D1, const int64_t *rows, int64_t n_rows_listed)
+{
+    if (rows) {
+        for (int64_t r = 0; r < n_rows_listed; ++r) gemm_ct_row(rows[r], bcol, ccol, B, Ct, D1);
+    } else {
+        for (int64_t i = 0; i < n; ++i) gemm_ct_row(i, bcol, ccol, B, Ct, D1);
     }
 }
 

@@ -15,6 +15,7 @@ TF_F32, TF_F64 = 0, 1
 TF_FLAG_NO_SPLIT = 1
 TF_FLAG_SCHEDULE_ONLY = 2
 TF_FLAG_REORDER = 4
+TF_FLAG_C_TRANSPOSED = 8
 
 _STATUS = {0: "TF_OK", 1: "TF_EINVAL", 2: "TF_EBADCSR", 3: "TF_ENOMEM", 4: "TF_EHIP",
            5: "TF_EUNSUPPORTED", 6: "TF_EMISMATCH"}

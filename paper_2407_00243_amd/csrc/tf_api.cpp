@@ -50,6 +50,7 @@ struct tf_plan {
     int device = 0;
     int64_t lds_per_cu = 160 * 1024;
     bool schedule_only = false;
+    bool c_transposed = false;             // dense-B calls take C as cCol x bCol (D = A (B C^T))
     tf::Schedule s;
     double plan_seconds = 0.0;
     struct PackBufs {
@@ -118,6 +119,8 @@ tf::FusedLaunch fused_args(const tf_plan *p, const void *C, void *D) {
     a.tile_desc = static_cast<const tf::TileDesc *>(p->tile_desc.p);
     a.tile_meta = static_cast<const unsigned char *>(p->tile_meta.p);
     a.C = C;
+    a.c_ldk = p->c_transposed ? 1 : a.ccol;
+    a.c_ldc = p->c_transposed ? a.bcol : 1;
     a.D = D;
     a.D1 = p->d1.p;
     return a;
@@ -196,6 +199,8 @@ tf_status tf_plan_create(const tf_csr *A, int64_t bCol, int64_t cCol, int32_t b_
         return fail(TF_EINVAL, "negative tile parameter");
 
     const bool schedule_only = tp && (tp->flags & TF_FLAG_SCHEDULE_ONLY);
+    if (tp && (tp->flags & TF_FLAG_C_TRANSPOSED) && b_is_sparse)
+        return fail(TF_EUNSUPPORTED, "TF_FLAG_C_TRANSPOSED needs a dense B: a sparse B gathers rows of C");
     if (schedule_only && A->on_device)
         return fail(TF_EINVAL, "TF_FLAG_SCHEDULE_ONLY needs A in host memory");
     const int64_t n = A->n_rows, nnz = A->nnz;
@@ -238,6 +243,7 @@ tf_status tf_plan_create(const tf_csr *A, int64_t bCol, int64_t cCol, int32_t b_
         p->dtype = A->dtype;
         p->b_is_sparse = b_is_sparse ? 1 : 0;
         p->schedule_only = schedule_only;
+        p->c_transposed = tp && (tp->flags & TF_FLAG_C_TRANSPOSED);
         if (!schedule_only) (void)hipGetDevice(&p->device);
 
         tf::InspectorInput in{};
@@ -439,6 +445,8 @@ tf_status tf_unfused_gemm_spmm(const tf_plan *p, const void *B, const void *C, v
     g.n_slices = (int32_t)((p->ccol + g.cs - 1) / g.cs);
     g.B = B;
     g.C = C;
+    g.c_ldk = p->c_transposed ? 1 : g.ccol;
+    g.c_ldc = p->c_transposed ? g.bcol : 1;
     g.D1 = p->d1.p;
     int e = tf::launch_gemm(g, stream);
     if (e) return hip_fail((hipError_t)e, "launching the GeMM");

@@ -222,6 +222,7 @@ struct FusedLaunch {
     const void *B;                    // dense B (gemm) or nullptr
     CsrDev Bs;                        // sparse B (spmm)
     const void *C;
+    int32_t c_ldk, c_ldc;             // dense B: element (k, c) of the multiplier is C[k c_ldk + c c_ldc]
     void *D;
     void *D1;
 };
@@ -254,6 +255,7 @@ struct GemmLaunch {
     int64_t n;
     int32_t bcol, ccol, cs, n_slices;
     const void *B, *C;
+    int32_t c_ldk, c_ldc;             // element (k, c) of the multiplier is C[k c_ldk + c c_ldc]
     void *D1;
 };
 

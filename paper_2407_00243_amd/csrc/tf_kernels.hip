@@ -139,8 +139,8 @@ __device__ __forceinline__ bool tile_and_slice(int bid, int n_tiles, int n_slice
 // The product is formed transposed (C^T in the first operand, B^T in the second), which leaves
 // lane (g, r) with D1[row r][16 nb + 4 g .. + 3]: four contiguous columns, one vector store.
 template <typename T, int NB>
-__device__ __forceinline__ void stage_c_slice(T *Cl, const T *__restrict__ C, int bcol, int ccol,
-                                              int c0, int w) {
+__device__ __forceinline__ void stage_c_slice(T *Cl, const T *__restrict__ C, int bcol, int ldk,
+                                              int ldc, int c0, int w) {
     constexpr int V = Tr<T>::V, KC = 4 * V;
     const int ksteps = (bcol + KC - 1) / KC;
     const int total = ksteps * V * NB * 64;
@@ -157,7 +157,7 @@ __device__ __forceinline__ void stage_c_slice(T *Cl, const T *__restrict__ C, in
             const int k = KC * (sq / V) + V * (l >> 4) + (sq % V);
             const int col = 16 * nb + Tr<T>::col_of_m(l & 15);
             const bool in = e < total && k < bcol && col < w;
-            tmp[u] = C[in ? (int64_t)k * ccol + c0 + col : 0];
+            tmp[u] = C[in ? (int64_t)k * ldk + (int64_t)(c0 + col) * ldc : 0];
             if (!in) tmp[u] = T(0);
         }
 #pragma unroll
@@ -169,22 +169,23 @@ __device__ __forceinline__ void stage_c_slice(T *Cl, const T *__restrict__ C, in
 }
 
 // The operands of the C slice that one lane feeds to the MFMAs, straight from device memory
-// (what stage_c_slice would put at Cl[i * 64 + lane]); bCol = KC * KS exactly.
+// (what stage_c_slice would put at Cl[i * 64 + lane]); bCol = KC * KS exactly.  Element (k, c) of
+// the multiplier is C[k ldk + c ldc] (ldc = 1 for C as given, ldk = 1 for its transpose).
 template <typename T, int NB, int KS>
 __device__ __forceinline__ void load_c_regs(T (&creg)[KS * Tr<T>::V * NB], const T *__restrict__ C,
-                                            int ccol, int c0, int w, int lane) {
+                                            int ldk, int ldc, int c0, int w, int lane) {
     constexpr int V = Tr<T>::V, KC = 4 * V;
     // element (k, col) with k = V (lane / 16) + [KC (sq / V) + sq % V] and col = col_of_m(lane % 16)
     // + [16 nb]: a per-lane offset plus a wave-uniform one (the bracketed parts)
     const int lcol = Tr<T>::col_of_m(lane & 15);
-    const uint32_t lane_off = (uint32_t)(V * (lane >> 4) * ccol + lcol);
-    const T *base = C + c0;
+    const uint32_t lane_off = (uint32_t)(V * (lane >> 4) * ldk + lcol * ldc);
+    const T *base = C + (int64_t)c0 * ldc;
 #pragma unroll
     for (int i = 0; i < KS * V * NB; ++i) {
         const int nb = i % NB, sq = i / NB;
         const int ku = KC * (sq / V) + (sq % V);
         const bool in = 16 * nb + lcol < w;
-        creg[i] = (base + (ku * ccol + 16 * nb))[in ? lane_off : 0u];
+        creg[i] = (base + (ku * ldk + 16 * nb * ldc))[in ? lane_off : 0u];
         if (!in) creg[i] = T(0);
     }
 }
@@ -747,8 +748,9 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
                 for (int i = 0; i < ND - 1; ++i) load_b_frag<T, KSF>(fb[i], B + row0[i] * a.bcol, g);
             }
         }
-        if constexpr (CREG) load_c_regs<T, NB, KSF>(creg, static_cast<const T *>(a.C), a.ccol, c0, w, lane);
-        else stage_c_slice<T, NB>(Cl, static_cast<const T *>(a.C), a.bcol, a.ccol, c0, w);
+        const T *Cg = static_cast<const T *>(a.C);
+        if constexpr (CREG) load_c_regs<T, NB, KSF>(creg, Cg, a.c_ldk, a.c_ldc, c0, w, lane);
+        else stage_c_slice<T, NB>(Cl, Cg, a.bcol, a.c_ldk, a.c_ldc, c0, w);
         __syncthreads();
     }
 
@@ -1151,7 +1153,8 @@ __global__ __launch_bounds__(kFusedThreads) void k_gemm(const GemmLaunch a) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = blockDim.x >> 6;
     const int g = lane >> 4, r = lane & 15;
     T *Cl = reinterpret_cast<T *>(tf_smem);
-    stage_c_slice<T, NB>(Cl, static_cast<const T *>(a.C), a.bcol, a.ccol, c0, w);
+    stage_c_slice<T, NB>(Cl, static_cast<const T *>(a.C), a.bcol, a.c_ldk, a.c_ldc, c0,
+                         w);
     __syncthreads();
     const int64_t nblk = (a.n + 15) >> 4;
     const T *__restrict__ B = static_cast<const T *>(a.B);

@@ -23,13 +23,17 @@ class Case:
     def __init__(self, prob, **params):
         self.prob = prob
         self.sparse = prob.kind == "spmm_spmm"
-        self.plan = tf.Plan(prob.A, prob.bcol, prob.ccol, self.sparse, **params)
+        # with TF_FLAG_C_TRANSPOSED prob.C holds the cCol x bCol array
+        self.bcol, self.ccol = prob.C.shape
+        if params.get("flags", 0) & tf.TF_FLAG_C_TRANSPOSED:
+            self.bcol, self.ccol = self.ccol, self.bcol
+        self.plan = tf.Plan(prob.A, self.bcol, self.ccol, self.sparse, **params)
         self.B = dev_csr(prob.B) if self.sparse else dev(prob.B)
         self.C = dev(prob.C)
         self.tdtype = torch.float32 if prob.dtype == np.float32 else torch.float64
 
     def run(self, fused=True, fill=float("nan")):
-        D = torch.full((self.prob.n, self.prob.ccol), fill, dtype=self.tdtype, device="cuda")
+        D = torch.full((self.prob.n, self.ccol), fill, dtype=self.tdtype, device="cuda")
         stream = torch.cuda.current_stream().cuda_stream
         if fused:
             self.plan.run(self.B, self.C, D, stream)

@@ -135,6 +135,54 @@ def test_every_specialised_gemm_shape_bit_exact(dtype, bcol, ccol):
 
 
 @pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("bcol,ccol", [(16, 32), (32, 16), (64, 64), (128, 128), (64, 128),
+                                       (256, 48), (20, 12), (7, 5), (48, 160)])
+def test_transposed_c_bit_exact(dtype, bcol, ccol):
+    """D = A (B C^T) with C handed over as cCol x bCol (Section 3.2): the shapes cover the C
+    operands in registers, in LDS, the generic k loop and two column slices; non-square shapes
+    make a swapped stride read a different element.  Integer entries, so bit-exact."""
+    import paper_2407_00243_amd as tf
+    n = 333
+    A = ti.random_local_csr(n, 5, 6, 0.1, dtype, 51, int_values=True)
+    B = ti.dense_small_int(n, bcol, dtype, 52)
+    Ct = ti.dense_small_int(ccol, bcol, dtype, 53)
+    D_ref, _ = oracle.chain_ct(A, B, Ct)
+    # the case tells the two readings of the array apart
+    assert not np.array_equal(D_ref, oracle.chain(A, B, Ct.reshape(bcol, ccol))[0])
+    prob = ti.Problem("transposed C", "gemm_spmm", np.dtype(dtype), A, B, Ct)
+    for flags in (tf.TF_FLAG_C_TRANSPOSED, tf.TF_FLAG_C_TRANSPOSED | tf.TF_FLAG_REORDER):
+        c = _case(prob, ct_size=100, p=1, flags=flags)
+        try:
+            assert 0 < c.plan.schedule()["n_fused_rows"] < n
+            for fused in (True, False):
+                assert np.array_equal(c.run(fused=fused).astype(np.float64), D_ref), (flags, fused)
+        finally:
+            c.close()
+
+
+@pytest.mark.parametrize("cfg,scale,params", [(1, 1000, dict(ct_size=128, p=1)),
+                                              (2, 96, dict(ct_size=1024, p=1)),
+                                              (3, 12, dict(ct_size=2048, p=32))])
+def test_transposed_c_small_configs(cfg, scale, params):
+    """The dense-B configurations with C handed over transposed: same result as the oracle's
+    chain with C^T, to the floating-point bar."""
+    import paper_2407_00243_amd as tf
+    from gpu_util import TOL
+    prob = ti.config(cfg, scale_down=scale)
+    Ct = np.ascontiguousarray(prob.C.T)
+    D_ref, W = oracle.chain_ct(prob.A, prob.B, Ct)
+    tprob = ti.Problem(prob.name + " Ct", "gemm_spmm", prob.dtype, prob.A, prob.B, Ct)
+    c = _case(tprob, flags=tf.TF_FLAG_C_TRANSPOSED, **params)
+    try:
+        for fused in (True, False):
+            D = c.run(fused=fused)
+            assert np.all(np.isfinite(D))
+            assert oracle.rowwise_rel_err(D, D_ref, W) <= TOL[np.dtype(prob.dtype)], fused
+    finally:
+        c.close()
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
 @pytest.mark.parametrize("kind", ["gemm_spmm", "spmm_spmm"])
 def test_packed_entries_too_large_for_lds_are_read_in_place(dtype, kind):
     """One tile holds a dense 64 x 64 block of A (64 fused rows of 64 entries) while the average

@@ -174,6 +174,15 @@ def test_error_paths():
     assert bad(A._replace(colidx=ci)) == "TF_EBADCSR"
     assert bad(A._replace(n_cols=33)) == "TF_EINVAL"           # not square
     assert "square" in tf.tf_last_error()
+    # the transpose of C is a dense-B variant; it leaves the schedule as it is
+    with pytest.raises(tf.TfError) as e:
+        tf.Plan(A, 4, 4, True, flags=SO | tf.TF_FLAG_C_TRANSPOSED)
+    assert e.value.status_name == "TF_EUNSUPPORTED"
+    with tf.Plan(A, 4, 8, False, flags=SO) as p0, \
+            tf.Plan(A, 4, 8, False, flags=SO | tf.TF_FLAG_C_TRANSPOSED) as p1:
+        s0, s1 = p0.schedule(), p1.schedule()
+        assert np.array_equal(s0["first_rows"], s1["first_rows"])
+        assert np.array_equal(s0["second_rows"], s1["second_rows"])
     # a schedule-only plan cannot execute
     with tf.Plan(A, 4, 4, False, flags=SO) as pl:
         with pytest.raises(tf.TfError) as e:

@@ -262,3 +262,35 @@ def test_error_metric_flags_nonzero_in_empty_row():
     T[2, 1] = 3e-6
     assert abs(oracle.rowwise_rel_err(T, D, W) - 1e-6) < 1e-18
     assert abs(oracle.elementwise_rel_err(T, D, W) - 3e-6) < 1e-18
+
+
+# ---- the chain with the transpose of C (Section 3.2)
+
+def test_transposed_c_hand_worked():
+    """B = [1 2], Ct = [[3 4], [5 6]]: B Ct^T = [1*3 + 2*4, 1*5 + 2*6] = [11 17], whereas the
+    plain product B Ct = [13 16]; a transposed index gives the other one."""
+    B = np.array([[1.0, 2.0]])
+    Ct = np.array([[3.0, 4.0], [5.0, 6.0]])
+    assert np.array_equal(oracle.gemm_ct(B, Ct), [[11.0, 17.0]])
+    assert np.array_equal(oracle.gemm(B, Ct), [[13.0, 16.0]])
+
+
+@pytest.mark.parametrize("seed", [1, 2])
+def test_transposed_c_brute_force(seed):
+    n, bcol, ccol = 11, 5, 7          # non-square: a wrong stride reads the wrong element
+    A = ti.random_pattern_csr(n, n, 0.3, np.float64, seed, sort_cols=False, duplicates=True,
+                              empty_row_prob=0.2)
+    B = ti.dense_normal(n, bcol, np.float64, seed + 10)
+    Ct = ti.dense_normal(ccol, bcol, np.float64, seed + 20)
+    D, W = oracle.chain_ct(A, B, Ct)
+    ref = brute_force_chain(A, B, np.ascontiguousarray(Ct.T))
+    k = bcol + int(np.diff(A.rowptr).max())
+    assert np.all(np.abs(D - ref.astype(np.float64)) <= 2 * gamma(k) * W + 1e-300)
+    # same summation order as the plain chain on the explicitly transposed array: bit-identical
+    D2, W2 = oracle.chain(A, B, np.ascontiguousarray(Ct.T))
+    assert np.array_equal(D, D2) and np.array_equal(W, W2)
+    # listed rows only: the others stay untouched
+    out = np.full((n, ccol), 7.0)
+    oracle.gemm_ct(B, Ct, rows=[2, 5], out=out)
+    full = oracle.gemm_ct(B, Ct)
+    assert np.array_equal(out[[2, 5]], full[[2, 5]]) and np.all(np.delete(out, [2, 5], 0) == 7.0)
