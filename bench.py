@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the fused chain D = A(BC) on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5] [--no-cpu] [tile options]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5] [--no-cpu] [--skip-unread] [tile options]
 
 A step is one fused execution (first wavefront + second wavefront) of the workload; the
 schedule is built once before the timed region and its time is reported separately, as the
@@ -63,6 +63,9 @@ def parse():
     ap.add_argument("--col-slice", type=int, default=None)
     ap.add_argument("--fast-mem", type=int, default=None)
     ap.add_argument("--reorder", type=int, default=None, help="1: graph-grown tiles, 0: consecutive")
+    ap.add_argument("--skip-unread", action="store_true",
+                    help="opt in to TF_FLAG_SKIP_UNREAD (D1 rows that no row of A reads are not "
+                         "computed by the fused path; the useful-FLOP count is left as it is)")
     ap.add_argument("--calibrate-copy", type=int, default=0, metavar="MIB",
                     help="instead of the benchmark, run 10 plain device copies of MIB MiB (for "
                          "scaling the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
@@ -116,6 +119,9 @@ def main():
     if args.reorder is not None:
         params["flags"] = (params.get("flags", 0) & ~tf.TF_FLAG_REORDER) | \
             (tf.TF_FLAG_REORDER if args.reorder else 0)
+
+    if args.skip_unread:
+        params["flags"] = params.get("flags", 0) | tf.TF_FLAG_SKIP_UNREAD
 
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
     n, bcol, ccol = prob.n, prob.bcol, prob.ccol
@@ -278,6 +284,7 @@ def main():
         "fused_ratio": {"eq3": sched["fused_ratio_eq3"], "rows": sched["fused_ratio_rows"],
                         "nnz": sched["fused_ratio_nnz"]},
         "spill_fraction": sched["n_spill_rows"] / max(n, 1),
+        "first_rows_fraction": sched["n_first_rows"] / max(n, 1),
         "schedule": {"t": sched["t"], "tiles": sched["n_tiles"], "col_slice": sched["col_slice"],
                      "wf1_units": sched["n_wf1_units"], "eq2_cost_max": sched["eq2_cost_max"]},
         "plan_ms": min(plan_seconds) * 1e3,

@@ -85,12 +85,19 @@ typedef struct tf_tile_params {
  * plans for a dense B accept the flag (a sparse B gathers whole rows of C; plan creation fails
  * with TF_EUNSUPPORTED). */
 #define TF_FLAG_C_TRANSPOSED 8u
+/* Rows of D1 = B C that no row of A reads (columns of A without a stored entry) are not computed
+ * by the fused calls: they leave the tiles' first lists.  The paper's schedule runs every
+ * iteration of both operations exactly once (Section 3.1); this flag gives that up for the first
+ * operation, D is unchanged.  The unfused calls still compute all of D1, and after a fused call
+ * the workspace rows of skipped D1 rows are not written. */
+#define TF_FLAG_SKIP_UNREAD 16u
 
 typedef struct tf_plan tf_plan; /* opaque, library-owned */
 
 /* Host-readable view of a plan's schedule.  All pointers are HOST memory owned by the plan and
  * stay valid until tf_plan_destroy.  A tile v of the first wavefront produces the D1 rows
- *   first_rows[tile_first_ptr[v] .. tile_first_ptr[v+1])      (the tile's "first" list)
+ *   first_rows[tile_first_ptr[v] .. tile_first_ptr[v+1])      (the tile's "first" list;
+ *                                         n_first_rows entries in all: n unless rows are skipped)
  * and then computes the rows of D
  *   second_rows[tile_second_ptr[v] .. tile_second_ptr[v+1])   (the tile's "second" list);
  * unit u of the second wavefront computes the rows wf1_rows[wf1_unit_ptr[u] .. wf1_unit_ptr[u+1]).
@@ -135,6 +142,7 @@ typedef struct tf_schedule_view {
     int64_t alg_bytes_unfused;  /* the same for the unfused two-kernel execution               */
     int64_t second_block_bytes; /* largest per-tile block of packed entries (fused rows)       */
     int64_t lds_launch_bytes;   /* LDS one fused workgroup is launched with (0: schedule only) */
+    int64_t n_first_rows;       /* D1 rows the first wavefront produces (length of first_rows) */
 } tf_schedule_view;
 
 /* Inspector: builds the fused schedule for the pattern of A (Algorithm 1: step 1, coarse tile

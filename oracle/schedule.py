@@ -162,7 +162,8 @@ class ScheduleError(AssertionError):
 def validate(rowptr, colidx, tiles: Sequence[Tuple[np.ndarray, np.ndarray]],
              wf1_units: Sequence[np.ndarray], spill: np.ndarray,
              tile_cost: Optional[Callable[[int], int]] = None,
-             fast_mem: Optional[int] = None, check_maximal: bool = True) -> Dict:
+             fast_mem: Optional[int] = None, check_maximal: bool = True,
+             unread_may_be_skipped: bool = False) -> Dict:
     """Checks a schedule given in its most general form.
 
     tiles      sequence of (first, second): the first-operation rows the tile produces and the
@@ -172,6 +173,8 @@ def validate(rowptr, colidx, tiles: Sequence[Tuple[np.ndarray, np.ndarray]],
 
     Raises ScheduleError naming the violated property:
       V1  every first-operation row is produced by exactly one first-wavefront tile
+          (with unread_may_be_skipped: every row that some row of A reads exactly once, the
+          others at most once; V7 then needs check_maximal=False, a skipped row has no tile)
       V2  every second-operation row runs exactly once over both wavefronts
       V3  every incoming edge of a fused row is a first-operation row of the same tile
       V4  every incoming edge of a second-wavefront row is spilled
@@ -191,8 +194,13 @@ def validate(rowptr, colidx, tiles: Sequence[Tuple[np.ndarray, np.ndarray]],
             raise ScheduleError(f"V1: tile {v} lists a first-operation row outside [0, n)")
         np.add.at(produced, first, 1)
         tile_of[first] = v
-    if np.any(produced != 1):
-        bad = int(np.nonzero(produced != 1)[0][0])
+    wrong = produced != 1
+    if unread_may_be_skipped:
+        is_read = np.zeros(n, dtype=bool)
+        is_read[colidx] = True
+        wrong = np.where(is_read, produced != 1, produced > 1)
+    if np.any(wrong):
+        bad = int(np.nonzero(wrong)[0][0])
         raise ScheduleError(f"V1: first-operation row {bad} produced {int(produced[bad])} times")
 
     runs = np.zeros(n, dtype=np.int64)

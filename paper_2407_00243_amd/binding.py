@@ -16,6 +16,7 @@ TF_FLAG_NO_SPLIT = 1
 TF_FLAG_SCHEDULE_ONLY = 2
 TF_FLAG_REORDER = 4
 TF_FLAG_C_TRANSPOSED = 8
+TF_FLAG_SKIP_UNREAD = 16
 
 _STATUS = {0: "TF_OK", 1: "TF_EINVAL", 2: "TF_EBADCSR", 3: "TF_ENOMEM", 4: "TF_EHIP",
            5: "TF_EUNSUPPORTED", 6: "TF_EMISMATCH"}
@@ -68,7 +69,8 @@ class tf_schedule_view(ctypes.Structure):
                 ("second_block_in_lds", ctypes.c_int32),
                 ("eq2_cost_max", ctypes.c_double), ("plan_seconds", ctypes.c_double),
                 ("alg_bytes", ctypes.c_int64), ("alg_bytes_unfused", ctypes.c_int64),
-                ("second_block_bytes", ctypes.c_int64), ("lds_launch_bytes", ctypes.c_int64)]
+                ("second_block_bytes", ctypes.c_int64), ("lds_launch_bytes", ctypes.c_int64),
+                ("n_first_rows", ctypes.c_int64)]
 
 
 EXPORTS = ["tf_plan_create", "tf_plan_destroy", "tf_plan_schedule", "tf_plan_workspace",
@@ -200,7 +202,7 @@ def tf_plan_schedule(plan: int) -> dict:
            if not name.startswith("reserved")}
     nt, nu = v.n_tiles, v.n_wf1_units
     out["tile_first_ptr"] = _np_copy(v.tile_first_ptr, nt + 1, np.int32)
-    out["first_rows"] = _np_copy(v.first_rows, v.n, np.int32)
+    out["first_rows"] = _np_copy(v.first_rows, v.n_first_rows, np.int32)
     out["tile_second_ptr"] = _np_copy(v.tile_second_ptr, nt + 1, np.int32)
     out["second_rows"] = _np_copy(v.second_rows, v.n_fused_rows, np.int32)
     out["wf1_unit_ptr"] = _np_copy(v.wf1_unit_ptr, nu + 1, np.int32)

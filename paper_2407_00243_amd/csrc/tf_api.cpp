@@ -347,9 +347,11 @@ tf_status tf_plan_schedule(const tf_plan *p, tf_schedule_view *v) {
     // out), C once, D once, and every spilled D1 row written once and read once
     const int64_t a_bytes = 4 * (p->n + 1) + p->nnz * (4 + es);
     const int64_t b_bytes = p->b_is_sparse ? 0 : p->n * p->bcol * es;
+    const int64_t b_read = p->b_is_sparse ? 0 : (int64_t)s.first_rows.size() * p->bcol * es;
     const int64_t c_bytes = p->bcol * p->ccol * es;
     const int64_t d_bytes = p->n * p->ccol * es;
-    v->alg_bytes = a_bytes + b_bytes + c_bytes + d_bytes + 2 * s.n_spill_rows * p->ccol * es;
+    v->n_first_rows = (int64_t)s.first_rows.size();
+    v->alg_bytes = a_bytes + b_read + c_bytes + d_bytes + 2 * s.n_spill_rows * p->ccol * es;
     v->alg_bytes_unfused = a_bytes + b_bytes + c_bytes + 3 * d_bytes;
     v->second_block_in_lds = s.second_block_in_lds ? 1 : 0;
     v->second_block_bytes = s.second_block_cap;

@@ -370,18 +370,39 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
         return TF_EUNSUPPORTED;
     }
     std::vector<int32_t> wf1;
-    std::vector<int32_t> tile_of((size_t)n), local_of((size_t)n);
-    for (int64_t vt = 0; vt < nt; ++vt)
-        for (int64_t q = s.tile_first_ptr[vt]; q < s.tile_first_ptr[vt + 1]; ++q) {
-            tile_of[s.first_rows[q]] = (int32_t)vt;
-            local_of[s.first_rows[q]] = (int32_t)(q - s.tile_first_ptr[vt]);
+    // A row belongs to one tile: there it is a candidate for fusion and there its D1 row is
+    // produced.  With TF_FLAG_SKIP_UNREAD the D1 rows that no row of A reads are not produced at
+    // all: they leave the tiles' first lists (a tile keeps at least one row) and get no place in LDS.
+    std::vector<int32_t> member_ptr = s.tile_first_ptr, member_rows = s.first_rows;
+    if (in.flags & TF_FLAG_SKIP_UNREAD) {
+        std::vector<uint8_t> read((size_t)n, 0);
+        for (int64_t q = 0; q < in.nnz; ++q) read[in.colidx[q]] = 1;
+        int64_t kept = 0;
+        s.max_tile_rows = 0;
+        for (int64_t vt = 0; vt < nt; ++vt) {
+            const int64_t before = kept;
+            for (int64_t q = member_ptr[vt]; q < member_ptr[vt + 1]; ++q)
+                if (read[member_rows[q]]) s.first_rows[kept++] = member_rows[q];
+            if (kept == before && member_ptr[vt + 1] > member_ptr[vt])
+                s.first_rows[kept++] = member_rows[member_ptr[vt]];
+            s.tile_first_ptr[vt + 1] = (int32_t)kept;
+            s.max_tile_rows = std::max(s.max_tile_rows, kept - before);
         }
+        s.first_rows.resize((size_t)kept);
+    }
+    std::vector<int32_t> tile_of((size_t)n), local_of((size_t)n, 0);
+    for (int64_t vt = 0; vt < nt; ++vt) {
+        for (int64_t q = member_ptr[vt]; q < member_ptr[vt + 1]; ++q)
+            tile_of[member_rows[q]] = (int32_t)vt;
+        for (int64_t q = s.tile_first_ptr[vt]; q < s.tile_first_ptr[vt + 1]; ++q)
+            local_of[s.first_rows[q]] = (int32_t)(q - s.tile_first_ptr[vt]);
+    }
     std::vector<int32_t> seen((size_t)n, -1);      // Eq. 2: distinct columns per tile
     for (int64_t vt = 0; vt < nt; ++vt) {
         std::vector<int32_t> tile_rows;
         int64_t tile_nnz = 0, uc = 0;
-        for (int64_t fq = s.tile_first_ptr[vt]; fq < s.tile_first_ptr[vt + 1]; ++fq) {
-            const int64_t j = s.first_rows[fq];
+        for (int64_t fq = member_ptr[vt]; fq < member_ptr[vt + 1]; ++fq) {
+            const int64_t j = member_rows[fq];
             // (a row of 32768 entries or more, possible only with duplicates, is left to the second
             // wavefront: the tile units store lengths in 15 bits)
             bool inside = in.rowptr[j + 1] - in.rowptr[j] < 32768;

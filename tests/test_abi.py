@@ -37,4 +37,4 @@ def test_struct_layouts_match_the_header():
     assert ctypes.sizeof(binding.tf_csr) == 3 * 8 + 3 * 8 + 2 * 4
     assert ctypes.sizeof(binding.tf_tile_params) == 4 + 4 + 8 + 4 + 4
     assert ctypes.sizeof(binding.tf_schedule_view) == 2 * 8 + 6 * 4 + 2 * 8 + 4 * 8 + 8 + 3 * 8 + \
-        4 * 8 + 3 * 8 + 3 * 8 + 2 * 4 + 2 * 8 + 2 * 8 + 2 * 8
+        4 * 8 + 3 * 8 + 3 * 8 + 2 * 4 + 2 * 8 + 2 * 8 + 2 * 8 + 8

@@ -184,6 +184,36 @@ def test_transposed_c_small_configs(cfg, scale, params):
 
 @pytest.mark.parametrize("dtype", [np.float32, np.float64])
 @pytest.mark.parametrize("kind", ["gemm_spmm", "spmm_spmm"])
+@pytest.mark.parametrize("reorder", [0, 1])
+def test_unread_d1_rows_skipped(dtype, kind, reorder):
+    """TF_FLAG_SKIP_UNREAD on a graph with many edgeless vertices: D is the oracle's bit for bit
+    (integer entries) although about half of the D1 rows are never computed."""
+    import paper_2407_00243_amd as tf
+    A0 = ti.config(5, scale_down=11).A
+    n = A0.n_rows
+    rng = np.random.default_rng(5)
+    A = ti.Csr(n, n, A0.rowptr, A0.colidx, rng.integers(-2, 3, A0.colidx.size).astype(dtype))
+    bcol, ccol = 24, 40
+    if kind == "gemm_spmm":
+        B = ti.dense_small_int(n, bcol, dtype, 61)
+    else:
+        B = ti.random_pattern_csr(n, bcol, 0.2, dtype, 61, int_values=True)
+    C = ti.dense_small_int(bcol, ccol, dtype, 62)
+    prob = ti.Problem("unread rows", kind, np.dtype(dtype), A, B, C)
+    D_ref, _ = oracle.chain(A, B, C)
+    flags = tf.TF_FLAG_SKIP_UNREAD | (tf.TF_FLAG_REORDER if reorder else 0)
+    c = _case(prob, ct_size=128, p=1, flags=flags)
+    try:
+        s = c.plan.schedule()
+        assert s["n_first_rows"] < 0.8 * n
+        assert np.array_equal(c.run().astype(np.float64), D_ref)
+        assert np.array_equal(c.run(fused=False).astype(np.float64), D_ref)
+    finally:
+        c.close()
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("kind", ["gemm_spmm", "spmm_spmm"])
 def test_packed_entries_too_large_for_lds_are_read_in_place(dtype, kind):
     """One tile holds a dense 64 x 64 block of A (64 fused rows of 64 entries) while the average
     row has 5 entries: the tile's packed entries exceed what the schedule set aside beside the

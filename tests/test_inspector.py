@@ -134,6 +134,40 @@ def test_schedule_view_reports_the_second_phase_blocks():
     assert s["second_block_in_lds"] == 1 and s["lds_launch_bytes"] == 0      # schedule only
 
 
+@pytest.mark.parametrize("reorder", [0, 1])
+def test_unread_rows_leave_the_first_lists(reorder):
+    """TF_FLAG_SKIP_UNREAD: the first lists are those of the plain plan without the rows that no
+    row of A reads (a tile whose rows are all unread keeps its first); second lists, second
+    wavefront and spill set do not change."""
+    from oracle import schedule as so
+    prob = ti.config(5, scale_down=12)            # R-MAT: many vertices without an edge
+    A = prob.A
+    read = np.zeros(A.n_rows, bool)
+    read[A.colidx] = True
+    assert 0.2 < read.mean() < 0.9
+    base = tf.TF_FLAG_REORDER if reorder else 0
+    s0 = plan_schedule(A, 8, 32, True, ct_size=200, p=1, flags=base)
+    s1 = plan_schedule(A, 8, 32, True, ct_size=200, p=1, flags=base | tf.TF_FLAG_SKIP_UNREAD)
+    assert s0["n_first_rows"] == A.n_rows and s1["n_first_rows"] == s1["first_rows"].size
+    for key in ("second_rows", "tile_second_ptr", "wf1_rows", "wf1_unit_ptr", "spill"):
+        assert np.array_equal(s0[key], s1[key]), key
+    all_unread = 0
+    for (f0, _), (f1, _) in zip(tiles_of(s0), tiles_of(s1)):
+        keep = f0[read[f0]]
+        if keep.size == 0:
+            keep = f0[:1]
+            all_unread += 1
+        assert np.array_equal(f1, keep)
+    assert s1["n_first_rows"] == int(read.sum()) + all_unread
+    so.validate(A.rowptr, A.colidx, tiles_of(s1), units_of(s1), s1["spill"].astype(bool),
+                check_maximal=False, unread_may_be_skipped=True)
+    # a matrix with a full diagonal has no unread row: nothing changes
+    B = ti.config(3, scale_down=12).A
+    t0 = plan_schedule(B, 16, 16, False, ct_size=200, p=1)
+    t1 = plan_schedule(B, 16, 16, False, ct_size=200, p=1, flags=tf.TF_FLAG_SKIP_UNREAD)
+    assert np.array_equal(t0["first_rows"], t1["first_rows"])
+
+
 def test_degenerate_inputs():
     empty = ti.Csr(0, 0, np.zeros(1, np.int32), np.zeros(0, np.int32), np.zeros(0, np.float32))
     s = plan_schedule(empty, 4, 4, False)

@@ -155,6 +155,34 @@ def test_validator_catches_planted_mistakes():
     assert so.validate(A.rowptr, A.colidx, tiles, units, s2)["superfluous_spill"] > 0
 
 
+def test_validator_with_unread_rows_skipped():
+    """A pattern whose columns 3 and 7 are read by no row: their first-operation rows may be
+    missing from the tiles when the option says so, a row that is read may not."""
+    n = 10
+    cols = [[0, 1], [1], [2, 4], [4], [4, 5], [5], [6], [6, 8], [8, 9], [9]]
+    rowptr = np.cumsum([0] + [len(c) for c in cols])
+    colidx = np.concatenate(cols)
+    res = so.algorithm1(rowptr, colidx, ct_size=5, p=1)
+    tiles, units = as_general(res, n)
+    so.validate(rowptr, colidx, tiles, units, res["spill"])
+    drop = lambda first, r: first[first != r]
+    skipped = [(drop(tiles[0][0], 3), tiles[0][1]), (drop(tiles[1][0], 7), tiles[1][1])]
+    with pytest.raises(so.ScheduleError, match="V1"):
+        so.validate(rowptr, colidx, skipped, units, res["spill"], check_maximal=False)
+    so.validate(rowptr, colidx, skipped, units, res["spill"], check_maximal=False,
+                unread_may_be_skipped=True)
+    # row 4 is read: it has to stay
+    bad = [(drop(tiles[0][0], 4), tiles[0][1]), tiles[1]]
+    with pytest.raises(so.ScheduleError, match="V1"):
+        so.validate(rowptr, colidx, bad, units, res["spill"], check_maximal=False,
+                    unread_may_be_skipped=True)
+    # an unread row may still not be produced twice
+    twice = [(np.append(tiles[0][0], 7), tiles[0][1]), tiles[1]]
+    with pytest.raises(so.ScheduleError, match="V1"):
+        so.validate(rowptr, colidx, twice, units, res["spill"], check_maximal=False,
+                    unread_may_be_skipped=True)
+
+
 def test_fused_ratio_forms():
     n, h, t = 512, 4, 64
     A = ti.banded(n, h, np.float64, 4)
