@@ -63,6 +63,11 @@ def parse():
     ap.add_argument("--col-slice", type=int, default=None)
     ap.add_argument("--fast-mem", type=int, default=None)
     ap.add_argument("--reorder", type=int, default=None, help="1: graph-grown tiles, 0: consecutive")
+    ap.add_argument("--width", type=int, default=None,
+                    help="experiment grid: bCol = cCol (cCol only for a sparse B) instead of the "
+                         "configuration's own")
+    ap.add_argument("--dtype", choices=["f32", "f64"], default=None,
+                    help="experiment grid: precision instead of the configuration's own")
     ap.add_argument("--skip-unread", action="store_true",
                     help="opt in to TF_FLAG_SKIP_UNREAD (D1 rows that no row of A reads are not "
                          "computed by the fused path; the useful-FLOP count is left as it is)")
@@ -105,7 +110,8 @@ def main():
 
     cfg = args.config
     t0 = time.time()
-    prob = ti.config(cfg)
+    prob = ti.config(cfg, width=args.width,
+                     dtype={None: None, "f32": np.float32, "f64": np.float64}[args.dtype])
     log(f"[bench] {prob.name}: n={prob.n} nnz(A)={prob.A.nnz} bCol={prob.bcol} cCol={prob.ccol} "
         f"generated in {time.time() - t0:.1f}s")
     sparse = prob.kind == "spmm_spmm"

@@ -272,10 +272,39 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
         s.lds_bytes_per_row = lds_ldl(in.dtype, in.b_is_sparse, (int)width) * es + s.lds_meta_bytes_per_row;
     };
     model(cs);
-    // a default slice is narrowed (in steps of 16 columns) until its C slice and a first block of
-    // D1 rows fit; a slice the caller asked for is taken as given
-    while (in.col_slice == 0 && !in.b_is_sparse && cs > 16 && tile_footprint(s, 1) > s.fast_mem_bytes) {
-        cs = (cs - 1) / 16 * 16;
+    // ---- step 1: tile size --------------------------------------------------------------
+    const int64_t ct = in.ct_size > 0 ? in.ct_size : 2048;
+    const int64_t p = in.p > 0 ? in.p : 32;
+    int64_t t = ct;
+    if (n > 0 && (n + ct - 1) / ct < p) t = (n + p - 1) / p;
+    if (t < 1) t = 1;
+    s.t = (int32_t)std::min<int64_t>(t, INT32_MAX);
+
+    // A default slice is narrowed (cCol / 2, / 3, ... rounded up to 16 columns) until the fast
+    // memory holds a tile of t rows, or of kWantedTileRows if t is larger: a C slice that fills
+    // the LDS leaves tiles of a few rows, which fuse nothing.  If no width gets there the one
+    // with the most rows is taken.  A slice the caller asked for is taken as given.
+    if (in.col_slice == 0) {
+        auto capacity = [&]() -> int64_t {
+            const int64_t room = s.fast_mem_bytes - s.lds_fixed_bytes;
+            if (room < s.lds_bytes_per_row) return 0;
+            return room / s.lds_bytes_per_row / s.lds_row_granule * s.lds_row_granule;
+        };
+        const int64_t want = round_up(std::min<int64_t>(std::max<int64_t>(t, 1), kWantedTileRows),
+                                      s.lds_row_granule);
+        const int64_t widest = cs;
+        int64_t best_cs = cs, best_rows = capacity();
+        for (int64_t k = 2; best_rows < want && cs > 16; ++k) {
+            const int64_t c = round_up((widest + k - 1) / k, 16);
+            if (c >= cs) continue;
+            cs = c;
+            model(cs);
+            if (capacity() > best_rows) {
+                best_rows = capacity();
+                best_cs = cs;
+            }
+        }
+        cs = best_cs;
         model(cs);
     }
     if (tile_footprint(s, 1) > s.fast_mem_bytes) {
@@ -284,14 +313,6 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
     }
     s.col_slice = (int32_t)cs;
     s.n_slices = (int32_t)((in.ccol + cs - 1) / cs);
-
-    // ---- step 1: tile size --------------------------------------------------------------
-    const int64_t ct = in.ct_size > 0 ? in.ct_size : 2048;
-    const int64_t p = in.p > 0 ? in.p : 32;
-    int64_t t = ct;
-    if (n > 0 && (n + ct - 1) / ct < p) t = (n + p - 1) / p;
-    if (t < 1) t = 1;
-    s.t = (int32_t)std::min<int64_t>(t, INT32_MAX);
 
     // ---- tiles: lists of first-operation rows -------------------------------------------
     // first_rows holds the rows tile after tile; tile_first_ptr delimits the tiles.

@@ -13,6 +13,7 @@ constexpr int kMaxMfmaSliceCols = 128;   // one wave holds at most 8 accumulator
 constexpr int kRowGranuleDense = 16;     // dense-B tiles are produced in blocks of 16 rows (MFMA M/N)
 constexpr int kFusedThreads = 512;       // workgroup size of the fused kernels
 constexpr int kSpmmThreads = 256;        // workgroup size of the row-list SpMM kernel
+constexpr int kWantedTileRows = 256;     // a default column slice is narrowed until tiles this large fit
 constexpr int kUnitRows = 64;            // most rows in one unit of a packed row list
 constexpr int kUnitSlots = 2048;         // most padded entries (rows x slots) in one such unit (they are staged in LDS)
 constexpr int kSplitMinSlots = 128;      // rows at least this long are split over several lane groups

@@ -111,18 +111,39 @@ def test_step2_splits_to_the_lds_budget():
     assert e.value.status_name == "TF_EUNSUPPORTED"
 
 
-def test_default_column_slice_narrows_until_the_c_slice_fits():
-    """fp64, bCol = 256, cCol = 128: a 128-column C slice is 256 KiB, more than the fast memory;
-    the default slice shrinks in steps of 16 columns, an explicit one is taken as given."""
+def test_default_column_slice_narrows_until_the_tiles_fit():
+    """A default column slice is cCol / k (rounded up to 16 columns) for the smallest k whose
+    tiles hold t rows, or 256 rows if t is larger; an explicit slice is taken as given."""
     A = ti.banded(512, 3, np.float64, 5)
+
+    def rows_that_fit(s):
+        room = s["fast_mem_bytes"] - s["lds_fixed_bytes"]
+        g = s["lds_row_granule"]
+        return room // s["lds_bytes_per_row"] // g * g
+
+    # fp64, bCol = 256, cCol = 128: a 128-column C slice is 256 KiB, more than the fast memory
     s = plan_schedule(A, 256, 128, False, ct_size=64, p=1)
     assert s["col_slice"] % 16 == 0 and 16 <= s["col_slice"] < 128
     assert s["n_slices"] == -(-128 // s["col_slice"])
-    assert s["lds_fixed_bytes"] + s["lds_row_granule"] * s["lds_bytes_per_row"] <= s["fast_mem_bytes"]
+    assert rows_that_fit(s) >= 64 or s["col_slice"] == 16
     check_schedule(A, s, 64, 1)
     with pytest.raises(tf.TfError) as e:
         plan_schedule(A, 256, 128, False, ct_size=64, p=1, col_slice=128)
     assert e.value.status_name == "TF_EUNSUPPORTED"
+    # fp64, 128 -> 128: the full-width C slice fits (128 KiB) but leaves tiles of a few rows
+    wide = plan_schedule(A, 128, 128, False, ct_size=64, p=1, col_slice=128)
+    assert rows_that_fit(wide) < 64
+    s = plan_schedule(A, 128, 128, False, ct_size=64, p=1)
+    assert s["col_slice"] == 64 and rows_that_fit(s) >= 64
+    assert s["n_fused_rows"] > wide["n_fused_rows"]
+    # a large t asks for 256 rows, not for t
+    s = plan_schedule(A, 128, 128, False, ct_size=2048, p=1)
+    assert rows_that_fit(s) >= 256 and s["col_slice"] in (32, 48)
+    s2 = plan_schedule(A, 128, 128, False, ct_size=2048, p=1, col_slice=2 * s["col_slice"])
+    assert rows_that_fit(s2) < 256
+    # nothing to narrow when the tiles fit as they are
+    s = plan_schedule(ti.config(2, scale_down=64).A, 64, 64, False, ct_size=65536, p=1)
+    assert s["col_slice"] == 64 and s["n_slices"] == 1
 
 
 def test_schedule_view_reports_the_second_phase_blocks():

@@ -275,50 +275,58 @@ def dense_small_int(rows: int, cols: int, dtype, seed: int) -> np.ndarray:
 N_CONFIGS = 5
 
 
-def config(cfg: int, scale_down: Optional[int] = None) -> Problem:
+def config(cfg: int, scale_down: Optional[int] = None, width: Optional[int] = None,
+           dtype=None) -> Problem:
     """The benchmark configurations, numbered 1..5.  Seeds are 1000 + cfg.
 
     `scale_down` (tests only) shrinks the problem while keeping its structure: it is the grid
     edge for configs 2 and 4, the R-MAT scale for configs 3 and 5, and n for config 1.
+    `width` and `dtype` move a configuration over the paper's experiment grid (Section 4.1:
+    bCol = cCol in {32, 64, 128}, single and double precision): width replaces bCol and cCol of a
+    dense B and cCol of a sparse one, dtype the precision; matrices and seeds stay the same.
     """
     seed = 1000 + cfg
+    tag = lambda dt: "fp32" if np.dtype(dt) == np.float32 else "fp64"
     if cfg == 1:
         n = scale_down or 4096
-        dt = np.float64
+        dt = dtype or np.float64
+        w = width or 32
         A = banded(n, 8, dt, seed)
-        B = dense_normal(n, 32, dt, seed + 1)
-        C = dense_normal(32, 32, dt, seed + 2)
-        return Problem("cfg1 GeMM-SpMM fp64 band h=8", "gemm_spmm", np.dtype(dt), A, B, C)
+        B = dense_normal(n, w, dt, seed + 1)
+        C = dense_normal(w, w, dt, seed + 2)
+        return Problem(f"cfg1 GeMM-SpMM {tag(dt)} band h=8", "gemm_spmm", np.dtype(dt), A, B, C)
     if cfg == 2:
         g = scale_down or 512
-        dt = np.float32
+        dt = dtype or np.float32
+        w = width or 64
         A = laplacian_2d(g, dt)
-        B = dense_normal(g * g, 64, dt, seed + 1)
-        C = dense_normal(64, 64, dt, seed + 2, std=0.125)      # variance 1/64
-        return Problem("cfg2 GeMM-SpMM fp32 2D Laplacian", "gemm_spmm", np.dtype(dt), A, B, C)
+        B = dense_normal(g * g, w, dt, seed + 1)
+        C = dense_normal(w, w, dt, seed + 2, std=float(1.0 / np.sqrt(w)))      # variance 1/w
+        return Problem(f"cfg2 GeMM-SpMM {tag(dt)} 2D Laplacian", "gemm_spmm", np.dtype(dt), A, B, C)
     if cfg == 3:
         s = scale_down or 20
-        dt = np.float32
+        dt = dtype or np.float32
+        w = width or 128
         n = 1 << s
         A = gcn_normalised(s, 8 * n, dt, seed)
-        B = dense_normal(n, 128, dt, seed + 1)
-        C = dense_uniform(128, 128, dt, seed + 2, bound=float(np.sqrt(6.0 / 256.0)))
-        return Problem("cfg3 GeMM-SpMM fp32 GCN R-MAT", "gemm_spmm", np.dtype(dt), A, B, C)
+        B = dense_normal(n, w, dt, seed + 1)
+        C = dense_uniform(w, w, dt, seed + 2, bound=float(np.sqrt(6.0 / (2 * w))))
+        return Problem(f"cfg3 GeMM-SpMM {tag(dt)} GCN R-MAT", "gemm_spmm", np.dtype(dt), A, B, C)
     if cfg == 4:
         g = scale_down or 64
-        dt = np.float64
+        dt = dtype or np.float64
         A = laplacian_3d(g, dt)
-        C = dense_normal(g ** 3, 64, dt, seed + 2)
-        return Problem("cfg4 SpMM-SpMM fp64 3D Laplacian", "spmm_spmm", np.dtype(dt), A, A, C,
+        C = dense_normal(g ** 3, width or 64, dt, seed + 2)
+        return Problem(f"cfg4 SpMM-SpMM {tag(dt)} 3D Laplacian", "spmm_spmm", np.dtype(dt), A, A, C,
                        b_is_A=True)
     if cfg == 5:
         s = scale_down or 20
-        dt = np.float32
+        dt = dtype or np.float32
         n = 1 << s
         A = rmat_symmetric(s, 8 * n, dt, seed)
         B = uniform_random_csr(n, n, 8, dt, seed + 1)
-        C = dense_normal(n, 32, dt, seed + 2)
-        return Problem("cfg5 SpMM-SpMM fp32 R-MAT x random", "spmm_spmm", np.dtype(dt), A, B, C)
+        C = dense_normal(n, width or 32, dt, seed + 2)
+        return Problem(f"cfg5 SpMM-SpMM {tag(dt)} R-MAT x random", "spmm_spmm", np.dtype(dt), A, B, C)
     raise ValueError(f"config must be 1..{N_CONFIGS}")
 
 
