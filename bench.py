@@ -32,7 +32,7 @@ MFMA_PEAK_TFLOPS = {"f32": 157.3, "f64": 78.6}
 TILE_PARAMS = {
     1: dict(ct_size=64, p=1),
     2: dict(ct_size=65536, p=1, flags=4),
-    3: dict(ct_size=256, p=1),
+    3: dict(ct_size=128, p=1),
     4: dict(ct_size=65536, p=1, flags=4),
     5: dict(ct_size=2048, p=1),
 }

@@ -246,6 +246,37 @@ def test_packed_entries_too_large_for_lds_are_read_in_place(dtype, kind):
             c.close()
 
 
+def test_gcn_layers_reuse_one_plan():
+    """Two graph-convolution layers H_{l+1} = relu(A_hat (H_l W_l)) with one plan (scheduler-overhead analysis of Section 4:
+    the schedule depends on the pattern of A only, so it is built once and amortised over
+    layers and epochs).  The second layer's input is the first layer's GPU output, so each layer
+    is compared with the oracle on exactly the operands it was given."""
+    import torch
+    from gpu_util import TOL, dev
+    prob = ti.config(3, scale_down=12)
+    n, w = prob.n, 32
+    A = prob.A
+    H0 = ti.dense_normal(n, w, np.float32, 71)
+    W = [ti.dense_uniform(w, w, np.float32, 72 + l, bound=float(np.sqrt(6.0 / (2 * w))))
+         for l in range(2)]
+    c = _case(ti.Problem("gcn layers", "gemm_spmm", np.dtype(np.float32), A, H0, W[0]),
+              ct_size=256, p=1)
+    try:
+        stream = torch.cuda.current_stream().cuda_stream
+        H = dev(H0)
+        for l in range(2):
+            D = torch.full((n, w), float("nan"), dtype=torch.float32, device="cuda")
+            c.plan.run(H, dev(W[l]), D, stream)
+            torch.cuda.synchronize()
+            D_ref, Wn = oracle.chain(A, H.cpu().numpy(), W[l])
+            got = D.cpu().numpy()
+            assert np.all(np.isfinite(got))
+            assert oracle.rowwise_rel_err(got, D_ref, Wn) <= TOL[np.dtype(np.float32)], l
+            H = torch.relu(D)
+    finally:
+        c.close()
+
+
 # ---------------------------------------------------------------- invariants on the GPU
 
 def test_identity_a_returns_bc():
