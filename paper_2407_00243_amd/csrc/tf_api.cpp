@@ -165,6 +165,15 @@ tf_status check_sparse_b(const tf_plan *p, const tf_csr *B) {
     return TF_OK;
 }
 
+int device_compute_units() {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 256;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        cus <= 0)
+        return 256;
+    return cus;
+}
+
 int device_lds_limit() {
     int dev = 0, lds = 0;
     if (hipGetDevice(&dev) != hipSuccess) return 64 * 1024;
@@ -260,6 +269,7 @@ tf_status tf_plan_create(const tf_csr *A, int64_t bCol, int64_t cCol, int32_t b_
         in.p = tp ? tp->p : 0;
         in.col_slice = tp ? tp->col_slice : 0;
         in.flags = tp ? tp->flags : 0;
+        in.n_cu = schedule_only ? 256 : device_compute_units();
         const int64_t lds_limit = schedule_only ? 160 * 1024 : device_lds_limit();
         in.fast_mem_bytes = (tp && tp->fast_mem_bytes > 0) ? tp->fast_mem_bytes : lds_limit;
         if (!schedule_only && in.fast_mem_bytes > lds_limit) in.fast_mem_bytes = lds_limit;

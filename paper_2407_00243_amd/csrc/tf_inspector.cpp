@@ -328,6 +328,20 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
         while (cap > 1 && tile_footprint(s, cap) > s.fast_mem_bytes) --cap;
         cap = std::max<int64_t>(1, cap / s.lds_row_granule * s.lds_row_granule);
         if (tile_footprint(s, cap) > s.fast_mem_bytes) cap = 1;
+        // One workgroup per compute unit walks the tiles of its column slice, so a tile count that
+        // is not a multiple of the workgroups per slice leaves most of them waiting for the few
+        // that got one tile more (304 tiles on 256 units: two rounds for the work of 1.2).  The
+        // tiles are made smaller (by less than half) so that the count becomes such a multiple.
+        // With fewer tiles than workgroups there is nothing to balance.
+        if (n > 0 && in.n_cu > 0) {
+            const int64_t per_slice = std::max<int64_t>(1, in.n_cu / s.n_slices);
+            const int64_t count0 = (n + cap - 1) / cap;
+            if (count0 >= per_slice) {
+                const int64_t count = round_up(count0, per_slice);
+                const int64_t even = round_up((n + count - 1) / count, s.lds_row_granule);
+                if (even >= 1 && even < cap) cap = even;
+            }
+        }
         std::vector<uint8_t> taken((size_t)n, 0);
         std::vector<int32_t> queue;
         queue.reserve((size_t)cap);

@@ -190,6 +190,7 @@ struct InspectorInput {
     int64_t fast_mem_bytes;
     int32_t col_slice;
     uint32_t flags;
+    int32_t n_cu;                     // compute units of the device the plan will run on
 };
 
 // Builds the schedule; returns TF_OK or an error with a message in `err`.

@@ -146,6 +146,24 @@ def test_default_column_slice_narrows_until_the_tiles_fit():
     assert s["col_slice"] == 64 and s["n_slices"] == 1
 
 
+@pytest.mark.parametrize("width,dtype", [(32, np.float32), (64, np.float32), (32, np.float64),
+                                         (128, np.float64)])
+def test_graph_grown_tiles_fill_the_workgroups_evenly(width, dtype):
+    """One workgroup per compute unit (256 when no device is asked) walks the tiles of its column
+    slice: the tile count is brought close below a multiple of the workgroups per slice, so the
+    last round is nearly full, by shrinking the tiles by less than half."""
+    A = ti.laplacian_2d(512, dtype)
+    s = plan_schedule(A, width, width, False, ct_size=65536, p=1, flags=tf.TF_FLAG_REORDER)
+    per_slice = 256 // s["n_slices"]
+    nt = s["n_tiles"]
+    rounds = -(-nt // per_slice)
+    assert nt / (rounds * per_slice) >= 0.95
+    sizes = np.diff(s["tile_first_ptr"])
+    room = (s["fast_mem_bytes"] - s["lds_fixed_bytes"]) // s["lds_bytes_per_row"]
+    assert sizes.max() <= room and sizes.max() > room // 2 - s["lds_row_granule"]
+    check_schedule_general(A, s)
+
+
 def test_schedule_view_reports_the_second_phase_blocks():
     prob = ti.config(2, scale_down=128)
     s = plan_schedule(prob.A, 64, 64, False, ct_size=256, p=1)
