@@ -68,6 +68,9 @@ def parse():
                          "configuration's own")
     ap.add_argument("--dtype", choices=["f32", "f64"], default=None,
                     help="experiment grid: precision instead of the configuration's own")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time the step replayed from a HIP graph (one graph per buffer set), "
+                         "reported as graph_ms; the headline figures stay those of plain launches")
     ap.add_argument("--skip-unread", action="store_true",
                     help="opt in to TF_FLAG_SKIP_UNREAD (D1 rows that no row of A reads are not "
                          "computed by the fused path; the useful-FLOP count is left as it is)")
@@ -198,6 +201,33 @@ def main():
     warm_fused = statistics.median(event_times(fused, 9, rotate=False)[2:])
     warm_unfused = statistics.median(event_times(unfused, 9, rotate=False)[2:])
 
+    graph_ms = None
+    if args.graph:
+        side = torch.cuda.Stream()
+
+        def graphs_of(fn):
+            out = []
+            for s in sets:
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=side):
+                    cap = torch.cuda.current_stream().cuda_stream
+                    (s[0].run if fn is fused else s[0].run_unfused)(s[1], s[2], s[3], cap)
+                out.append(g)
+            return out
+
+        def timed_graphs(gs):
+            for i in range(args.warmup):
+                gs[i % n_sets].replay()
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            for i in range(args.steps):
+                gs[i % n_sets].replay()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t) / args.steps * 1e3
+
+        graph_ms = {"fused": timed_graphs(graphs_of(fused)),
+                    "unfused": timed_graphs(graphs_of(unfused))}
+
     # ---- per-kernel durations over the same rotation, HIP events on the launch stream
     def avg_kernel_ms(fn, before=None):
         reps = max(args.steps, 2 * n_sets)
@@ -286,6 +316,7 @@ def main():
         "speedup_vs_unfused": ms_unfused / ms_fused,
         "median7_ms": {"fused": med_fused, "unfused": med_unfused},
         "warm_ms": {"fused": warm_fused, "unfused": warm_unfused},
+        "graph_ms": graph_ms,
         "kernels_ms": {"wavefront0": ms_wf0, "wavefront1": ms_wf1},
         "fused_ratio": {"eq3": sched["fused_ratio_eq3"], "rows": sched["fused_ratio_rows"],
                         "nnz": sched["fused_ratio_nnz"]},

@@ -277,6 +277,45 @@ def test_gcn_layers_reuse_one_plan():
         c.close()
 
 
+@pytest.mark.parametrize("kind", ["gemm_spmm", "spmm_spmm"])
+def test_execution_calls_can_be_captured_in_a_graph(kind):
+    """The execution calls allocate nothing and never synchronise, so a stream capture records
+    them (two kernel launches each).  The graph is replayed several times with new operand values
+    written into the same buffers and other work of the process in between; every replay must
+    equal the eager result for the same operands bit for bit, and the oracle to the parity bar."""
+    import torch
+    from gpu_util import TOL, dev, dev_csr
+    prob = ti.config(1 if kind == "gemm_spmm" else 4, scale_down=1000 if kind == "gemm_spmm" else 16)
+    c = _case(prob, ct_size=128, p=1)
+    try:
+        n, ccol = prob.n, prob.ccol
+        Cs = dev(prob.C)
+        D = torch.zeros((n, ccol), dtype=c.tdtype, device="cuda")
+        side = torch.cuda.Stream()
+        with torch.cuda.stream(side):
+            c.plan.run(c.B, Cs, D, side.cuda_stream)          # warm-up outside the capture
+        side.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            c.plan.run(c.B, Cs, D, torch.cuda.current_stream().cuda_stream)
+        for rep in range(4):
+            Cn = ti.dense_normal(prob.C.shape[0], ccol, prob.dtype, 300 + rep)
+            Cs.copy_(dev(Cn))
+            D.fill_(float("nan"))
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            got = D.cpu().numpy()
+            E = torch.full((n, ccol), float("nan"), dtype=c.tdtype, device="cuda")
+            c.plan.run(c.B, Cs, E, torch.cuda.current_stream().cuda_stream)
+            torch.cuda.synchronize()
+            assert np.array_equal(got, E.cpu().numpy()), rep
+            D_ref, Wn = oracle.chain(prob.A, prob.B, Cn)
+            assert oracle.rowwise_rel_err(got, D_ref, Wn) <= TOL[np.dtype(prob.dtype)], rep
+    finally:
+        c.close()
+
+
 # ---------------------------------------------------------------- invariants on the GPU
 
 def test_identity_a_returns_bc():
