@@ -727,7 +727,9 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
     const bool is_mfma = wave < nmw;
     const int snt = nwaves > nmw ? (int)blockDim.x - 64 * nmw : (int)blockDim.x;
     const int stid = nwaves > nmw ? (int)threadIdx.x - 64 * nmw : (int)threadIdx.x;
-    constexpr int ND = 3;                          // B buffers per wave: ND - 1 blocks ahead (measured: better than 4)
+    // B buffers per wave, ND - 1 blocks ahead (measured: 3 is better than 4); two when a block of B
+    // rows is 64 registers per lane, three of which would not leave room for the rest
+    constexpr int ND = KSF * Tr<T>::V * (int)(sizeof(T) / 4) >= 64 ? 2 : 3;
     BFrag<T, KSF> fb[ND];
     T creg[CREG ? KSF * V * NB : 1];
     {
@@ -811,6 +813,10 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
                 constexpr int FI = decltype(fi)::value;
                 load_b_frag<T, KSF>(fb[(FI + ND - 1) % ND],
                                     B + row_of(first, rows, lb + (ND - 1) * nmw) * a.bcol, g);
+                // the loads go out before the multiplications, not after them: left alone the
+                // compiler reuses the accumulators' registers for the buffer being filled and
+                // sinks the loads to the end of the step, which halves the distance they run ahead
+                __builtin_amdgcn_sched_barrier(0);
                 typename Tr<T>::Acc acc[NB];
                 if constexpr (CREG) {
                     mfma_frag_reg<T, NB, KSF>(acc, creg, fb[FI]);
@@ -828,9 +834,11 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
                     step(std::integral_constant<int, 0>(), lb);
                     if (lb + nmw >= nblk) break;
                     step(std::integral_constant<int, 1>(), lb + nmw);
-                    if (lb + 2 * nmw >= nblk) break;
-                    step(std::integral_constant<int, 2>(), lb + 2 * nmw);
-                    static_assert(ND == 3 || ND == 4, "the loop is unrolled once per B buffer");
+                    static_assert(ND >= 2 && ND <= 4, "the loop is unrolled once per B buffer");
+                    if constexpr (ND >= 3) {
+                        if (lb + 2 * nmw >= nblk) break;
+                        step(std::integral_constant<int, 2>(), lb + 2 * nmw);
+                    }
                     if constexpr (ND == 4) {
                         if (lb + 3 * nmw >= nblk) break;
                         step(std::integral_constant<int, 3>(), lb + 3 * nmw);
