@@ -112,6 +112,7 @@ tf::FusedLaunch fused_args(const tf_plan *p, const void *C, void *D) {
     a.ccol = (int32_t)p->ccol;
     a.bcol = (int32_t)p->bcol;
     a.rows_cap = (int32_t)tf::round_up(p->s.max_tile_rows, 16);     // size of a row id buffer
+    a.tile_rows = (int32_t)tf::round_up(p->s.max_tile_rows, tf::lds_row_granule(p->b_is_sparse));
     a.s_cap = (int32_t)p->s.second_block_cap;
     a.s_in_lds = p->s.second_block_in_lds ? 1 : 0;
     a.lds_bytes = tf::fused_lds_bytes(p->dtype, p->b_is_sparse, a.bcol, a.ccol, a.cs,

@@ -261,6 +261,7 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
     // The C slice of a dense B takes LDS for good only when the waves read their operands from it.
     const int64_t avg_nnz = n > 0 ? (in.nnz + n - 1) / n : 0;
     s.lds_meta_bytes_per_row = 8 + 4 + avg_nnz * (2 + es);
+    const int64_t b_stage = in.b_is_sparse ? lds_sparse_b_bytes_per_row(in.dtype) : 0;
     s.lds_row_granule = lds_row_granule(in.b_is_sparse);
     s.fast_mem_bytes = in.fast_mem_bytes;
     auto model = [&](int64_t width) {
@@ -269,7 +270,8 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
                                            mfma_ksteps_special(in.dtype, (int)in.bcol, (int)in.ccol, (int)width));
         s.lds_fixed_bytes =
             (c_regs ? 0 : lds_fixed_bytes(in.dtype, in.b_is_sparse, (int)in.bcol, (int)width)) + 256;
-        s.lds_bytes_per_row = lds_ldl(in.dtype, in.b_is_sparse, (int)width) * es + s.lds_meta_bytes_per_row;
+        s.lds_bytes_per_row =
+            lds_ldl(in.dtype, in.b_is_sparse, (int)width) * es + s.lds_meta_bytes_per_row + b_stage;
     };
     model(cs);
     // ---- step 1: tile size --------------------------------------------------------------

@@ -58,6 +58,13 @@ inline int64_t lds_fixed_bytes(int dtype, int b_is_sparse, int bcol, int cs) {
     return round_up(bcol, kc) * mfma_cols(cs) * elem_size(dtype);
 }
 inline int lds_row_granule(int b_is_sparse) { return b_is_sparse ? 1 : kRowGranuleDense; }
+// A CSR B: the workgroup first copies the extents of the tile's rows of B and up to
+// kSparseEntryCap entries of each into LDS (two loads per row for the whole tile instead of a
+// chain of dependent loads per row); bytes of LDS per tile row that this takes.
+constexpr int kSparseEntryCap = 8;
+inline int64_t lds_sparse_b_bytes_per_row(int dtype) {
+    return 8 + kSparseEntryCap * (4 + (int64_t)elem_size(dtype));
+}
 
 // Whether a wave of the dense-B kernels keeps its operands of the C slice in registers: only for
 // the specialised shallow depths (ks = bCol / (4 * elements per 16 bytes) steps, nb accumulator
@@ -104,10 +111,10 @@ struct TileUnit {          // n_rows rows of `stride` entry slots each, from ent
 };
 
 // Dynamic LDS of a fused workgroup: two buffers of row ids (this tile's and the next one's),
-// the staged second-phase block (s_lds bytes, 0 when it is read in place), the C slice unless
-// the waves hold it in registers, the D1 tile.
+// the staged second-phase block (s_lds bytes, 0 when it is read in place), the staged rows of a
+// CSR B, the C slice of a dense B unless the waves hold it in registers, the D1 tile.
 struct FusedLdsLayout {
-    int64_t first0, first1, second, cslice, tile, total;
+    int64_t first0, first1, second, bext, bidx, bval, cslice, tile, total;
 };
 inline FusedLdsLayout fused_lds_layout(int dtype, int b_is_sparse, int bcol, int ccol, int cs,
                                        int max_tile_rows, int s_lds) {
@@ -118,7 +125,11 @@ inline FusedLdsLayout fused_lds_layout(int dtype, int b_is_sparse, int bcol, int
     l.first0 = 0;
     l.first1 = rows16 * 4;
     l.second = 2 * rows16 * 4;
-    l.cslice = l.second + round_up(s_lds, 16);
+    // staged rows of a CSR B: (first entry, length) per row, then the column indices, then the values
+    l.bext = l.second + round_up(s_lds, 16);
+    l.bidx = l.bext + (b_is_sparse ? round_up(rows_cap * 8, 16) : 0);
+    l.bval = l.bidx + (b_is_sparse ? round_up(rows_cap * kSparseEntryCap * 4, 16) : 0);
+    l.cslice = l.bval + (b_is_sparse ? round_up(rows_cap * kSparseEntryCap * es, 16) : 0);
     const int64_t cbytes = lds_fixed_bytes(dtype, b_is_sparse, bcol, cs);
     const bool c_regs = !b_is_sparse && c_in_registers(dtype, mfma_blocks(cs),
                                                        mfma_ksteps_special(dtype, bcol, ccol, cs));
@@ -216,6 +227,7 @@ struct FusedLaunch {
     int32_t dtype;
     int32_t n_tiles, n_slices, cs, ccol, bcol;
     int32_t rows_cap;                 // largest tile, in rows, rounded up to 16
+    int32_t tile_rows;                // largest tile, in rows, rounded up to the tile's row granule
     int32_t s_cap;                    // largest second-phase block, bytes (multiple of 16)
     int32_t s_in_lds;                 // 1: second-phase blocks are staged in LDS, 0: read in place
     int64_t lds_bytes;                // dynamic LDS of the launch

@@ -498,15 +498,27 @@ __device__ __forceinline__ TileWalk tile_walk(int n_tiles, int n_slices) {
 struct FusedSmem {
     int32_t *first[2];            // row ids (bit 31 = spill) of the current and of the next tile
     unsigned char *second;        // staged second-phase block (or unused)
+    int32_t *bext, *bidx;         // CSR B: (first entry, length) of the tile's rows of B, their column
+    unsigned char *bval;          //        indices and values, kSparseEntryCap slots per row
     unsigned char *cslice;
     unsigned char *tile;
 };
-__device__ __forceinline__ FusedSmem fused_smem(const FusedLaunch &a, bool c_regs, int64_t cbytes) {
+// sparse_es: element size for a CSR B (its staged rows take LDS), 0 for a dense B
+__device__ __forceinline__ FusedSmem fused_smem(const FusedLaunch &a, bool c_regs, int64_t cbytes,
+                                                int sparse_es) {
+    auto up16 = [](int64_t x) { return (x + 15) & ~(int64_t)15; };
     FusedSmem m;
     m.first[0] = reinterpret_cast<int32_t *>(tf_smem);
     m.first[1] = m.first[0] + a.rows_cap;
     m.second = tf_smem + 2 * (int64_t)a.rows_cap * 4;
-    m.cslice = m.second + (a.s_in_lds ? a.s_cap : 0);
+    unsigned char *p = m.second + (a.s_in_lds ? a.s_cap : 0);
+    m.bext = reinterpret_cast<int32_t *>(p);
+    if (sparse_es) p += up16((int64_t)a.tile_rows * 8);
+    m.bidx = reinterpret_cast<int32_t *>(p);
+    if (sparse_es) p += up16((int64_t)a.tile_rows * kSparseEntryCap * 4);
+    m.bval = p;
+    if (sparse_es) p += up16((int64_t)a.tile_rows * kSparseEntryCap * sparse_es);
+    m.cslice = p;
     m.tile = m.cslice + (c_regs ? 0 : cbytes);
     return m;
 }
@@ -574,35 +586,14 @@ __device__ __forceinline__ SecondBlock<T> second_block(const unsigned char *sb, 
 // and are walked R rows at a time, two slots per step.  Nothing but LDS latency limits this
 // loop, so the entries (index pair, value pair) of the next step are read while the operands of
 // the current step are on their way.
-// RS > 0: the spilled rows are copied here, RS rows per lane group at a time; RS = 0: the caller
-// has already stored them.
-template <typename T, int VV, int R, int RS>
+// (The spilled rows of the tile have been stored by the waves that produced them.)
+template <typename T, int VV, int R>
 __device__ __forceinline__ void fused_tail(const FusedLaunch &a, const TileDesc &d,
-                                           const int32_t *first, const unsigned char *sb,
+                                           const unsigned char *sb,
                                            const T *tileD1, int ldl, int c0, int gl, int grp,
                                            int ngrp) {
     const int ccol = a.ccol;
     const uint32_t lane_off = (uint32_t)(VV * gl);
-    if constexpr (RS > 0) {
-        T *__restrict__ D1 = static_cast<T *>(a.D1);
-        const int rows = d.n_rows;
-        for (int i0 = grp; i0 < rows; i0 += ngrp * RS) {
-            uint32_t enc[RS > 0 ? RS : 1];
-#pragma unroll
-            for (int r = 0; r < RS; ++r) {
-                const int i = i0 + r * ngrp;
-                enc[r] = i < rows ? (uint32_t)first[i] : 0u;
-            }
-            T x[RS > 0 ? RS : 1][VV];
-#pragma unroll
-            for (int r = 0; r < RS; ++r)
-                if (enc[r] & kSpillBit) load_pack<T, VV>(x[r], tileD1 + (i0 + r * ngrp) * ldl + lane_off);
-#pragma unroll
-            for (int r = 0; r < RS; ++r)
-                if (enc[r] & kSpillBit)
-                    store_pack<T, VV>(D1 + (int64_t)(enc[r] & ~kSpillBit) * ccol + c0 + lane_off, x[r]);
-        }
-    }
     const SecondBlock<T> b = second_block<T>(sb, d);
     T *__restrict__ D = static_cast<T *>(a.D);
     typedef Pack<T, 2> ValPair;
@@ -699,12 +690,12 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
     if (tw.tile >= tw.tile_end) return;
     const int c0 = tw.slice * a.cs;
     const int w = min(a.cs, a.ccol - c0);
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nwaves = (int)blockDim.x >> 6;
     const int g = lane >> 4, r = lane & 15;
     const int bcol_pad = (a.bcol + KC - 1) / KC * KC;
     const int ldl = 16 * NB + V;
-    const FusedSmem sm = fused_smem(a, CREG, (int64_t)bcol_pad * 16 * NB * (int64_t)sizeof(T));
+    const FusedSmem sm = fused_smem(a, CREG, (int64_t)bcol_pad * 16 * NB * (int64_t)sizeof(T), 0);
     T *Cl = reinterpret_cast<T *>(sm.cslice);
     T *tileD1 = reinterpret_cast<T *>(sm.tile);
     const T *__restrict__ B = static_cast<const T *>(a.B);
@@ -872,7 +863,7 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
         // (three rows per lane group at a time: with four the kernel no longer fits the 256
         // registers of a wave at this occupancy and spills)
         if (VV * gl < w)
-            fused_tail<T, VV, 3, 0>(a, d, first, SLDS ? sm.second : blk, tileD1, ldl, c0, gl, grp, ngrp);
+            fused_tail<T, VV, 3>(a, d, SLDS ? sm.second : blk, tileD1, ldl, c0, gl, grp, ngrp);
         if (!has_next) break;
         __syncthreads();
         d = nd;
@@ -881,11 +872,147 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
     }
 }
 
+constexpr int kEntriesPerPassLong = 4;   // entries in flight per lane for a row too long to stage
+
+// Phase 1 of a tile with a CSR B: D1[pos] = B[row(pos), :] C for the tile's rows, into the LDS tile.
+// Per row the chain row id -> extent -> entries -> rows of C is three dependent loads; walked row
+// by row it leaves the memory pipe idle most of the time.  Here the whole workgroup takes each
+// link of the chain for all rows of the tile at once, handing over through LDS: (1) extents of all
+// rows, (2) up to kSparseEntryCap entries of every row (padding slots repeat the row's last
+// entry, or column 0 for an empty row, so that the gathers need no bounds), (3) the gathers, RP
+// rows of kSparseEntryCap slots each in flight per lane; a finished row goes to the LDS tile and,
+// if the second wavefront reads it, to the D1 workspace.  A row with more entries than the cap is
+// gathered from device memory entry by entry.
+template <typename T, int VV, int RP>
+__device__ __forceinline__ void sparse_phase1(const int32_t *first, int rows, const FusedSmem &sm,
+                                              const int32_t *__restrict__ rowptr,
+                                              const int32_t *__restrict__ colidx,
+                                              const T *__restrict__ vals, const T *Xl, int64_t ldx,
+                                              bool active, T *tile_lane, int ldl, T *D1l, int64_t ldd,
+                                              int grp, int ngrp) {
+    constexpr int CAP = kSparseEntryCap;
+    int32_t *ext = sm.bext, *eidx = sm.bidx;
+    T *eval = reinterpret_cast<T *>(sm.bval);
+    for (int i = threadIdx.x; i < rows; i += (int)blockDim.x) {
+        const int64_t rid = (int64_t)((uint32_t)first[i] & ~kSpillBit);
+        const int kb = rowptr[rid], ke = rowptr[rid + 1];
+        ext[2 * i] = kb;
+        ext[2 * i + 1] = ke - kb;
+    }
+    __syncthreads();
+    constexpr int SW = 4;                                  // slots per thread whose loads go out together
+    const int total = rows * CAP;
+    for (int s0 = threadIdx.x; s0 < total; s0 += SW * (int)blockDim.x) {
+        int32_t ci[SW];
+        T v[SW];
+#pragma unroll
+        for (int u = 0; u < SW; ++u) {
+            const int s = s0 + u * (int)blockDim.x;
+            const int i = (s < total ? s : s0) / CAP, e = s % CAP;
+            const int kb = ext[2 * i], len = ext[2 * i + 1];
+            ci[u] = 0;
+            v[u] = T(0);
+            if (len > 0 && len <= CAP) {
+                const int k = kb + (e < len ? e : len - 1);
+                ci[u] = colidx[k];
+                v[u] = vals[k];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < SW; ++u) {
+            const int s = s0 + u * (int)blockDim.x;
+            if (s < total) {
+                eidx[s] = ci[u];
+                eval[s] = v[u];
+            }
+        }
+    }
+    __syncthreads();
+    typedef int32_t Idx4 __attribute__((ext_vector_type(4)));
+    for (int base = grp; base < rows; base += ngrp * RP) {
+        int pos[RP], len[RP];
+        uint32_t enc[RP];
+        bool ok[RP];
+#pragma unroll
+        for (int r = 0; r < RP; ++r) {
+            pos[r] = base + r * ngrp;
+            ok[r] = pos[r] < rows;
+            if (!ok[r]) pos[r] = base;
+            len[r] = ok[r] ? ext[2 * pos[r] + 1] : 0;
+            enc[r] = (uint32_t)first[pos[r]];
+        }
+        if (!active) continue;
+        T acc[RP][VV];
+        int32_t ci[RP][CAP];
+#pragma unroll
+        for (int r = 0; r < RP; ++r) {
+#pragma unroll
+            for (int i = 0; i < VV; ++i) acc[r][i] = T(0);
+            const Idx4 *p = reinterpret_cast<const Idx4 *>(eidx + pos[r] * CAP);
+#pragma unroll
+            for (int q = 0; q < CAP / 4; ++q) {
+                const Idx4 c4 = p[q];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) ci[r][4 * q + j] = c4[j];
+            }
+        }
+        // slot e is fetched if any row of the wave has an entry there (a wave-uniform branch)
+        T x[RP][CAP][VV];
+        bool any[CAP];
+#pragma unroll
+        for (int e = 0; e < CAP; ++e) {
+            bool mine = false;
+#pragma unroll
+            for (int r = 0; r < RP; ++r) mine = mine || (e < len[r] && len[r] <= CAP);
+            any[e] = __builtin_amdgcn_ballot_w64(mine) != 0;
+            if (any[e]) {
+#pragma unroll
+                for (int r = 0; r < RP; ++r) load_pack<T, VV>(x[r][e], Xl + (int64_t)ci[r][e] * ldx);
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < RP; ++r) {
+            T v[CAP];
+            const T *vp = eval + pos[r] * CAP;
+#pragma unroll
+            for (int q = 0; q < CAP; q += Tr<T>::V) load_pack<T, Tr<T>::V>(*reinterpret_cast<T(*)[Tr<T>::V]>(&v[q]), vp + q);
+#pragma unroll
+            for (int e = 0; e < CAP; ++e) {
+                if (any[e]) {
+                    const bool use = e < len[r] && len[r] <= CAP;
+                    const T vv = use ? v[e] : T(0);
+#pragma unroll
+                    for (int i = 0; i < VV; ++i) acc[r][i] += vv * (use ? x[r][e][i] : T(0));
+                }
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < RP; ++r) {
+            if (len[r] > CAP) {
+                const int kb1[1] = {ext[2 * pos[r]]};
+                const int ke1[1] = {kb1[0] + len[r]};
+                T a1[1][VV];
+#pragma unroll
+                for (int i = 0; i < VV; ++i) a1[0][i] = T(0);
+                rows_dot<T, VV, int32_t, 1, kEntriesPerPassLong>(a1, colidx, vals, kb1, ke1, Xl, ldx);
+#pragma unroll
+                for (int i = 0; i < VV; ++i) acc[r][i] = a1[0][i];
+            }
+            if (ok[r]) {
+                store_pack<T, VV>(tile_lane + (int64_t)pos[r] * ldl, acc[r]);
+                // a row that the second wavefront reads goes to the D1 workspace from here
+                if (enc[r] & kSpillBit)
+                    store_pack<T, VV>(D1l + (int64_t)(enc[r] & ~kSpillBit) * ldd, acc[r]);
+            }
+        }
+    }
+}
+
 // First wavefront, CSR B: phase 1 gathers rows of C for the tile's rows of B into the LDS tile.
 // Gathers hide their latency with waves: the workgroup is as large as the machine allows (16
-// waves) and each lane group keeps fewer rows in flight, so that a wave fits 128 registers.
+// waves) and each lane group keeps one row (kSparseEntryCap gathers) in flight, so that a wave
+// fits 128 registers.
 constexpr int kFusedSparseThreads = 1024;
-constexpr int kSparseRowsPerPass = 2;
 template <typename T, bool FAST, bool SLDS>
 __global__ __launch_bounds__(kFusedSparseThreads) void k_fused_spmm_spmm(const FusedLaunch a) {
     constexpr int VV = FAST ? Tr<T>::V : 1;
@@ -894,7 +1021,7 @@ __global__ __launch_bounds__(kFusedSparseThreads) void k_fused_spmm_spmm(const F
     const int c0 = tw.slice * a.cs;
     const int w = min(a.cs, a.ccol - c0);
     const int ldl = (a.cs + Tr<T>::V - 1) / Tr<T>::V * Tr<T>::V;
-    const FusedSmem sm = fused_smem(a, true, 0);
+    const FusedSmem sm = fused_smem(a, true, 0, (int)sizeof(T));
     T *tileD1 = reinterpret_cast<T *>(sm.tile);
     const int G = pow2_at_least((a.cs + VV - 1) / VV);
     const int gl = threadIdx.x % G, grp = threadIdx.x / G, ngrp = (int)blockDim.x / G;
@@ -923,12 +1050,10 @@ __global__ __launch_bounds__(kFusedSparseThreads) void k_fused_spmm_spmm(const F
         const Piece nfirst = reinterpret_cast<const Piece *>(
             a.tile_meta + nd.meta_off)[(int)threadIdx.x < nfirst_pieces ? threadIdx.x : 0];
 
-        gather_rows<T, VV, int32_t, kSparseRowsPerPass, kEntriesPerPass>(
-            grp, rows, ngrp, a.Bs.rowptr, a.Bs.colidx, bvals, C + c0 + VV * gl, ccol, VV * gl < w,
-            [&](int pos) { return (int32_t)((uint32_t)first[pos] & ~kSpillBit); },
-            [&](int pos, int64_t, const T(&acc)[VV]) {
-                store_pack<T, VV>(tileD1 + (int64_t)pos * ldl + VV * gl, acc);
-            });
+        sparse_phase1<T, VV, 1>(first, rows, sm, a.Bs.rowptr, a.Bs.colidx, bvals,
+                                                 C + c0 + VV * gl, ccol, VV * gl < w,
+                                                 tileD1 + VV * gl, ldl,
+                                                 static_cast<T *>(a.D1) + c0 + VV * gl, ccol, grp, ngrp);
 
         if constexpr (SLDS) stage_write<kStagePieces>(st, sm.second, blk, d.s_bytes, threadIdx.x, blockDim.x);
         if ((int)threadIdx.x < nfirst_pieces)
@@ -938,7 +1063,7 @@ __global__ __launch_bounds__(kFusedSparseThreads) void k_fused_spmm_spmm(const F
                 reinterpret_cast<const Piece *>(a.tile_meta + nd.meta_off)[e];
         __syncthreads();
         if (VV * gl < w)
-            fused_tail<T, VV, 2, 4>(a, d, first, SLDS ? sm.second : blk, tileD1, ldl, c0, gl, grp, ngrp);
+            fused_tail<T, VV, 2>(a, d, SLDS ? sm.second : blk, tileD1, ldl, c0, gl, grp, ngrp);
         if (!has_next) break;
         __syncthreads();
         d = nd;

@@ -233,7 +233,7 @@ def test_packed_entries_too_large_for_lds_are_read_in_place(dtype, kind):
     C = ti.dense_small_int(bcol, ccol, dtype, 79)
     prob = ti.Problem("dense block", kind, np.dtype(dtype), A, B, C)
     D_ref, _ = oracle.chain(A, B, C)
-    for fast_mem, staged in ((16 * 1024, 0), (0, 1)):
+    for fast_mem, staged in ((24 * 1024, 0), (0, 1)):
         c = _case(prob, ct_size=64, p=1, fast_mem_bytes=fast_mem)
         try:
             s = c.plan.schedule()
