@@ -476,7 +476,7 @@ tf_status tf_unfused_spmm_spmm(const tf_plan *p, const tf_csr *B, const void *C,
     if (st != TF_OK) return st;
     tf::CsrSpmmLaunch f{};
     f.dtype = p->dtype;
-    f.rows_per_wg = 64;
+    f.rows_per_wg = tf::kCsrRowsPerWg;
     f.n_rows = p->n;
     f.S.rowptr = B->rowptr;
     f.S.colidx = B->colidx;

@@ -62,6 +62,7 @@ inline int lds_row_granule(int b_is_sparse) { return b_is_sparse ? 1 : kRowGranu
 // kSparseEntryCap entries of each into LDS (two loads per row for the whole tile instead of a
 // chain of dependent loads per row); bytes of LDS per tile row that this takes.
 constexpr int kSparseEntryCap = 8;
+constexpr int kCsrRowsPerWg = 64;        // rows of one workgroup of the unfused CSR SpMM
 inline int64_t lds_sparse_b_bytes_per_row(int dtype) {
     return 8 + kSparseEntryCap * (4 + (int64_t)elem_size(dtype));
 }

@@ -874,27 +874,25 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
 
 constexpr int kEntriesPerPassLong = 4;   // entries in flight per lane for a row too long to stage
 
-// Phase 1 of a tile with a CSR B: D1[pos] = B[row(pos), :] C for the tile's rows, into the LDS tile.
-// Per row the chain row id -> extent -> entries -> rows of C is three dependent loads; walked row
+// Y[pos] = S[row_of(pos), :] X for a list of `rows` rows of a CSR matrix S handled by one workgroup.
+// Per row the chain row id -> extent -> entries -> rows of X is three dependent loads; walked row
 // by row it leaves the memory pipe idle most of the time.  Here the whole workgroup takes each
-// link of the chain for all rows of the tile at once, handing over through LDS: (1) extents of all
-// rows, (2) up to kSparseEntryCap entries of every row (padding slots repeat the row's last
-// entry, or column 0 for an empty row, so that the gathers need no bounds), (3) the gathers, RP
-// rows of kSparseEntryCap slots each in flight per lane; a finished row goes to the LDS tile and,
-// if the second wavefront reads it, to the D1 workspace.  A row with more entries than the cap is
-// gathered from device memory entry by entry.
-template <typename T, int VV, int RP>
-__device__ __forceinline__ void sparse_phase1(const int32_t *first, int rows, const FusedSmem &sm,
-                                              const int32_t *__restrict__ rowptr,
-                                              const int32_t *__restrict__ colidx,
-                                              const T *__restrict__ vals, const T *Xl, int64_t ldx,
-                                              bool active, T *tile_lane, int ldl, T *D1l, int64_t ldd,
-                                              int grp, int ngrp) {
+// link of the chain for all rows of the list at once, handing over through LDS:
+// stage_csr_rows     (1) extents of all rows, (2) up to kSparseEntryCap entries of every row
+//                    (padding slots repeat the row's last entry, or column 0 for an empty row, so
+//                    that the gathers need no bounds); ends with a barrier;
+// gather_staged_rows (3) the gathers, RP rows of kSparseEntryCap slots each in flight per lane;
+//                    out(pos, acc) takes a finished row.  A row with more entries than the cap
+//                    is gathered from device memory entry by entry.
+// ext holds 2 ints per row, eidx and eval kSparseEntryCap slots per row (LDS, 16-byte aligned).
+template <typename T, typename RowFn>
+__device__ __forceinline__ void stage_csr_rows(int rows, int32_t *ext, int32_t *eidx, T *eval,
+                                               const int32_t *__restrict__ rowptr,
+                                               const int32_t *__restrict__ colidx,
+                                               const T *__restrict__ vals, RowFn row_of) {
     constexpr int CAP = kSparseEntryCap;
-    int32_t *ext = sm.bext, *eidx = sm.bidx;
-    T *eval = reinterpret_cast<T *>(sm.bval);
     for (int i = threadIdx.x; i < rows; i += (int)blockDim.x) {
-        const int64_t rid = (int64_t)((uint32_t)first[i] & ~kSpillBit);
+        const int64_t rid = row_of(i);
         const int kb = rowptr[rid], ke = rowptr[rid + 1];
         ext[2 * i] = kb;
         ext[2 * i + 1] = ke - kb;
@@ -928,10 +926,19 @@ __device__ __forceinline__ void sparse_phase1(const int32_t *first, int rows, co
         }
     }
     __syncthreads();
+}
+
+template <typename T, int VV, int RP, typename OutFn>
+__device__ __forceinline__ void gather_staged_rows(int rows, const int32_t *ext, const int32_t *eidx,
+                                                   const T *eval,
+                                                   const int32_t *__restrict__ colidx,
+                                                   const T *__restrict__ vals, const T *Xl,
+                                                   int64_t ldx, bool active, int grp, int ngrp,
+                                                   OutFn out) {
+    constexpr int CAP = kSparseEntryCap;
     typedef int32_t Idx4 __attribute__((ext_vector_type(4)));
     for (int base = grp; base < rows; base += ngrp * RP) {
         int pos[RP], len[RP];
-        uint32_t enc[RP];
         bool ok[RP];
 #pragma unroll
         for (int r = 0; r < RP; ++r) {
@@ -939,7 +946,6 @@ __device__ __forceinline__ void sparse_phase1(const int32_t *first, int rows, co
             ok[r] = pos[r] < rows;
             if (!ok[r]) pos[r] = base;
             len[r] = ok[r] ? ext[2 * pos[r] + 1] : 0;
-            enc[r] = (uint32_t)first[pos[r]];
         }
         if (!active) continue;
         T acc[RP][VV];
@@ -975,7 +981,8 @@ __device__ __forceinline__ void sparse_phase1(const int32_t *first, int rows, co
             T v[CAP];
             const T *vp = eval + pos[r] * CAP;
 #pragma unroll
-            for (int q = 0; q < CAP; q += Tr<T>::V) load_pack<T, Tr<T>::V>(*reinterpret_cast<T(*)[Tr<T>::V]>(&v[q]), vp + q);
+            for (int q = 0; q < CAP; q += Tr<T>::V)
+                load_pack<T, Tr<T>::V>(*reinterpret_cast<T(*)[Tr<T>::V]>(&v[q]), vp + q);
 #pragma unroll
             for (int e = 0; e < CAP; ++e) {
                 if (any[e]) {
@@ -998,12 +1005,7 @@ __device__ __forceinline__ void sparse_phase1(const int32_t *first, int rows, co
 #pragma unroll
                 for (int i = 0; i < VV; ++i) acc[r][i] = a1[0][i];
             }
-            if (ok[r]) {
-                store_pack<T, VV>(tile_lane + (int64_t)pos[r] * ldl, acc[r]);
-                // a row that the second wavefront reads goes to the D1 workspace from here
-                if (enc[r] & kSpillBit)
-                    store_pack<T, VV>(D1l + (int64_t)(enc[r] & ~kSpillBit) * ldd, acc[r]);
-            }
+            if (ok[r]) out(pos[r], acc[r]);
         }
     }
 }
@@ -1050,10 +1052,23 @@ __global__ __launch_bounds__(kFusedSparseThreads) void k_fused_spmm_spmm(const F
         const Piece nfirst = reinterpret_cast<const Piece *>(
             a.tile_meta + nd.meta_off)[(int)threadIdx.x < nfirst_pieces ? threadIdx.x : 0];
 
-        sparse_phase1<T, VV, 1>(first, rows, sm, a.Bs.rowptr, a.Bs.colidx, bvals,
-                                                 C + c0 + VV * gl, ccol, VV * gl < w,
-                                                 tileD1 + VV * gl, ldl,
-                                                 static_cast<T *>(a.D1) + c0 + VV * gl, ccol, grp, ngrp);
+        // D1[pos] = B[row(pos), :] C for the tile's rows, into the LDS tile; a row that the second
+        // wavefront reads also goes to the D1 workspace, from the registers of its lane group
+        {
+            T *eval = reinterpret_cast<T *>(sm.bval);
+            stage_csr_rows<T>(rows, sm.bext, sm.bidx, eval, a.Bs.rowptr, a.Bs.colidx, bvals,
+                              [&](int i) { return (int64_t)((uint32_t)first[i] & ~kSpillBit); });
+            T *tile_lane = tileD1 + VV * gl;
+            T *D1l = static_cast<T *>(a.D1) + c0 + VV * gl;
+            gather_staged_rows<T, VV, 1>(
+                rows, sm.bext, sm.bidx, eval, a.Bs.colidx, bvals, C + c0 + VV * gl, ccol,
+                VV * gl < w, grp, ngrp, [&](int pos, const T(&acc)[VV]) {
+                    store_pack<T, VV>(tile_lane + (int64_t)pos * ldl, acc);
+                    const uint32_t enc = (uint32_t)first[pos];
+                    if (enc & kSpillBit)
+                        store_pack<T, VV>(D1l + (int64_t)(enc & ~kSpillBit) * ccol, acc);
+                });
+        }
 
         if constexpr (SLDS) stage_write<kStagePieces>(st, sm.second, blk, d.s_bytes, threadIdx.x, blockDim.x);
         if ((int)threadIdx.x < nfirst_pieces)
@@ -1267,12 +1282,19 @@ __global__ __launch_bounds__(kSpmmThreads) void k_csr_spmm(const CsrSpmmLaunch a
     const T *__restrict__ vals = static_cast<const T *>(a.S.vals);
     const T *__restrict__ X = static_cast<const T *>(a.X);
     T *__restrict__ Y = static_cast<T *>(a.Y);
+    // the rows of the workgroup are staged once (see stage_csr_rows), then gathered per column block
+    __shared__ __align__(16) int32_t ext_s[2 * kCsrRowsPerWg];
+    __shared__ __align__(16) int32_t idx_s[kSparseEntryCap * kCsrRowsPerWg];
+    __shared__ __align__(16) T val_s[kSparseEntryCap * kCsrRowsPerWg];
+    const int rows = (int)(r1 - r0);
+    stage_csr_rows<T>(rows, ext_s, idx_s, val_s, a.S.rowptr, a.S.colidx, vals,
+                      [&](int i) { return r0 + i; });
     for (int cb = 0; cb < ccol; cb += G * VV) {
         const int col = cb + VV * gl;
-        gather_rows<T, VV, int32_t, kRowsPerPass, kEntriesPerPass>(
-            grp, (int)(r1 - r0), ngrp, a.S.rowptr, a.S.colidx, vals, X + col, ccol, col < ccol,
-            [&](int pos) { return (int32_t)(r0 + pos); },
-            [&](int, int64_t j, const T(&acc)[VV]) { store_pack<T, VV>(Y + j * ccol + col, acc); });
+        gather_staged_rows<T, VV, 2>(rows, ext_s, idx_s, val_s, a.S.colidx, vals, X + col, ccol,
+                                     col < ccol, grp, ngrp, [&](int pos, const T(&acc)[VV]) {
+                                         store_pack<T, VV>(Y + (r0 + pos) * ccol + col, acc);
+                                     });
     }
 }
 
@@ -1535,6 +1557,8 @@ int launch_packed_spmm(const PackedSpmmLaunch &a, void *stream) {
 int launch_csr_spmm(const CsrSpmmLaunch &a, void *stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (a.n_rows == 0) return 0;
+    // the kernel stages the rows of a workgroup in LDS arrays of this many rows
+    if (a.rows_per_wg < 1 || a.rows_per_wg > kCsrRowsPerWg) return (int)hipErrorInvalidValue;
     const bool fast = spmm_fast(a.dtype, a.ccol, a.ccol);
     const int64_t n_wg = (a.n_rows + a.rows_per_wg - 1) / a.rows_per_wg;
     const dim3 grid((unsigned)((n_wg + 7) / 8 * 8)), block(kSpmmThreads);
