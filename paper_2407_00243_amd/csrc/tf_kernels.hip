@@ -962,20 +962,34 @@ __device__ __forceinline__ void gather_staged_rows(int rows, const int32_t *ext,
                 for (int j = 0; j < 4; ++j) ci[r][4 * q + j] = c4[j];
             }
         }
-        // slot e is fetched if any row of the wave has an entry there (a wave-uniform branch)
+        // All loads of a half (four slots) go out back to back, unconditionally: every slot names a
+        // valid row of X.  The second half is skipped when no row of the wave reaches into it (a
+        // wave-uniform branch; a branch per slot made the compiler wait for each load in turn).
+        static_assert(CAP == 8, "the slots are fetched in two halves of four");
         T x[RP][CAP][VV];
-        bool any[CAP];
+        bool far = false;
 #pragma unroll
-        for (int e = 0; e < CAP; ++e) {
-            bool mine = false;
+        for (int r = 0; r < RP; ++r) far = far || (len[r] > CAP / 2 && len[r] <= CAP);
+        const bool second_half = __builtin_amdgcn_ballot_w64(far) != 0;
 #pragma unroll
-            for (int r = 0; r < RP; ++r) mine = mine || (e < len[r] && len[r] <= CAP);
-            any[e] = __builtin_amdgcn_ballot_w64(mine) != 0;
-            if (any[e]) {
+        for (int e = 0; e < CAP / 2; ++e)
+#pragma unroll
+            for (int r = 0; r < RP; ++r) load_pack<T, VV>(x[r][e], Xl + (int64_t)ci[r][e] * ldx);
+        if (second_half) {
+#pragma unroll
+            for (int e = CAP / 2; e < CAP; ++e)
 #pragma unroll
                 for (int r = 0; r < RP; ++r) load_pack<T, VV>(x[r][e], Xl + (int64_t)ci[r][e] * ldx);
-            }
         }
+        auto sum_slots = [&](int r, const T(&v)[CAP], int e0) {
+#pragma unroll
+            for (int e = e0; e < e0 + CAP / 2; ++e) {
+                const bool use = e < len[r] && len[r] <= CAP;
+                const T vv = use ? v[e] : T(0);
+#pragma unroll
+                for (int i = 0; i < VV; ++i) acc[r][i] += vv * (use ? x[r][e][i] : T(0));
+            }
+        };
 #pragma unroll
         for (int r = 0; r < RP; ++r) {
             T v[CAP];
@@ -983,15 +997,8 @@ __device__ __forceinline__ void gather_staged_rows(int rows, const int32_t *ext,
 #pragma unroll
             for (int q = 0; q < CAP; q += Tr<T>::V)
                 load_pack<T, Tr<T>::V>(*reinterpret_cast<T(*)[Tr<T>::V]>(&v[q]), vp + q);
-#pragma unroll
-            for (int e = 0; e < CAP; ++e) {
-                if (any[e]) {
-                    const bool use = e < len[r] && len[r] <= CAP;
-                    const T vv = use ? v[e] : T(0);
-#pragma unroll
-                    for (int i = 0; i < VV; ++i) acc[r][i] += vv * (use ? x[r][e][i] : T(0));
-                }
-            }
+            sum_slots(r, v, 0);
+            if (second_half) sum_slots(r, v, CAP / 2);
         }
 #pragma unroll
         for (int r = 0; r < RP; ++r) {
