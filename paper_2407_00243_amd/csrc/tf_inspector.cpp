@@ -282,7 +282,8 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
     if (t < 1) t = 1;
     s.t = (int32_t)std::min<int64_t>(t, INT32_MAX);
 
-    // A default slice is narrowed (cCol / 2, / 3, ... rounded up to 16 columns) until the fast
+    // A default slice is narrowed (cCol / 2, / 4, ... rounded up to 16 columns; thirds leave a
+    // ragged last slice and measured worse than either neighbour) until the fast
     // memory holds a tile of t rows, or of kWantedTileRows if t is larger: a C slice that fills
     // the LDS leaves tiles of a few rows, which fuse nothing.  If no width gets there the one
     // with the most rows is taken.  A slice the caller asked for is taken as given.
@@ -296,7 +297,7 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
                                       s.lds_row_granule);
         const int64_t widest = cs;
         int64_t best_cs = cs, best_rows = capacity();
-        for (int64_t k = 2; best_rows < want && cs > 16; ++k) {
+        for (int64_t k = 2; best_rows < want && cs > 16; k *= 2) {
             const int64_t c = round_up((widest + k - 1) / k, 16);
             if (c >= cs) continue;
             cs = c;
