@@ -610,19 +610,40 @@ __device__ __forceinline__ void fused_tail(const FusedLaunch &a, const TileDesc 
             const int i = grp + (kb * R + r) * ngrp;
             return i < un.n_rows ? i : un.n_rows - 1;
         };
-        // entries of step sp of row block kb: operand offsets (16-byte units) and values
+        // entries of step sp of the rows whose first entries sit at rb[]: operand offsets (16-byte
+        // units) and values.  The step offset is kept as a scalar the compiler cannot fold into
+        // the per-row positions, which would cost one vector add per array and row in every step.
         uint32_t cn[R][2];
         ValPair vn[R];
-        auto read_entries = [&](int kb, int sp) {
+        struct RowEntries {           // where the entries of a row start in the three arrays
+            const uint16_t *a, *b;
+            const ValPair *v;
+        };
+        auto first_entries = [&](RowEntries (&rb)[R], int kb) {
 #pragma unroll
             for (int r = 0; r < R; ++r) {
-                const int at = row_at(kb, r) * S + sp;
-                cn[r][0] = ia[at];
-                cn[r][1] = ib[at];
-                vn[r] = vp[at];
+                const int at = row_at(kb, r) * S;
+                rb[r].a = ia + at;
+                rb[r].b = ib + at;
+                rb[r].v = vp + at;
             }
         };
-        if (S > 0) read_entries(0, 0);
+        auto read_entries = [&](const RowEntries (&rb)[R], int sp) {
+            int so = sp;
+            asm volatile("" : "+s"(so));
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                cn[r][0] = rb[r].a[so];
+                cn[r][1] = rb[r].b[so];
+                vn[r] = rb[r].v[so];
+            }
+        };
+        RowEntries rb[R], rbn[R];
+        first_entries(rb, 0);
+        if (S > 0) read_entries(rb, 0);
+        // all steps of a row but the last have two entries; the last has two when the longest
+        // row's length is even.  `more`: entries are read ahead for the following step.
+        const bool last_two = 2 * S - 1 < len;
         for (int kb = 0; kb < KB; ++kb) {
             int32_t rid[R];
 #pragma unroll
@@ -632,32 +653,38 @@ __device__ __forceinline__ void fused_tail(const FusedLaunch &a, const TileDesc 
             for (int r = 0; r < R; ++r)
 #pragma unroll
                 for (int i = 0; i < VV; ++i) acc[r][i] = T(0);
-            for (int sp = 0; sp < S; ++sp) {
-                const bool two = 2 * sp + 1 < len;
+            auto step = [&](auto two_c, const RowEntries (&next_rb)[R], int nsp, bool more) {
+                constexpr bool TWO = decltype(two_c)::value;
                 ValPair v[R];
                 T x[R][2][VV];
 #pragma unroll
                 for (int r = 0; r < R; ++r) {
                     v[r] = vn[r];
                     load_pack<T, VV>(x[r][0], reinterpret_cast<const T *>(tile_lane + (cn[r][0] << 4)));
-                    if (two)
+                    if (TWO)
                         load_pack<T, VV>(x[r][1], reinterpret_cast<const T *>(tile_lane + (cn[r][1] << 4)));
                 }
-                // next step of this row block, or the first step of the next one
-                int nsp = sp + 1, nkb = kb;
-                if (nsp == S) {
-                    nsp = 0;
-                    nkb = kb + 1;
-                }
-                if (nkb < KB) read_entries(nkb, nsp);
+                if (more) read_entries(next_rb, nsp);
 #pragma unroll
                 for (int r = 0; r < R; ++r) {
 #pragma unroll
                     for (int i = 0; i < VV; ++i) acc[r][i] += v[r].x[0] * x[r][0][i];
-                    if (two) {
+                    if (TWO) {
 #pragma unroll
                         for (int i = 0; i < VV; ++i) acc[r][i] += v[r].x[1] * x[r][1][i];
                     }
+                }
+            };
+            for (int sp = 0; sp + 1 < S; ++sp) step(std::true_type(), rb, sp + 1, true);
+            if (S > 0) {
+                // the step after the last one is the first of the next row block
+                const bool more = kb + 1 < KB;
+                if (more) first_entries(rbn, kb + 1);
+                if (last_two) step(std::true_type(), rbn, 0, more);
+                else step(std::false_type(), rbn, 0, more);
+                if (more) {
+#pragma unroll
+                    for (int r = 0; r < R; ++r) rb[r] = rbn[r];
                 }
             }
 #pragma unroll
