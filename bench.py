@@ -41,8 +41,8 @@ TILE_PARAMS = {
 # WRITE_SIZE, scaled by what the same counters read for a plain copy), keyed by workload;
 # None until measured.  See profiles/.
 MEASURED_TRAFFIC_BYTES = {
-    # profiles/k_fused_gemm_spmm_cfg2_2dlaplacian.md: FETCH_SIZE 37927.7 KiB x 2.000 + WRITE_SIZE 73448.2 KiB
-    "cfg2 GeMM-SpMM fp32 2D Laplacian n=262144 64->64": int((2.0 * 37927.7 + 73448.2) * 1024),
+    # profiles/k_fused_gemm_spmm_cfg2_2dlaplacian.md: FETCH_SIZE 37931.7 KiB x 2.000 + WRITE_SIZE 73448.2 KiB
+    "cfg2 GeMM-SpMM fp32 2D Laplacian n=262144 64->64": int((2.0 * 37931.7 + 73448.2) * 1024),
     # profiles/k_fused_spmm_spmm_cfg4_3dlaplacian.md: FETCH_SIZE 125556.3 KiB x 2.000 + WRITE_SIZE 168471.5 KiB
     "cfg4 SpMM-SpMM fp64 3D Laplacian n=262144 262144->64": int((2.0 * 125556.3 + 168471.5) * 1024),
 }
