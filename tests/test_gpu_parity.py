@@ -316,6 +316,36 @@ def test_execution_calls_can_be_captured_in_a_graph(kind):
         c.close()
 
 
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("ccol", [8, 32, 100])
+def test_csr_b_rows_of_every_length(dtype, ccol):
+    """The CSR-B kernels stage up to 8 entries of a row of B in LDS and gather longer rows from
+    device memory: rows of B with 0, 1, ..., 8, 9, ... 40 entries (duplicates, unsorted columns)
+    side by side, so that both paths and every padding pattern of the staged slots occur in one
+    wave; integer entries, so bit-exact, fused and unfused, consecutive and graph-grown tiles."""
+    import paper_2407_00243_amd as tf
+    n, bcol = 700, 90
+    rng = np.random.default_rng(17)
+    A = ti.random_local_csr(n, 6, 5, 0.15, dtype, 18, int_values=True)
+    lens = np.concatenate([np.arange(0, 41), rng.integers(0, 12, n - 41)])
+    rng.shuffle(lens)
+    rowptr = np.zeros(n + 1, np.int32)
+    rowptr[1:] = np.cumsum(lens)
+    colidx = np.concatenate([rng.integers(0, bcol, l) for l in lens]).astype(np.int32)
+    B = ti.Csr(n, bcol, rowptr, colidx, rng.integers(-2, 3, colidx.size).astype(dtype))
+    C = ti.dense_small_int(bcol, ccol, dtype, 19)
+    prob = ti.Problem("row lengths", "spmm_spmm", np.dtype(dtype), A, B, C)
+    D_ref, _ = oracle.chain(A, B, C)
+    for params in (dict(ct_size=96, p=1), dict(ct_size=96, p=1, flags=tf.TF_FLAG_REORDER)):
+        c = _case(prob, **params)
+        try:
+            assert 0 < c.plan.schedule()["n_fused_rows"] < n
+            for fused in (True, False):
+                assert np.array_equal(c.run(fused=fused).astype(np.float64), D_ref), (params, fused)
+        finally:
+            c.close()
+
+
 # ---------------------------------------------------------------- invariants on the GPU
 
 def test_identity_a_returns_bc():
