@@ -64,7 +64,7 @@ inline int lds_row_granule(int b_is_sparse) { return b_is_sparse ? 1 : kRowGranu
 constexpr int kSparseEntryCap = 8;
 constexpr int kCsrRowsPerWg = 64;        // rows of one workgroup of the unfused CSR SpMM
 inline int64_t lds_sparse_b_bytes_per_row(int dtype) {
-    return 8 + kSparseEntryCap * (4 + (int64_t)elem_size(dtype));
+    return 2 * 8 + kSparseEntryCap * (4 + (int64_t)elem_size(dtype));    // extents of two tiles
 }
 
 // Whether a wave of the dense-B kernels keeps its operands of the C slice in registers: only for
@@ -126,9 +126,10 @@ inline FusedLdsLayout fused_lds_layout(int dtype, int b_is_sparse, int bcol, int
     l.first0 = 0;
     l.first1 = rows16 * 4;
     l.second = 2 * rows16 * 4;
-    // staged rows of a CSR B: (first entry, length) per row, then the column indices, then the values
+    // staged rows of a CSR B: (first entry, length) per row for this tile and for the next one,
+    // then the column indices, then the values
     l.bext = l.second + round_up(s_lds, 16);
-    l.bidx = l.bext + (b_is_sparse ? round_up(rows_cap * 8, 16) : 0);
+    l.bidx = l.bext + (b_is_sparse ? 2 * round_up(rows_cap * 8, 16) : 0);
     l.bval = l.bidx + (b_is_sparse ? round_up(rows_cap * kSparseEntryCap * 4, 16) : 0);
     l.cslice = l.bval + (b_is_sparse ? round_up(rows_cap * kSparseEntryCap * es, 16) : 0);
     const int64_t cbytes = lds_fixed_bytes(dtype, b_is_sparse, bcol, cs);

@@ -498,8 +498,9 @@ __device__ __forceinline__ TileWalk tile_walk(int n_tiles, int n_slices) {
 struct FusedSmem {
     int32_t *first[2];            // row ids (bit 31 = spill) of the current and of the next tile
     unsigned char *second;        // staged second-phase block (or unused)
-    int32_t *bext, *bidx;         // CSR B: (first entry, length) of the tile's rows of B, their column
-    unsigned char *bval;          //        indices and values, kSparseEntryCap slots per row
+    int32_t *bext, *bidx;         // CSR B: (first entry, length) of the rows of B of this tile and of the
+    unsigned char *bval;          //        next (bext_stride ints apart), column indices and values
+    int bext_stride;              //        (kSparseEntryCap slots per row)
     unsigned char *cslice;
     unsigned char *tile;
 };
@@ -513,7 +514,8 @@ __device__ __forceinline__ FusedSmem fused_smem(const FusedLaunch &a, bool c_reg
     m.second = tf_smem + 2 * (int64_t)a.rows_cap * 4;
     unsigned char *p = m.second + (a.s_in_lds ? a.s_cap : 0);
     m.bext = reinterpret_cast<int32_t *>(p);
-    if (sparse_es) p += up16((int64_t)a.tile_rows * 8);
+    m.bext_stride = (int)(up16((int64_t)a.tile_rows * 8) / 4);
+    if (sparse_es) p += 2 * up16((int64_t)a.tile_rows * 8);
     m.bidx = reinterpret_cast<int32_t *>(p);
     if (sparse_es) p += up16((int64_t)a.tile_rows * kSparseEntryCap * 4);
     m.bval = p;
@@ -905,26 +907,30 @@ constexpr int kEntriesPerPassLong = 4;   // entries in flight per lane for a row
 // Per row the chain row id -> extent -> entries -> rows of X is three dependent loads; walked row
 // by row it leaves the memory pipe idle most of the time.  Here the whole workgroup takes each
 // link of the chain for all rows of the list at once, handing over through LDS:
-// stage_csr_rows     (1) extents of all rows, (2) up to kSparseEntryCap entries of every row
-//                    (padding slots repeat the row's last entry, or column 0 for an empty row, so
-//                    that the gathers need no bounds); ends with a barrier;
+// stage_extents      (1) extents of all rows;
+// stage_entries      (2) up to kSparseEntryCap entries of every row (padding slots repeat the
+//                    row's last entry, or column 0 for an empty row, so that the gathers need no
+//                    bounds);
 // gather_staged_rows (3) the gathers, RP rows of kSparseEntryCap slots each in flight per lane;
 //                    out(pos, acc) takes a finished row.  A row with more entries than the cap
 //                    is gathered from device memory entry by entry.
 // ext holds 2 ints per row, eidx and eval kSparseEntryCap slots per row (LDS, 16-byte aligned).
-template <typename T, typename RowFn>
-__device__ __forceinline__ void stage_csr_rows(int rows, int32_t *ext, int32_t *eidx, T *eval,
-                                               const int32_t *__restrict__ rowptr,
-                                               const int32_t *__restrict__ colidx,
-                                               const T *__restrict__ vals, RowFn row_of) {
-    constexpr int CAP = kSparseEntryCap;
+template <typename RowFn>
+__device__ __forceinline__ void stage_extents(int rows, int32_t *ext,
+                                              const int32_t *__restrict__ rowptr, RowFn row_of) {
     for (int i = threadIdx.x; i < rows; i += (int)blockDim.x) {
         const int64_t rid = row_of(i);
         const int kb = rowptr[rid], ke = rowptr[rid + 1];
         ext[2 * i] = kb;
         ext[2 * i + 1] = ke - kb;
     }
-    __syncthreads();
+}
+// (the extents must be visible to the workgroup; ends with a barrier)
+template <typename T>
+__device__ __forceinline__ void stage_entries(int rows, const int32_t *ext, int32_t *eidx, T *eval,
+                                              const int32_t *__restrict__ colidx,
+                                              const T *__restrict__ vals) {
+    constexpr int CAP = kSparseEntryCap;
     constexpr int SW = 4;                                  // slots per thread whose loads go out together
     const int total = rows * CAP;
     for (int s0 = threadIdx.x; s0 < total; s0 += SW * (int)blockDim.x) {
@@ -1073,6 +1079,11 @@ __global__ __launch_bounds__(kFusedSparseThreads) void k_fused_spmm_spmm(const F
         for (int e = threadIdx.x; e < n16; e += (int)blockDim.x) sm.first[0][e] = src[e];
     }
     __syncthreads();
+    // extents of the first tile's rows of B; those of every later tile are fetched during the
+    // second phase of the tile before it
+    auto row_id = [](const int32_t *ids, int i) { return (int64_t)((uint32_t)ids[i] & ~kSpillBit); };
+    stage_extents(d.n_rows, sm.bext, a.Bs.rowptr, [&](int i) { return row_id(sm.first[0], i); });
+    __syncthreads();
     for (;;) {
         const int rows = d.n_rows;
         const int32_t *first = sm.first[0] + par * a.rows_cap;
@@ -1090,12 +1101,12 @@ __global__ __launch_bounds__(kFusedSparseThreads) void k_fused_spmm_spmm(const F
         // wavefront reads also goes to the D1 workspace, from the registers of its lane group
         {
             T *eval = reinterpret_cast<T *>(sm.bval);
-            stage_csr_rows<T>(rows, sm.bext, sm.bidx, eval, a.Bs.rowptr, a.Bs.colidx, bvals,
-                              [&](int i) { return (int64_t)((uint32_t)first[i] & ~kSpillBit); });
+            const int32_t *ext_cur = sm.bext + par * sm.bext_stride;
+            stage_entries<T>(rows, ext_cur, sm.bidx, eval, a.Bs.colidx, bvals);
             T *tile_lane = tileD1 + VV * gl;
             T *D1l = static_cast<T *>(a.D1) + c0 + VV * gl;
             gather_staged_rows<T, VV, 1>(
-                rows, sm.bext, sm.bidx, eval, a.Bs.colidx, bvals, C + c0 + VV * gl, ccol,
+                rows, ext_cur, sm.bidx, eval, a.Bs.colidx, bvals, C + c0 + VV * gl, ccol,
                 VV * gl < w, grp, ngrp, [&](int pos, const T(&acc)[VV]) {
                     store_pack<T, VV>(tile_lane + (int64_t)pos * ldl, acc);
                     const uint32_t enc = (uint32_t)first[pos];
@@ -1111,9 +1122,42 @@ __global__ __launch_bounds__(kFusedSparseThreads) void k_fused_spmm_spmm(const F
             reinterpret_cast<Piece *>((sm.first[0] + (par ^ 1) * a.rows_cap))[e] =
                 reinterpret_cast<const Piece *>(a.tile_meta + nd.meta_off)[e];
         __syncthreads();
+        // the extents of the next tile's rows of B are on their way during the second phase
+        constexpr int NE = 1;                               // rows per thread fetched that way
+        const int32_t *next_first = sm.first[0] + (par ^ 1) * a.rows_cap;
+        int nb0[NE], nb1[NE];
+        if (has_next) {
+#pragma unroll
+            for (int e = 0; e < NE; ++e) {
+                const int i = (int)threadIdx.x + e * (int)blockDim.x;
+                if (i < nd.n_rows) {
+                    const int64_t rid = row_id(next_first, i);
+                    nb0[e] = a.Bs.rowptr[rid];
+                    nb1[e] = a.Bs.rowptr[rid + 1];
+                }
+            }
+        }
         if (VV * gl < w)
             fused_tail<T, VV, 2>(a, d, SLDS ? sm.second : blk, tileD1, ldl, c0, gl, grp, ngrp);
         if (!has_next) break;
+        {
+            int32_t *ext = sm.bext + (par ^ 1) * sm.bext_stride;
+#pragma unroll
+            for (int e = 0; e < NE; ++e) {
+                const int i = (int)threadIdx.x + e * (int)blockDim.x;
+                if (i < nd.n_rows) {
+                    ext[2 * i] = nb0[e];
+                    ext[2 * i + 1] = nb1[e] - nb0[e];
+                }
+            }
+            // (a tile of more rows than that: the rest the plain way)
+            for (int i = NE * (int)blockDim.x + (int)threadIdx.x; i < nd.n_rows; i += (int)blockDim.x) {
+                const int64_t rid = row_id(next_first, i);
+                const int kb = a.Bs.rowptr[rid];
+                ext[2 * i] = kb;
+                ext[2 * i + 1] = a.Bs.rowptr[rid + 1] - kb;
+            }
+        }
         __syncthreads();
         d = nd;
         tw.tile = ntile;
@@ -1316,13 +1360,14 @@ __global__ __launch_bounds__(kSpmmThreads) void k_csr_spmm(const CsrSpmmLaunch a
     const T *__restrict__ vals = static_cast<const T *>(a.S.vals);
     const T *__restrict__ X = static_cast<const T *>(a.X);
     T *__restrict__ Y = static_cast<T *>(a.Y);
-    // the rows of the workgroup are staged once (see stage_csr_rows), then gathered per column block
+    // the rows of the workgroup are staged once (see stage_extents), then gathered per column block
     __shared__ __align__(16) int32_t ext_s[2 * kCsrRowsPerWg];
     __shared__ __align__(16) int32_t idx_s[kSparseEntryCap * kCsrRowsPerWg];
     __shared__ __align__(16) T val_s[kSparseEntryCap * kCsrRowsPerWg];
     const int rows = (int)(r1 - r0);
-    stage_csr_rows<T>(rows, ext_s, idx_s, val_s, a.S.rowptr, a.S.colidx, vals,
-                      [&](int i) { return r0 + i; });
+    stage_extents(rows, ext_s, a.S.rowptr, [&](int i) { return r0 + i; });
+    __syncthreads();
+    stage_entries<T>(rows, ext_s, idx_s, val_s, a.S.colidx, vals);
     for (int cb = 0; cb < ccol; cb += G * VV) {
         const int col = cb + VV * gl;
         gather_staged_rows<T, VV, 2>(rows, ext_s, idx_s, val_s, a.S.colidx, vals, X + col, ccol,
