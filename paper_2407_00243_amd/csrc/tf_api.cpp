@@ -66,7 +66,7 @@ struct tf_plan {
             return d;
         }
     };
-    DevBuf tile_desc, tile_meta;
+    DevBuf tile_desc, tile_meta, tile_first;
     PackBufs wf1, all;
     DevBuf d1;
 };
@@ -119,6 +119,8 @@ tf::FusedLaunch fused_args(const tf_plan *p, const void *C, void *D) {
                                       (int)p->s.max_tile_rows, a.s_in_lds ? a.s_cap : 0);
     a.tile_desc = static_cast<const tf::TileDesc *>(p->tile_desc.p);
     a.tile_meta = static_cast<const unsigned char *>(p->tile_meta.p);
+    a.tile_first = static_cast<const int32_t *>(p->tile_first.p);
+    a.first_stride = p->s.first_stride;
     a.C = C;
     a.c_ldk = p->c_transposed ? 1 : a.ccol;
     a.c_ldc = p->c_transposed ? a.bcol : 1;
@@ -302,6 +304,8 @@ tf_status tf_plan_create(const tf_csr *A, int64_t bCol, int64_t cCol, int32_t b_
         ok(up(p->tile_desc, p->s.tile_desc));
         ok(up(p->tile_meta, p->s.tile_meta));
         std::vector<unsigned char>().swap(p->s.tile_meta);
+        ok(up(p->tile_first, p->s.tile_first));
+        std::vector<int32_t>().swap(p->s.tile_first);
         ok(upload_pack(p->wf1, p->s.wf1));
         ok(upload_pack(p->all, p->s.all));
         ok(p->d1.alloc((size_t)n * cCol * es));

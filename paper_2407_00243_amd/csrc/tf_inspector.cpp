@@ -488,10 +488,11 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
     s.n_spill_rows = std::accumulate(s.spill.begin(), s.spill.end(), (int64_t)0);
     // ---- per-tile blocks (see TileDesc) ---------------------------------------------------
     s.tile_desc.resize((size_t)nt);
+    s.first_stride = (int32_t)round_up(std::max<int64_t>(s.max_tile_rows, 1), 16);
+    s.tile_first.assign((size_t)nt * s.first_stride, 0);
     for (int64_t vt = 0; vt < nt; ++vt) {
         const int64_t f0 = s.tile_first_ptr[vt], f1 = s.tile_first_ptr[vt + 1];
         TileBlock &tb = blocks[(size_t)vt];
-        const size_t first_bytes = (size_t)round_up(f1 - f0, 16) * 4;
         TileDesc &d = s.tile_desc[(size_t)vt];
         d.meta_off = (int64_t)s.tile_meta.size();
         d.n_rows = (int32_t)(f1 - f0);
@@ -500,15 +501,13 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
         d.n_entries = tb.n_entries;
         d.s_bytes = (int32_t)tb.bytes.size();
         d.reserved = 0;
-        s.tile_meta.resize(s.tile_meta.size() + first_bytes + tb.bytes.size(), 0);
-        unsigned char *m = s.tile_meta.data() + d.meta_off;
-        int32_t *first = reinterpret_cast<int32_t *>(m);
+        int32_t *first = s.tile_first.data() + (size_t)vt * s.first_stride;
         for (int64_t q = f0; q < f1; ++q) {
             const int32_t row = s.first_rows[q];
             first[q - f0] = (int32_t)((uint32_t)row | (s.spill[row] ? kSpillBit : 0u));
         }
-        for (int64_t q = f1 - f0; q < (int64_t)(first_bytes / 4); ++q) first[q] = s.first_rows[f1 - 1];
-        if (!tb.bytes.empty()) std::memcpy(m + first_bytes, tb.bytes.data(), tb.bytes.size());
+        for (int64_t q = f1 - f0; q < s.first_stride; ++q) first[q] = s.first_rows[f1 - 1];
+        s.tile_meta.insert(s.tile_meta.end(), tb.bytes.begin(), tb.bytes.end());
         s.second_block_cap = std::max<int64_t>(s.second_block_cap, (int64_t)tb.bytes.size());
         TileBlock().bytes.swap(tb.bytes);
     }

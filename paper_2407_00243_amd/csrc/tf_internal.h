@@ -83,12 +83,12 @@ inline int mfma_ksteps_special(int dtype, int bcol, int ccol, int cs) {
     return (ks == 2 || ks == 4 || ks == 8 || ks == 16) ? ks : 0;
 }
 
-// What a fused workgroup needs to know about one tile, as one contiguous block of bytes in
-// device memory plus this fixed-size descriptor, so that nothing in the tile waits for a chain
-// of dependent loads (row list -> unit -> entries).  The block, 16-byte aligned, holds
-//   int32    first[round_up(n_rows, 16)]   row ids of the tile's D1 rows, bit 31 = spill;
-//                                          padding repeats the last row without the bit
-// followed by the second-phase block of s_bytes bytes (each array padded to 16 bytes):
+// What a fused workgroup needs to know about one tile: the ids of its D1 rows (bit 31 = spill)
+// in an array with the same stride for every tile, so that their address follows from the tile's
+// number alone (the first loads of a workgroup do not wait for a descriptor); padding up to the
+// stride repeats the last row without the bit.  And, so that nothing in the tile waits for a
+// chain of dependent loads (row list -> unit -> entries), this fixed-size descriptor plus one
+// contiguous, 16-byte aligned second-phase block of s_bytes bytes (each array padded to 16 bytes):
 //   TileUnit units[n_units]
 //   int32    rows2[n_second]               row ids of the fused rows of D, unit after unit
 //   uint16   idx[n_entries]                where the D1 row of every packed entry sits in the LDS tile,
@@ -179,7 +179,9 @@ struct Schedule {
     std::vector<int32_t> wf1_unit_ptr, wf1_rows;
     std::vector<uint8_t> spill;
     std::vector<TileDesc> tile_desc;                      // one per tile, see TileDesc
-    std::vector<unsigned char> tile_meta;                 // the tiles' blocks, back to back
+    std::vector<unsigned char> tile_meta;                 // the tiles' second-phase blocks, back to back
+    std::vector<int32_t> tile_first;                      // the tiles' row ids, first_stride ints per tile
+    int32_t first_stride = 0;                             // largest tile, in rows, rounded up to 16
     int64_t second_block_cap = 0;                         // largest second-phase block, bytes
     bool second_block_in_lds = true;                      // it fits beside the largest tile
     int64_t lds_meta_bytes_per_row = 0;                   // part of lds_bytes_per_row: row ids + estimate of the second-phase block
@@ -235,6 +237,8 @@ struct FusedLaunch {
     int64_t lds_bytes;                // dynamic LDS of the launch
     const TileDesc *tile_desc;
     const unsigned char *tile_meta;
+    const int32_t *tile_first;        // row ids of tile v at tile_first + v * first_stride
+    int32_t first_stride;
     const void *B;                    // dense B (gemm) or nullptr
     CsrDev Bs;                        // sparse B (spmm)
     const void *C;

@@ -753,14 +753,16 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
     BFrag<T, KSF> fb[ND];
     T creg[CREG ? KSF * V * NB : 1];
     {
-        // Start-up, ordered so that the longest chain (descriptor -> row ids -> rows of B) begins
-        // first: each lane fetches the ids of its own first rows straight from device memory, the
-        // C operands and the copy of all row ids to LDS follow, then the B loads go out.
-        const int32_t *src = reinterpret_cast<const int32_t *>(a.tile_meta + d.meta_off);
+        // Start-up, ordered so that the longest chain (row ids -> rows of B) begins first: each
+        // lane fetches the ids of its own first rows straight from device memory, at an address
+        // that follows from the tile's number (no wait for the descriptor; ids past the tile's
+        // last row repeat it up to the stride); the C operands and the copy of all row ids to LDS
+        // follow, then the B loads go out.
+        const int32_t *src = a.tile_first + (int64_t)tw.tile * a.first_stride;
         int64_t row0[ND - 1];
         if constexpr (KS > 0) {
 #pragma unroll
-            for (int i = 0; i < ND - 1; ++i) row0[i] = row_of(src, d.n_rows, wave + i * nmw);
+            for (int i = 0; i < ND - 1; ++i) row0[i] = row_of(src, a.first_stride, wave + i * nmw);
         }
         const int n16 = (d.n_rows + 15) & ~15;
         for (int e = threadIdx.x; e < n16; e += (int)blockDim.x) sm.first[0][e] = src[e];
@@ -784,8 +786,9 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
         const int ntile = tw.tile + tw.step;
         const bool has_next = ntile < tw.tile_end;
         const TileDesc nd = a.tile_desc[has_next ? ntile : tw.tile];
-        const unsigned char *blk = a.tile_meta + d.meta_off + (((int64_t)rows + 15) & ~15) * 4;
-        const Piece *nsrc = reinterpret_cast<const Piece *>(a.tile_meta + nd.meta_off);
+        const unsigned char *blk = a.tile_meta + d.meta_off;
+        const Piece *nsrc = reinterpret_cast<const Piece *>(
+            a.tile_first + (int64_t)(has_next ? ntile : tw.tile) * a.first_stride);
 
         // on their way during phase 1: this tile's second-phase block, the next tile's row ids
         Staged<kStagePieces> st;
@@ -1075,7 +1078,7 @@ __global__ __launch_bounds__(kFusedSparseThreads) void k_fused_spmm_spmm(const F
     int par = 0;
     {
         const int n16 = (d.n_rows + 15) & ~15;
-        const int32_t *src = reinterpret_cast<const int32_t *>(a.tile_meta + d.meta_off);
+        const int32_t *src = a.tile_first + (int64_t)tw.tile * a.first_stride;
         for (int e = threadIdx.x; e < n16; e += (int)blockDim.x) sm.first[0][e] = src[e];
     }
     __syncthreads();
@@ -1090,12 +1093,13 @@ __global__ __launch_bounds__(kFusedSparseThreads) void k_fused_spmm_spmm(const F
         const int ntile = tw.tile + tw.step;
         const bool has_next = ntile < tw.tile_end;
         const TileDesc nd = a.tile_desc[has_next ? ntile : tw.tile];
-        const unsigned char *blk = a.tile_meta + d.meta_off + (((int64_t)rows + 15) & ~15) * 4;
+        const unsigned char *blk = a.tile_meta + d.meta_off;
         Staged<kStagePieces> st;
         const int nfirst_pieces = has_next ? ((nd.n_rows + 15) >> 4) * 4 : 0;
         if constexpr (SLDS) stage_issue<kStagePieces>(st, blk, d.s_bytes, threadIdx.x, blockDim.x);
-        const Piece nfirst = reinterpret_cast<const Piece *>(
-            a.tile_meta + nd.meta_off)[(int)threadIdx.x < nfirst_pieces ? threadIdx.x : 0];
+        const Piece *nsrc = reinterpret_cast<const Piece *>(
+            a.tile_first + (int64_t)(has_next ? ntile : tw.tile) * a.first_stride);
+        const Piece nfirst = nsrc[(int)threadIdx.x < nfirst_pieces ? threadIdx.x : 0];
 
         // D1[pos] = B[row(pos), :] C for the tile's rows, into the LDS tile; a row that the second
         // wavefront reads also goes to the D1 workspace, from the registers of its lane group
@@ -1120,7 +1124,7 @@ __global__ __launch_bounds__(kFusedSparseThreads) void k_fused_spmm_spmm(const F
             reinterpret_cast<Piece *>((sm.first[0] + (par ^ 1) * a.rows_cap))[threadIdx.x] = nfirst;
         for (int e = (int)blockDim.x + threadIdx.x; e < nfirst_pieces; e += (int)blockDim.x)
             reinterpret_cast<Piece *>((sm.first[0] + (par ^ 1) * a.rows_cap))[e] =
-                reinterpret_cast<const Piece *>(a.tile_meta + nd.meta_off)[e];
+                nsrc[e];
         __syncthreads();
         // the extents of the next tile's rows of B are on their way during the second phase
         constexpr int NE = 1;                               // rows per thread fetched that way
