@@ -28,7 +28,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_PEAK_TFLOPS = {"f32": 157.3, "f64": 78.6}
 
-# Tile parameters used per configuration.
+# Tile parameters used per configuration: graph-grown tiles as large as the LDS allows for the
+# stencils (2, 4), consecutive tiles of the given size for the band (1) and the graphs (3, 5).
 TILE_PARAMS = {
     1: dict(ct_size=64, p=1),
     2: dict(ct_size=65536, p=1, flags=4),
@@ -86,7 +87,8 @@ def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build runs on ONE GPU only (the path is a single-GPU kernel pipeline; "
-            "how it would shard is described in DESIGN.md).  Re-run with --gpus 1.")
+            "it would shard by row blocks aligned to tile boundaries with one exchange of spilled rows "
+            "between the wavefronts).  Re-run with --gpus 1.")
         sys.exit(2)
 
     import numpy as np
