@@ -448,13 +448,19 @@ __device__ __forceinline__ void mfma_frag(typename Tr<T>::Acc (&acc)[NB], const 
     constexpr int V = Tr<T>::V;
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) acc[nb] = typename Tr<T>::Acc{0, 0, 0, 0};
+    // the C operands of step i + 1 are read from LDS before the MFMAs of step i are issued
+    T c[2][NB];
 #pragma unroll
-    for (int s = 0; s < KS; ++s)
+    for (int nb = 0; nb < NB; ++nb) c[0][nb] = Cl[nb * 64 + lane];
 #pragma unroll
-        for (int q = 0; q < V; ++q)
+    for (int i = 0; i < KS * V; ++i) {
+        if (i + 1 < KS * V) {
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
-                acc[nb] = mfma16(Cl[((s * V + q) * NB + nb) * 64 + lane], f.v[s][q], acc[nb]);
+            for (int nb = 0; nb < NB; ++nb) c[(i + 1) & 1][nb] = Cl[((i + 1) * NB + nb) * 64 + lane];
+        }
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) acc[nb] = mfma16(c[i & 1][nb], f.v[i / V][i % V], acc[nb]);
+    }
 }
 
 // The same with the lane's C operands already in registers (creg[(s V + q) NB + nb]).
