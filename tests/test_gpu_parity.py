@@ -346,6 +346,28 @@ def test_csr_b_rows_of_every_length(dtype, ccol):
             c.close()
 
 
+def test_csr_b_tiles_of_more_rows_than_threads():
+    """Narrow fp32 C (4 columns): LDS holds tiles of 1200 rows, more rows than a workgroup has
+    threads, so every per-row staging loop of the CSR-B kernel takes more than one trip."""
+    import paper_2407_00243_amd as tf
+    dtype = np.float32
+    n, bcol, ccol = 9000, 50, 4
+    A = ti.random_local_csr(n, 4, 3, 0.1, dtype, 31, int_values=True)
+    B = ti.random_pattern_csr(n, bcol, 0.08, dtype, 32, int_values=True, empty_row_prob=0.1)
+    C = ti.dense_small_int(bcol, ccol, dtype, 33)
+    prob = ti.Problem("big tiles", "spmm_spmm", np.dtype(dtype), A, B, C)
+    D_ref, _ = oracle.chain(A, B, C)
+    for params in (dict(ct_size=2400, p=1), dict(ct_size=1200, p=1, flags=tf.TF_FLAG_REORDER)):
+        c = _case(prob, **params)
+        try:
+            s = c.plan.schedule()
+            assert np.diff(s["tile_first_ptr"]).max() > 1024 and s["n_tiles"] >= 2
+            for fused in (True, False):
+                assert np.array_equal(c.run(fused=fused).astype(np.float64), D_ref), (params, fused)
+        finally:
+            c.close()
+
+
 # ---------------------------------------------------------------- invariants on the GPU
 
 def test_identity_a_returns_bc():
