@@ -32,7 +32,7 @@ MFMA_PEAK_TFLOPS = {"f32": 157.3, "f64": 78.6}
 # stencils (2, 4), consecutive tiles of the given size for the band (1) and the graphs (3, 5).
 TILE_PARAMS = {
     1: dict(ct_size=64, p=1),
-    2: dict(ct_size=65536, p=1, flags=4),
+    2: dict(ct_size=65536, p=1, flags=4, fast_mem_bytes=81920),   # two workgroups per compute unit
     3: dict(ct_size=128, p=1),
     4: dict(ct_size=65536, p=1, flags=4),
     5: dict(ct_size=2048, p=1),
@@ -42,8 +42,8 @@ TILE_PARAMS = {
 # WRITE_SIZE, scaled by what the same counters read for a plain copy), keyed by workload;
 # None until measured.  See profiles/.
 MEASURED_TRAFFIC_BYTES = {
-    # profiles/k_fused_gemm_spmm_cfg2_2dlaplacian.md: FETCH_SIZE 37931.7 KiB x 2.000 + WRITE_SIZE 73448.2 KiB
-    "cfg2 GeMM-SpMM fp32 2D Laplacian n=262144 64->64": int((2.0 * 37931.7 + 73448.2) * 1024),
+    # profiles/k_fused_gemm_spmm_cfg2_2dlaplacian.md: FETCH_SIZE 37708.4 KiB x 2.000 + WRITE_SIZE 76090.2 KiB
+    "cfg2 GeMM-SpMM fp32 2D Laplacian n=262144 64->64": int((2.0 * 37708.4 + 76090.2) * 1024),
     # profiles/k_fused_spmm_spmm_cfg4_3dlaplacian.md: FETCH_SIZE 125556.3 KiB x 2.000 + WRITE_SIZE 168471.5 KiB
     "cfg4 SpMM-SpMM fp64 3D Laplacian n=262144 262144->64": int((2.0 * 125556.3 + 168471.5) * 1024),
 }
