@@ -29,7 +29,7 @@ def test_full_size_config(cfg):
     from gpu_util import Case, assert_parity
     print(f"config {cfg}: generating", flush=True)
     prob = ti.config(cfg)
-    params = dict(bench.TILE_PARAMS[cfg])
+    params = bench.tile_params(cfg)
     c = Case(prob, **params)
     try:
         s = c.plan.schedule()
