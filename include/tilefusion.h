@@ -137,7 +137,8 @@ typedef struct tf_schedule_view {
     int32_t second_block_in_lds; /* 1: the packed entries of a tile's fused rows are staged in LDS;
                                    0: they did not fit beside the largest tile and are read in place */
     double eq2_cost_max;        /* largest Eq. 2 data-movement cost over the tiles (elements)  */
-    double plan_seconds;        /* host time spent building the schedule                       */
+    double plan_seconds;        /* host time spent building the schedule (without the packed
+                                   copy of A that only the unfused baseline uses)              */
     int64_t alg_bytes;          /* algorithmic HBM bytes of one fused execution                */
     int64_t alg_bytes_unfused;  /* the same for the unfused two-kernel execution               */
     int64_t second_block_bytes; /* largest per-tile block of packed entries (fused rows)       */

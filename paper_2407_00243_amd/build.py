@@ -14,7 +14,7 @@ HEADERS = ["tf_internal.h", os.path.join("..", "..", "include", "tilefusion.h")]
 # packed-fp32 instructions are switched off for all device code
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-               "-Wno-unused-command-line-argument", "-x", "hip"]
+               "-Wno-unused-command-line-argument", "-pthread", "-x", "hip"]
 
 
 def is_stale() -> bool:

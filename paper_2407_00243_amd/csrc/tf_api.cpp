@@ -287,6 +287,7 @@ tf_status tf_plan_create(const tf_csr *A, int64_t bCol, int64_t cCol, int32_t b_
             *out = p;
             return TF_OK;
         }
+        tf::build_baseline_pack(in, p->s);
         p->lds_per_cu = lds_limit;
         // the launch must fit the device whatever the schedule's own estimate said
         auto launch_lds = [&]() {

@@ -10,9 +10,11 @@
 //
 // Pure host code: no HIP calls.
 #include <algorithm>
+#include <atomic>
 #include <chrono>
 #include <cstring>
 #include <numeric>
+#include <thread>
 
 #include "tf_internal.h"
 
@@ -227,6 +229,17 @@ TileBlock pack_tile(const int32_t *rowptr, const int32_t *colidx, const unsigned
 
 }  // namespace
 
+// Units of a packed row list of `count` rows: a unit is one workgroup; short lists are cut into
+// smaller units (down to one row per lane group) so that they still spread over the machine.
+static PackRules pack_rules(const InspectorInput &in, int64_t count) {
+    const int v = vec_elems(in.dtype);
+    const int vv = in.ccol % v == 0 ? v : 1;
+    const int groups = kSpmmThreads / lane_group((int)in.ccol, vv);
+    const int64_t want = (count + 1023) / 1024;
+    return PackRules{(int)std::min<int64_t>(kUnitRows, std::max<int64_t>(groups, want)), kUnitSlots,
+                     groups};
+}
+
 tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err) {
     const int64_t n = in.n;
     const int es = elem_size(in.dtype);
@@ -436,9 +449,18 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
             local_of[s.first_rows[q]] = (int32_t)(q - s.tile_first_ptr[vt]);
     }
     std::vector<int32_t> seen((size_t)n, -1);      // Eq. 2: distinct columns per tile
-    for (int64_t vt = 0; vt < nt; ++vt) {
+    // Per tile: which of its rows are fused, and their packed block.  Tiles are independent (a fused
+    // row only names columns of its own tile, so even `seen` is written at disjoint places), which
+    // lets several host threads share the tiles of a large matrix; the results are put together
+    // in tile order afterwards, so the schedule does not depend on the number of threads.
+    struct TileResult {
+        std::vector<int32_t> wf1;
+        int64_t tile_nnz = 0, uc = 0, nj = 0;
+    };
+    std::vector<TileResult> res((size_t)nt);
+    auto classify = [&](int64_t vt) {
+        TileResult &tr = res[(size_t)vt];
         std::vector<int32_t> tile_rows;
-        int64_t tile_nnz = 0, uc = 0;
         for (int64_t fq = member_ptr[vt]; fq < member_ptr[vt + 1]; ++fq) {
             const int64_t j = member_rows[fq];
             // (a row of 32768 entries or more, possible only with duplicates, is left to the second
@@ -456,27 +478,53 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
                     const int32_t c = in.colidx[q];
                     if (seen[c] != (int32_t)vt) {
                         seen[c] = (int32_t)vt;
-                        ++uc;
+                        ++tr.uc;
                     }
                 }
-                tile_nnz += in.rowptr[j + 1] - in.rowptr[j];
+                tr.tile_nnz += in.rowptr[j + 1] - in.rowptr[j];
             } else {
-                wf1.push_back((int32_t)j);
+                tr.wf1.push_back((int32_t)j);
             }
         }
-        const int64_t rows = s.tile_first_ptr[vt + 1] - s.tile_first_ptr[vt];
-        const int64_t nj = (int64_t)tile_rows.size();
-        s.tile_second_ptr[vt] = (int32_t)s.second_rows.size();
+        tr.nj = (int64_t)tile_rows.size();
         blocks[(size_t)vt] = pack_tile(in.rowptr, in.colidx, vals, es, tile_rows,
                                        [&](int32_t c) { return local_of[c] * pitch16; });
+    };
+    {
+        int nthreads = 1;
+        if (in.nnz >= (int64_t)1 << 18 && nt >= 64)
+            nthreads = (int)std::min<int64_t>(std::min<unsigned>(std::max(1u, std::thread::hardware_concurrency()), 16u),
+                                              nt / 16);
+        if (nthreads <= 1) {
+            for (int64_t vt = 0; vt < nt; ++vt) classify(vt);
+        } else {
+            std::atomic<bool> failed{false};
+            std::vector<std::thread> pool;
+            for (int th = 0; th < nthreads; ++th)
+                pool.emplace_back([&, th] {
+                    try {
+                        for (int64_t vt = nt * th / nthreads; vt < nt * (th + 1) / nthreads; ++vt) classify(vt);
+                    } catch (...) {
+                        failed = true;
+                    }
+                });
+            for (std::thread &t : pool) t.join();
+            if (failed) throw std::bad_alloc();
+        }
+    }
+    for (int64_t vt = 0; vt < nt; ++vt) {
+        const TileResult &tr = res[(size_t)vt];
+        const int64_t rows = s.tile_first_ptr[vt + 1] - s.tile_first_ptr[vt];
+        wf1.insert(wf1.end(), tr.wf1.begin(), tr.wf1.end());
+        s.tile_second_ptr[vt] = (int32_t)s.second_rows.size();
         s.second_rows.insert(s.second_rows.end(), blocks[(size_t)vt].rows.begin(),
                              blocks[(size_t)vt].rows.end());
         // Eq. 2 (diagnostic): (nz + uc + t + |J|) * cCol + idx, counted in elements; for a dense B
         // the tile's rows x bCol block of B is added to nz, a sparse B is unknown here.
-        const double nz = (double)tile_nnz + (in.b_is_sparse ? 0.0 : (double)rows * in.bcol);
-        const double idx = (double)(rows + 1) + (double)tile_nnz;
-        s.eq2_cost_max = std::max(s.eq2_cost_max, (nz + uc + rows + nj) * (double)in.ccol + idx);
-        s.fused_nnz += tile_nnz;
+        const double nz = (double)tr.tile_nnz + (in.b_is_sparse ? 0.0 : (double)rows * in.bcol);
+        const double idx = (double)(rows + 1) + (double)tr.tile_nnz;
+        s.eq2_cost_max = std::max(s.eq2_cost_max, (nz + tr.uc + rows + tr.nj) * (double)in.ccol + idx);
+        s.fused_nnz += tr.tile_nnz;
     }
     s.tile_second_ptr[nt] = (int32_t)s.second_rows.size();
     s.n_fused_rows = (int64_t)s.second_rows.size();
@@ -490,6 +538,11 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
     s.tile_desc.resize((size_t)nt);
     s.first_stride = (int32_t)round_up(std::max<int64_t>(s.max_tile_rows, 1), 16);
     s.tile_first.assign((size_t)nt * s.first_stride, 0);
+    {
+        size_t total = 64;
+        for (const TileBlock &tb : blocks) total += tb.bytes.size();
+        s.tile_meta.reserve(total);
+    }
     for (int64_t vt = 0; vt < nt; ++vt) {
         const int64_t f0 = s.tile_first_ptr[vt], f1 = s.tile_first_ptr[vt + 1];
         TileBlock &tb = blocks[(size_t)vt];
@@ -520,27 +573,23 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
         s.second_block_in_lds = need <= s.fast_mem_bytes;
     }
 
-    // ---- balance: units of the second wavefront, and of the unfused baseline ------------
-    const int vv = in.ccol % v == 0 ? v : 1;
-    // a unit is one workgroup: short lists are cut into smaller units (down to one row per lane
-    // group) so that they still spread over the machine
-    const int groups = kSpmmThreads / lane_group((int)in.ccol, vv);
-    auto unit_rows_for = [&](int64_t count) {
-        const int64_t want = (count + 1023) / 1024;
-        return (int)std::min<int64_t>(kUnitRows, std::max<int64_t>(groups, want));
-    };
-    PackRules wf1_rules{unit_rows_for((int64_t)wf1.size()), kUnitSlots, groups};
+    // ---- balance: units of the second wavefront --------------------------------------------
+    const PackRules wf1_rules = pack_rules(in, (int64_t)wf1.size());
     auto ident = [](int32_t c) { return c; };
     pack_rows(in.rowptr, in.colidx, vals, es, wf1, wf1_rules, true, ident, s.wf1.idx32, s.wf1);
     s.wf1_rows = s.wf1.rows;
     s.wf1_unit_ptr.clear();
     for (const UnitDesc &u : s.wf1.units) s.wf1_unit_ptr.push_back(u.row_begin);
     s.wf1_unit_ptr.push_back((int32_t)s.wf1_rows.size());
-    std::vector<int32_t> all((size_t)n);
-    std::iota(all.begin(), all.end(), 0);
-    const PackRules all_rules{unit_rows_for(n), kUnitSlots, groups};
-    pack_rows(in.rowptr, in.colidx, vals, es, all, all_rules, true, ident, s.all.idx32, s.all);
     return TF_OK;
+}
+
+void build_baseline_pack(const InspectorInput &in, Schedule &s) {
+    std::vector<int32_t> all((size_t)in.n);
+    std::iota(all.begin(), all.end(), 0);
+    auto ident = [](int32_t c) { return c; };
+    pack_rows(in.rowptr, in.colidx, static_cast<const unsigned char *>(in.vals), elem_size(in.dtype),
+              all, pack_rules(in, in.n), true, ident, s.all.idx32, s.all);
 }
 
 }  // namespace tf

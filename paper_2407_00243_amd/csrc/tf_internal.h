@@ -210,6 +210,9 @@ struct InspectorInput {
 
 // Builds the schedule; returns TF_OK or an error with a message in `err`.
 tf_status build_schedule(const InspectorInput &in, Schedule &out, std::string &err);
+// The packed copy of all rows of A that the unfused baseline's second operation runs on
+// (Schedule::all).  Not part of the fused schedule and not counted in its time.
+void build_baseline_pack(const InspectorInput &in, Schedule &s);
 
 
 // ---------------------------------------------------------------- device launch interface

@@ -164,6 +164,23 @@ def test_graph_grown_tiles_fill_the_workgroups_evenly(width, dtype):
     check_schedule_general(A, s)
 
 
+def test_large_matrix_schedule_built_by_several_threads():
+    """A matrix of a quarter of a million rows is classified and packed by several host threads;
+    the schedule must be valid, must not depend on how the tiles were dealt out (two builds
+    agree) and, for consecutive tiles, must equal the oracle's Algorithm 1."""
+    A = ti.laplacian_2d(512, np.float32)
+    s1 = plan_schedule(A, 64, 64, False, ct_size=65536, p=1, flags=tf.TF_FLAG_REORDER)
+    s2 = plan_schedule(A, 64, 64, False, ct_size=65536, p=1, flags=tf.TF_FLAG_REORDER)
+    for key in ("first_rows", "second_rows", "tile_second_ptr", "wf1_rows", "wf1_unit_ptr", "spill"):
+        assert np.array_equal(s1[key], s2[key]), key
+    assert s1["fused_nnz"] == s2["fused_nnz"] and s1["eq2_cost_max"] == s2["eq2_cost_max"]
+    check_schedule_general(A, s1)
+    B = ti.banded(300000, 3, np.float64, 3)
+    s = plan_schedule(B, 16, 16, False, ct_size=512, p=1)
+    assert s["n_tiles"] >= 64
+    check_schedule(B, s, 512, 1)
+
+
 def test_schedule_view_reports_the_second_phase_blocks():
     prob = ti.config(2, scale_down=128)
     s = plan_schedule(prob.A, 64, 64, False, ct_size=256, p=1)
