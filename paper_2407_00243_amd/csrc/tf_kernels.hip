@@ -595,13 +595,13 @@ __device__ __forceinline__ SecondBlock<T> second_block(const unsigned char *sb, 
 // loop, so the entries (index pair, value pair) of the next step are read while the operands of
 // the current step are on their way.
 // (The spilled rows of the tile have been stored by the waves that produced them.)
-template <typename T, int VV, int R>
+template <typename T, int VV, int R, int W = 1>
 __device__ __forceinline__ void fused_tail(const FusedLaunch &a, const TileDesc &d,
                                            const unsigned char *sb,
                                            const T *tileD1, int ldl, int c0, int gl, int grp,
                                            int ngrp) {
     const int ccol = a.ccol;
-    const uint32_t lane_off = (uint32_t)(VV * gl);
+    const uint32_t lane_off = (uint32_t)(W * VV * gl);      // W packs of VV columns per lane
     const SecondBlock<T> b = second_block<T>(sb, d);
     T *__restrict__ D = static_cast<T *>(a.D);
     typedef Pack<T, 2> ValPair;
@@ -656,30 +656,40 @@ __device__ __forceinline__ void fused_tail(const FusedLaunch &a, const TileDesc 
             int32_t rid[R];
 #pragma unroll
             for (int r = 0; r < R; ++r) rid[r] = b.rows2[un.row_begin + row_at(kb, r)];
-            T acc[R][VV];
+            T acc[R][W][VV];
 #pragma unroll
             for (int r = 0; r < R; ++r)
 #pragma unroll
-                for (int i = 0; i < VV; ++i) acc[r][i] = T(0);
+                for (int wq = 0; wq < W; ++wq)
+#pragma unroll
+                    for (int i = 0; i < VV; ++i) acc[r][wq][i] = T(0);
             auto step = [&](auto two_c, const RowEntries (&next_rb)[R], int nsp, bool more) {
                 constexpr bool TWO = decltype(two_c)::value;
                 ValPair v[R];
-                T x[R][2][VV];
+                T x[R][2][W][VV];
 #pragma unroll
                 for (int r = 0; r < R; ++r) {
                     v[r] = vn[r];
-                    load_pack<T, VV>(x[r][0], reinterpret_cast<const T *>(tile_lane + (cn[r][0] << 4)));
-                    if (TWO)
-                        load_pack<T, VV>(x[r][1], reinterpret_cast<const T *>(tile_lane + (cn[r][1] << 4)));
+#pragma unroll
+                    for (int wq = 0; wq < W; ++wq) {
+                        load_pack<T, VV>(x[r][0][wq],
+                                         reinterpret_cast<const T *>(tile_lane + (cn[r][0] << 4)) + wq * VV);
+                        if (TWO)
+                            load_pack<T, VV>(x[r][1][wq],
+                                             reinterpret_cast<const T *>(tile_lane + (cn[r][1] << 4)) + wq * VV);
+                    }
                 }
                 if (more) read_entries(next_rb, nsp);
 #pragma unroll
                 for (int r = 0; r < R; ++r) {
 #pragma unroll
-                    for (int i = 0; i < VV; ++i) acc[r][i] += v[r].x[0] * x[r][0][i];
-                    if (TWO) {
+                    for (int wq = 0; wq < W; ++wq) {
 #pragma unroll
-                        for (int i = 0; i < VV; ++i) acc[r][i] += v[r].x[1] * x[r][1][i];
+                        for (int i = 0; i < VV; ++i) acc[r][wq][i] += v[r].x[0] * x[r][0][wq][i];
+                        if (TWO) {
+#pragma unroll
+                            for (int i = 0; i < VV; ++i) acc[r][wq][i] += v[r].x[1] * x[r][1][wq][i];
+                        }
                     }
                 }
             };
@@ -697,8 +707,11 @@ __device__ __forceinline__ void fused_tail(const FusedLaunch &a, const TileDesc 
             }
 #pragma unroll
             for (int r = 0; r < R; ++r)
-                if (grp + (kb * R + r) * ngrp < un.n_rows)
-                    store_pack<T, VV>(D + (int64_t)rid[r] * ccol + c0 + lane_off, acc[r]);
+                if (grp + (kb * R + r) * ngrp < un.n_rows) {
+#pragma unroll
+                    for (int wq = 0; wq < W; ++wq)
+                        store_pack<T, VV>(D + (int64_t)rid[r] * ccol + c0 + lane_off + wq * VV, acc[r][wq]);
+                }
         }
     }
 }
@@ -900,8 +913,18 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
         }
         // (three rows per lane group at a time: with four the kernel no longer fits the 256
         // registers of a wave at this occupancy and spills)
-        if (VV * gl < w)
+        // When the slice is a whole number of double packs each lane takes two packs of a row
+        // (half as many lanes per row, twice as many rows per wave): the index and address work of
+        // a step is shared by twice as many columns.
+        if (FAST && G >= 2 && w % (2 * VV) == 0) {
+            const int G2 = G / 2;
+            const int gl2 = (int)threadIdx.x % G2;
+            if (2 * VV * gl2 < w)
+                fused_tail<T, VV, 2, 2>(a, d, SLDS ? sm.second : blk, tileD1, ldl, c0, gl2,
+                                        (int)threadIdx.x / G2, (int)blockDim.x / G2);
+        } else if (VV * gl < w) {
             fused_tail<T, VV, 3>(a, d, SLDS ? sm.second : blk, tileD1, ldl, c0, gl, grp, ngrp);
+        }
         if (!has_next) break;
         __syncthreads();
         d = nd;
