@@ -1170,8 +1170,17 @@ __global__ __launch_bounds__(kFusedSparseThreads) void k_fused_spmm_spmm(const F
                 }
             }
         }
-        if (VV * gl < w)
+        // (two packs of one row per lane when the slice allows, else one pack of two rows: the same
+        // registers, half the index and address work per column)
+        if (FAST && G >= 2 && w % (2 * VV) == 0) {
+            const int G2 = G / 2;
+            const int gl2 = (int)threadIdx.x % G2;
+            if (2 * VV * gl2 < w)
+                fused_tail<T, VV, 1, 2>(a, d, SLDS ? sm.second : blk, tileD1, ldl, c0, gl2,
+                                        (int)threadIdx.x / G2, (int)blockDim.x / G2);
+        } else if (VV * gl < w) {
             fused_tail<T, VV, 2>(a, d, SLDS ? sm.second : blk, tileD1, ldl, c0, gl, grp, ngrp);
+        }
         if (!has_next) break;
         {
             int32_t *ext = sm.bext + (par ^ 1) * sm.bext_stride;
