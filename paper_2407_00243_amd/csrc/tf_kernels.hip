@@ -73,40 +73,6 @@ __device__ __forceinline__ int pow2_at_least(int x) {
     return g;
 }
 
-// acc[0..N) += sum_{k in [kbeg, kend)} val[k] * X[idx[k] * ldx + 0..N), k ascending.
-// X already includes the lane's column offset.  Four independent gathers are kept in flight.
-template <typename T, int N, typename IdxT>
-__device__ __forceinline__ void row_dot(T (&acc)[N], const IdxT *__restrict__ idx,
-                                        const T *__restrict__ val, int kbeg, int kend,
-                                        const T *X, int64_t ldx) {
-    int k = kbeg;
-    for (; k + 4 <= kend; k += 4) {
-        const int64_t c0 = idx[k], c1 = idx[k + 1], c2 = idx[k + 2], c3 = idx[k + 3];
-        const T v0 = val[k], v1 = val[k + 1], v2 = val[k + 2], v3 = val[k + 3];
-        T x0[N], x1[N], x2[N], x3[N];
-        load_pack<T, N>(x0, X + c0 * ldx);
-        load_pack<T, N>(x1, X + c1 * ldx);
-        load_pack<T, N>(x2, X + c2 * ldx);
-        load_pack<T, N>(x3, X + c3 * ldx);
-#pragma unroll
-        for (int i = 0; i < N; ++i) acc[i] += v0 * x0[i];
-#pragma unroll
-        for (int i = 0; i < N; ++i) acc[i] += v1 * x1[i];
-#pragma unroll
-        for (int i = 0; i < N; ++i) acc[i] += v2 * x2[i];
-#pragma unroll
-        for (int i = 0; i < N; ++i) acc[i] += v3 * x3[i];
-    }
-    for (; k < kend; ++k) {
-        const int64_t c = idx[k];
-        const T v = val[k];
-        T x[N];
-        load_pack<T, N>(x, X + c * ldx);
-#pragma unroll
-        for (int i = 0; i < N; ++i) acc[i] += v * x[i];
-    }
-}
-
 // Consecutive workgroup ids are dealt round-robin to the eight XCDs, each with its own L2.
 // Work items that touch neighbouring rows (adjacent tiles, the column slices of one tile, adjacent
 // units of the second wavefront) should share an L2, so item ids are handed out in eight
@@ -114,17 +80,6 @@ __device__ __forceinline__ void row_dot(T (&acc)[N], const IdxT *__restrict__ id
 __device__ __forceinline__ int64_t xcd_contiguous(int64_t bid, int64_t total) {
     const int64_t per = (total + 7) >> 3;
     return (bid & 7) * per + (bid >> 3);
-}
-
-// (tile, slice) of a fused workgroup: the slices of a tile run back to back on one XCD.
-__device__ __forceinline__ bool tile_and_slice(int bid, int n_tiles, int n_slices, int &tile,
-                                               int &slice) {
-    const int per = (n_tiles + 7) >> 3;
-    const int q = bid >> 3;
-    slice = q % n_slices;
-    const int local = q / n_slices;
-    tile = (bid & 7) * per + local;
-    return local < per && tile < n_tiles;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -291,45 +246,6 @@ __device__ __forceinline__ void rows_dot(T (&acc)[R][N], const IdxT *__restrict_
 #pragma unroll
                 for (int i = 0; i < N; ++i) acc[r][i] += vv * (ok[r][e] ? x[r][e][i] : T(0));
             }
-        }
-    }
-}
-
-// One lane group walks the list positions first, first + stride, ... below count, R at a time.
-// row_of(pos) names the CSR row at a list position; out(pos, row, acc) consumes its result.
-template <typename T, int N, typename IdxT, int R, int E, typename RowFn, typename OutFn>
-__device__ __forceinline__ void gather_rows(int first, int count, int stride,
-                                            const int32_t *__restrict__ rowptr,
-                                            const IdxT *__restrict__ idx,
-                                            const T *__restrict__ val, const T *X, int64_t ldx,
-                                            bool active, RowFn row_of, OutFn out) {
-    for (int base = first; base < count; base += stride * R) {
-        int64_t row[R];
-        int kb[R], ke[R];
-        bool ok[R];
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const int pos = base + r * stride;
-            ok[r] = pos < count;
-            row[r] = (int64_t)row_of(ok[r] ? pos : base);      // `base` is always in range
-        }
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            kb[r] = rowptr[row[r]];
-            ke[r] = rowptr[row[r] + 1];
-        }
-#pragma unroll
-        for (int r = 0; r < R; ++r) ke[r] = ok[r] ? ke[r] : kb[r];
-        if (active) {
-            T acc[R][N];
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-#pragma unroll
-                for (int i = 0; i < N; ++i) acc[r][i] = T(0);
-            rows_dot<T, N, IdxT, R, E>(acc, idx, val, kb, ke, X, ldx);
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-                if (ok[r]) out(base + r * stride, row[r], acc[r]);
         }
     }
 }
