@@ -288,6 +288,5 @@ int launch_fused_spmm_spmm(const FusedLaunch &a, void *stream);
 int launch_packed_spmm(const PackedSpmmLaunch &a, void *stream);
 int launch_csr_spmm(const CsrSpmmLaunch &a, void *stream);
 int launch_gemm(const GemmLaunch &a, void *stream);
-int prepare_kernels(int64_t max_dynamic_lds);                 // raises the dynamic-LDS limit of the kernels
 
 }  // namespace tf

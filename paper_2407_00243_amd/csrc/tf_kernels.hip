@@ -17,6 +17,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <mutex>
 #include <type_traits>
 
 #include "tf_internal.h"
@@ -1438,20 +1439,36 @@ int64_t fused_grid(const FusedLaunch &a, int wg_per_cu) {
     return 8 * wg_per_xcd;
 }
 
+// Per kernel instantiation: the dynamic-LDS limit raised so far (it only ever grows: lowering it
+// would break a launch of another plan) and the launch shape last worked out.  Calls may come
+// from several host threads, so both sit behind a mutex.
+struct KernelSetup {
+    std::mutex m;
+    int64_t raised = -1, occ_lds = -1;
+    FusedShape shape;
+};
+template <typename K>
+int fused_setup(KernelSetup &ks, K kernel, int64_t lds_bytes, int max_threads, FusedShape &shape) {
+    std::lock_guard<std::mutex> lock(ks.m);
+    if (lds_bytes > ks.raised) {
+        const int e = raise_lds_limit(kernel, lds_bytes);
+        if (e) return e;
+        ks.raised = lds_bytes;
+    }
+    if (lds_bytes != ks.occ_lds) {
+        ks.shape = fused_shape(kernel, lds_bytes, max_threads);
+        ks.occ_lds = lds_bytes;
+    }
+    shape = ks.shape;
+    return 0;
+}
+
 template <typename T, int NB, int KS, bool FAST, bool SLDS>
 int run_fused_gemm2(const FusedLaunch &a, hipStream_t st) {
-    static int64_t raised = -1;
-    if (a.lds_bytes > raised) {
-        int e = raise_lds_limit(k_fused_gemm_spmm<T, NB, KS, FAST, SLDS>, a.lds_bytes);
-        if (e) return e;
-        raised = a.lds_bytes;
-    }
-    static int64_t occ_lds = -1;
-    static FusedShape shape;
-    if (a.lds_bytes != occ_lds) {
-        shape = fused_shape(k_fused_gemm_spmm<T, NB, KS, FAST, SLDS>, a.lds_bytes, kFusedThreads);
-        occ_lds = a.lds_bytes;
-    }
+    static KernelSetup ks;
+    FusedShape shape;
+    if (int e = fused_setup(ks, k_fused_gemm_spmm<T, NB, KS, FAST, SLDS>, a.lds_bytes, kFusedThreads, shape))
+        return e;
     k_fused_gemm_spmm<T, NB, KS, FAST, SLDS>
         <<<dim3((unsigned)fused_grid(a, shape.wg_per_cu)), dim3(shape.threads), a.lds_bytes, st>>>(a);
     return (int)hipGetLastError();
@@ -1463,18 +1480,10 @@ int run_fused_gemm(const FusedLaunch &a, hipStream_t st) {
 }
 
 template <typename T, bool FAST, bool SLDS> int run_fused_spmm2(const FusedLaunch &a, hipStream_t st) {
-    static int64_t raised = -1;
-    if (a.lds_bytes > raised) {
-        int e = raise_lds_limit(k_fused_spmm_spmm<T, FAST, SLDS>, a.lds_bytes);
-        if (e) return e;
-        raised = a.lds_bytes;
-    }
-    static int64_t occ_lds = -1;
-    static FusedShape shape;
-    if (a.lds_bytes != occ_lds) {
-        shape = fused_shape(k_fused_spmm_spmm<T, FAST, SLDS>, a.lds_bytes, kFusedSparseThreads);
-        occ_lds = a.lds_bytes;
-    }
+    static KernelSetup ks;
+    FusedShape shape;
+    if (int e = fused_setup(ks, k_fused_spmm_spmm<T, FAST, SLDS>, a.lds_bytes, kFusedSparseThreads, shape))
+        return e;
     k_fused_spmm_spmm<T, FAST, SLDS>
         <<<dim3((unsigned)fused_grid(a, shape.wg_per_cu)), dim3(shape.threads), a.lds_bytes, st>>>(a);
     return (int)hipGetLastError();
@@ -1485,11 +1494,15 @@ template <typename T, bool FAST> int run_fused_spmm(const FusedLaunch &a, hipStr
 
 template <typename T, int NB, int KS, bool FAST> int run_gemm(const GemmLaunch &a, hipStream_t st) {
     const int64_t lds = lds_fixed_bytes(a.dtype, 0, a.bcol, a.cs);
+    static std::mutex m;
     static int64_t raised = -1;
-    if (lds > raised) {
-        int e = raise_lds_limit(k_gemm<T, NB, KS, FAST>, lds);
-        if (e) return e;
-        raised = lds;
+    {
+        std::lock_guard<std::mutex> lock(m);
+        if (lds > raised) {
+            const int e = raise_lds_limit(k_gemm<T, NB, KS, FAST>, lds);
+            if (e) return e;
+            raised = lds;
+        }
     }
     const int nwaves = kFusedThreads / 64;
     const int64_t nblk = (a.n + 15) / 16;
