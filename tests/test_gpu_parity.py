@@ -368,6 +368,52 @@ def test_csr_b_tiles_of_more_rows_than_threads():
             c.close()
 
 
+@pytest.mark.parametrize("kind", ["gemm_spmm", "spmm_spmm"])
+def test_wavefronts_one_by_one_and_the_workspace(kind):
+    """tf_run_wavefront(0) writes exactly the fused rows of D and leaves the spilled D1 rows in
+    the plan's workspace; tf_run_wavefront(1) then writes exactly the remaining rows.  Integer
+    entries: everything is compared bit for bit with the oracle's D1 = B C and D = A D1."""
+    import ctypes
+    import torch
+    import paper_2407_00243_amd as tf
+    dtype = np.float64
+    n, bcol, ccol = 600, 24, 40
+    A = ti.random_local_csr(n, 6, 5, 0.15, dtype, 81, int_values=True)
+    if kind == "gemm_spmm":
+        B = ti.dense_small_int(n, bcol, dtype, 82)
+        D1_ref = oracle.gemm(B, ti.dense_small_int(bcol, ccol, dtype, 83))
+    else:
+        B = ti.random_pattern_csr(n, bcol, 0.2, dtype, 82, int_values=True)
+        D1_ref = oracle.spmm(B.rowptr, B.colidx, B.vals, ti.dense_small_int(bcol, ccol, dtype, 83))
+    C = ti.dense_small_int(bcol, ccol, dtype, 83)
+    prob = ti.Problem("wavefronts", kind, np.dtype(dtype), A, B, C)
+    D_ref, _ = oracle.chain(A, B, C)
+    c = _case(prob, ct_size=100, p=1)
+    try:
+        s = c.plan.schedule()
+        fused = np.zeros(n, bool)
+        fused[s["second_rows"]] = True
+        assert 0 < fused.sum() < n and s["n_spill_rows"] > 0
+        stream = torch.cuda.current_stream().cuda_stream
+        D = torch.full((n, ccol), float("nan"), dtype=torch.float64, device="cuda")
+        c.plan.run_wavefront(0, c.B, c.C, D, stream)
+        torch.cuda.synchronize()
+        got = D.cpu().numpy()
+        assert np.array_equal(got[fused], D_ref[fused])
+        assert np.all(np.isnan(got[~fused]))
+        ws = np.empty((n, ccol), dtype=np.float64)
+        hip = ctypes.CDLL("libamdhip64.so")
+        hip.hipMemcpy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int]
+        assert hip.hipMemcpy(ws.ctypes.data, c.plan.workspace(), ws.nbytes, 2) == 0   # device to host
+        spill = s["spill"].astype(bool)
+        assert np.array_equal(ws[spill], D1_ref[spill])
+        c.plan.run_wavefront(1, None, c.C, D, stream)
+        torch.cuda.synchronize()
+        assert np.array_equal(D.cpu().numpy(), D_ref)
+    finally:
+        c.close()
+
+
 # ---------------------------------------------------------------- invariants on the GPU
 
 def test_identity_a_returns_bc():
