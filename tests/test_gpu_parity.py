@@ -488,3 +488,68 @@ def test_execution_error_paths():
         with pytest.raises(tf.TfError) as e:
             tf.tf_spmm_spmm(pl.handle, dev_csr(A32), dev(prob.C), D)
         assert e.value.status_name == "TF_EMISMATCH"
+
+
+# ------------------------------------------------------------------ seeded random shapes
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_shapes_bit_exact(seed):
+    """Shapes, precisions, kinds of B, tile sizes, column slices, fast-memory sizes and plan flags
+    drawn from a seeded generator (the seed names the case): small integer entries, so the fused
+    path and the unfused path must both equal the oracle bit for bit."""
+    import paper_2407_00243_amd as tf
+    rng = np.random.default_rng(1000 + seed)
+    dtype = [np.float32, np.float64][int(rng.integers(2))]
+    kind = ["gemm_spmm", "spmm_spmm"][int(rng.integers(2))]
+    n = int(rng.choice([1, 2, 15, 16, 17, 63, 255, 256, 257, 700, 1500, 3000]))
+    bcol = int(rng.choice([1, 3, 8, 16, 20, 32, 33, 64, 100, 128, 256, 300]))
+    ccol = int(rng.choice([1, 2, 5, 8, 16, 24, 32, 40, 64, 96, 128, 130, 200]))
+    width = int(rng.choice([1, 3, 8, 40]))
+    A = ti.random_local_csr(n, min(width, n), int(rng.integers(1, 9)), float(rng.choice([0.0, 0.1, 0.5])),
+                            dtype, 2000 + seed, int_values=True,
+                            empty_row_prob=float(rng.choice([0.0, 0.1, 0.6])))
+    if kind == "gemm_spmm":
+        B = ti.dense_small_int(n, bcol, dtype, 3000 + seed)
+    else:
+        B = ti.random_pattern_csr(n, bcol, min(1.0, float(rng.choice([1.0, 4.0, 20.0])) / bcol), dtype,
+                                  3000 + seed, int_values=True, duplicates=bool(rng.integers(2)),
+                                  sort_cols=bool(rng.integers(2)),
+                                  empty_row_prob=float(rng.choice([0.0, 0.3])))
+    flags = int(rng.choice([0, tf.TF_FLAG_REORDER, tf.TF_FLAG_SKIP_UNREAD,
+                            tf.TF_FLAG_REORDER | tf.TF_FLAG_SKIP_UNREAD, tf.TF_FLAG_NO_SPLIT]))
+    transposed = kind == "gemm_spmm" and bool(rng.integers(2))
+    if transposed:
+        flags |= tf.TF_FLAG_C_TRANSPOSED
+        C = ti.dense_small_int(ccol, bcol, dtype, 4000 + seed)
+        D_ref, _ = oracle.chain_ct(A, B, C)
+    else:
+        C = ti.dense_small_int(bcol, ccol, dtype, 4000 + seed)
+        D_ref, _ = oracle.chain(A, B, C)
+    prob = ti.Problem(f"random {seed}", kind, np.dtype(dtype), A, B, C)
+    params = dict(ct_size=int(rng.choice([1, 16, 50, 64, 200, 1024, 65536])), p=1, flags=flags)
+    if flags & tf.TF_FLAG_NO_SPLIT:
+        params["ct_size"] = min(params["ct_size"], 16)     # tiles that fit without being split
+    v = 4 if dtype == np.float32 else 2
+    slices = [0] + [c for c in (16, 32, 48, 64) if c < ccol and ccol % v == 0]
+    params["col_slice"] = int(rng.choice(slices))
+    with tf.Plan(A, bcol, ccol, kind == "spmm_spmm", flags=tf.TF_FLAG_SCHEDULE_ONLY,
+                 col_slice=params["col_slice"]) as pl:
+        s0 = pl.schedule()
+    if rng.integers(2) and not flags & tf.TF_FLAG_NO_SPLIT:
+        rows = int(rng.choice([16, 48, 200]))              # a fast memory of so many rows
+        params["fast_mem_bytes"] = int(s0["lds_fixed_bytes"] + rows * s0["lds_bytes_per_row"])
+    print(f"seed {seed}: {kind} {np.dtype(dtype).name} n={n} bCol={bcol} cCol={ccol} "
+          f"transposed={transposed} {params}", flush=True)
+    c = _case(prob, **params)
+    try:
+        s = c.plan.schedule()
+        if not flags & (tf.TF_FLAG_SKIP_UNREAD | tf.TF_FLAG_NO_SPLIT):
+            if flags & tf.TF_FLAG_REORDER:
+                check_schedule_general(A, s)
+            else:
+                check_schedule(A, s, params["ct_size"], 1)
+        for fused in (True, False):
+            D = c.run(fused=fused)
+            assert np.array_equal(D.astype(np.float64), D_ref), (seed, fused)
+    finally:
+        c.close()
