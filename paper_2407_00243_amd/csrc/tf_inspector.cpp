@@ -120,25 +120,28 @@ void pack_rows(const int32_t *rowptr, const int32_t *colidx, const unsigned char
         }
         u.n_rows = (int32_t)take;
         u.slots = (int32_t)L;
-        for (int64_t q = pos; q < pos + take; ++q) {
-            const int32_t j = list[q];
-            const int64_t k0 = rowptr[j], ln = len(j);
-            for (int64_t s = 0; s < L; ++s) {
-                const int64_t k = k0 + (s < ln ? s : ln - 1);      // padding repeats the last entry
-                idx_out.push_back((typename IdxVec::value_type)local(colidx[k]));
-                const size_t at = out.vals.size();
-                out.vals.resize(at + es, 0);
-                if (s < ln) std::memcpy(&out.vals[at], vals + (size_t)k * es, es);
+        {
+            // every unit starts at a multiple of four entries (16-byte aligned pieces for the
+            // kernels' bulk copies, which may also read up to three entries past a unit's end)
+            const size_t at0 = idx_out.size();
+            const size_t n_ent = (size_t)(take * L);
+            const size_t padded = (at0 + n_ent + 3) / 4 * 4;
+            idx_out.resize(padded, 0);
+            out.vals.resize(padded * es, 0);
+            typename IdxVec::value_type *ip = idx_out.data() + at0;
+            unsigned char *vp = out.vals.data() + at0 * es;
+            for (int64_t q = pos; q < pos + take; ++q) {
+                const int32_t j = list[q];
+                const int64_t k0 = rowptr[j], ln = len(j);
+                for (int64_t s = 0; s < ln; ++s) *ip++ = (typename IdxVec::value_type)local(colidx[k0 + s]);
+                std::memcpy(vp, vals + (size_t)k0 * es, (size_t)ln * es);
+                // padding repeats the last entry's index with value 0 (units of empty rows have L = 0)
+                for (int64_t s = ln; s < L; ++s) *ip++ = (typename IdxVec::value_type)local(colidx[k0 + ln - 1]);
+                vp += (size_t)L * es;
             }
         }
         out.units.push_back(u);
         pos += take;
-        // every unit starts at a multiple of four entries (16-byte aligned pieces for the kernels'
-        // bulk copies, which may also read up to three entries past a unit's end)
-        while (idx_out.size() % 4) {
-            idx_out.push_back(0);
-            out.vals.resize(out.vals.size() + es, 0);
-        }
     }
     for (int i = 0; i < 4; ++i) {
         idx_out.push_back(0);
@@ -192,15 +195,22 @@ TileBlock pack_tile(const int32_t *rowptr, const int32_t *colidx, const unsigned
         u.row_begin = (int32_t)pos;
         u.n_rows = (int32_t)take;
         u.slots = (int32_t)(stride | (L << 16));
-        for (int64_t q = pos; q < pos + take; ++q) {
-            const int32_t j = list[q];
-            const int64_t k0 = rowptr[j], ln = len(j);
-            for (int64_t sl = 0; sl < stride; ++sl) {
-                const int64_t k = k0 + (sl < ln ? sl : ln - 1);
-                idx.push_back((uint16_t)local(colidx[k]));
-                const size_t at = val.size();
-                val.resize(at + es, 0);
-                if (sl < ln) std::memcpy(&val[at], vals + (size_t)k * es, es);
+        {
+            const size_t at0 = idx.size();
+            idx.resize(at0 + (size_t)(take * stride), 0);
+            val.resize(idx.size() * es, 0);
+            uint16_t *ip = idx.data() + at0;
+            unsigned char *vp = val.data() + at0 * es;
+            for (int64_t q = pos; q < pos + take; ++q) {
+                const int32_t j = list[q];
+                const int64_t k0 = rowptr[j], ln = len(j);
+                for (int64_t sl = 0; sl < ln; ++sl) *ip++ = (uint16_t)local(colidx[k0 + sl]);
+                std::memcpy(vp, vals + (size_t)k0 * es, (size_t)ln * es);
+                if (ln > 0)
+                    for (int64_t sl = ln; sl < stride; ++sl) *ip++ = (uint16_t)local(colidx[k0 + ln - 1]);
+                else
+                    ip += stride;
+                vp += (size_t)stride * es;
             }
         }
         units.push_back(u);
@@ -228,6 +238,34 @@ TileBlock pack_tile(const int32_t *rowptr, const int32_t *colidx, const unsigned
 }
 
 }  // namespace
+
+// Host threads for per-tile work: one for small matrices, else up to 16, at least 16 tiles each.
+static int host_threads(const InspectorInput &in, int64_t n_tiles) {
+    if (in.nnz < ((int64_t)1 << 18) || n_tiles < 64) return 1;
+    const unsigned hw = std::max(1u, std::thread::hardware_concurrency());
+    return (int)std::min<int64_t>(std::min<unsigned>(hw, 16u), n_tiles / 16);
+}
+
+// Runs fn(v) for v in [0, count) on `nthreads` host threads, each with a contiguous range (fn
+// writes to places of its own v only, so the outcome does not depend on the thread count).
+template <typename Fn> void for_each_tile(int64_t count, int nthreads, Fn fn) {
+    if (nthreads <= 1) {
+        for (int64_t v = 0; v < count; ++v) fn(v);
+        return;
+    }
+    std::atomic<bool> failed{false};
+    std::vector<std::thread> pool;
+    for (int th = 0; th < nthreads; ++th)
+        pool.emplace_back([&, th] {
+            try {
+                for (int64_t v = count * th / nthreads; v < count * (th + 1) / nthreads; ++v) fn(v);
+            } catch (...) {
+                failed = true;
+            }
+        });
+    for (std::thread &t : pool) t.join();
+    if (failed) throw std::bad_alloc();
+}
 
 // Units of a packed row list of `count` rows: a unit is one workgroup; short lists are cut into
 // smaller units (down to one row per lane group) so that they still spread over the machine.
@@ -381,12 +419,14 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
                     }
                 }
             }
-            std::sort(queue.begin(), queue.end());
             std::copy(queue.begin(), queue.end(), s.first_rows.begin() + filled);
             filled += (int64_t)queue.size();
             s.tile_first_ptr.push_back((int32_t)filled);
         }
         s.n_coarse_tiles = (int64_t)s.tile_first_ptr.size() - 1;
+        for_each_tile(s.n_coarse_tiles, host_threads(in, s.n_coarse_tiles), [&](int64_t vt) {
+            std::sort(s.first_rows.begin() + s.tile_first_ptr[vt], s.first_rows.begin() + s.tile_first_ptr[vt + 1]);
+        });
     } else {
         // Algorithm 1: uniform tiles of t consecutive rows (step 1), halved until they fit (step 2)
         std::vector<Range> tiles;
@@ -490,28 +530,7 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
         blocks[(size_t)vt] = pack_tile(in.rowptr, in.colidx, vals, es, tile_rows,
                                        [&](int32_t c) { return local_of[c] * pitch16; });
     };
-    {
-        int nthreads = 1;
-        if (in.nnz >= (int64_t)1 << 18 && nt >= 64)
-            nthreads = (int)std::min<int64_t>(std::min<unsigned>(std::max(1u, std::thread::hardware_concurrency()), 16u),
-                                              nt / 16);
-        if (nthreads <= 1) {
-            for (int64_t vt = 0; vt < nt; ++vt) classify(vt);
-        } else {
-            std::atomic<bool> failed{false};
-            std::vector<std::thread> pool;
-            for (int th = 0; th < nthreads; ++th)
-                pool.emplace_back([&, th] {
-                    try {
-                        for (int64_t vt = nt * th / nthreads; vt < nt * (th + 1) / nthreads; ++vt) classify(vt);
-                    } catch (...) {
-                        failed = true;
-                    }
-                });
-            for (std::thread &t : pool) t.join();
-            if (failed) throw std::bad_alloc();
-        }
-    }
+    for_each_tile(nt, host_threads(in, nt), classify);
     for (int64_t vt = 0; vt < nt; ++vt) {
         const TileResult &tr = res[(size_t)vt];
         const int64_t rows = s.tile_first_ptr[vt + 1] - s.tile_first_ptr[vt];
@@ -539,15 +558,18 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
     s.first_stride = (int32_t)round_up(std::max<int64_t>(s.max_tile_rows, 1), 16);
     s.tile_first.assign((size_t)nt * s.first_stride, 0);
     {
-        size_t total = 64;
-        for (const TileBlock &tb : blocks) total += tb.bytes.size();
-        s.tile_meta.reserve(total);
+        int64_t total = 0;
+        for (int64_t vt = 0; vt < nt; ++vt) {
+            s.tile_desc[(size_t)vt].meta_off = total;
+            total += (int64_t)blocks[(size_t)vt].bytes.size();
+            s.second_block_cap = std::max<int64_t>(s.second_block_cap, (int64_t)blocks[(size_t)vt].bytes.size());
+        }
+        s.tile_meta.assign((size_t)total + 64, 0);        // the kernels may read one piece past an empty block
     }
-    for (int64_t vt = 0; vt < nt; ++vt) {
+    for_each_tile(nt, host_threads(in, nt), [&](int64_t vt) {
         const int64_t f0 = s.tile_first_ptr[vt], f1 = s.tile_first_ptr[vt + 1];
         TileBlock &tb = blocks[(size_t)vt];
         TileDesc &d = s.tile_desc[(size_t)vt];
-        d.meta_off = (int64_t)s.tile_meta.size();
         d.n_rows = (int32_t)(f1 - f0);
         d.n_units = tb.n_units;
         d.n_second = (int32_t)tb.rows.size();
@@ -560,11 +582,9 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
             first[q - f0] = (int32_t)((uint32_t)row | (s.spill[row] ? kSpillBit : 0u));
         }
         for (int64_t q = f1 - f0; q < s.first_stride; ++q) first[q] = s.first_rows[f1 - 1];
-        s.tile_meta.insert(s.tile_meta.end(), tb.bytes.begin(), tb.bytes.end());
-        s.second_block_cap = std::max<int64_t>(s.second_block_cap, (int64_t)tb.bytes.size());
+        if (!tb.bytes.empty()) std::memcpy(s.tile_meta.data() + d.meta_off, tb.bytes.data(), tb.bytes.size());
         TileBlock().bytes.swap(tb.bytes);
-    }
-    s.tile_meta.resize(s.tile_meta.size() + 64, 0);      // the kernels may read one piece past an empty block
+    });
     {
         // LDS actually needed with the second-phase blocks staged: everything but the estimate
         const int64_t rows_cap = round_up(s.max_tile_rows, s.lds_row_granule);
