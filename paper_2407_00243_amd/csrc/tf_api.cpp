@@ -303,8 +303,8 @@ tf_status tf_plan_create(const tf_csr *A, int64_t bCol, int64_t cCol, int32_t b_
             if (e == hipSuccess) e = r;
         };
         ok(up(p->tile_desc, p->s.tile_desc));
-        ok(up(p->tile_meta, p->s.tile_meta));
-        std::vector<unsigned char>().swap(p->s.tile_meta);
+        if (e == hipSuccess) e = p->tile_meta.upload(p->s.tile_meta.get(), p->s.tile_meta_bytes);
+        p->s.tile_meta.reset();
         ok(up(p->tile_first, p->s.tile_first));
         std::vector<int32_t>().swap(p->s.tile_first);
         ok(upload_pack(p->wf1, p->s.wf1));

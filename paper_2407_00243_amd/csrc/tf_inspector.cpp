@@ -89,6 +89,14 @@ void pack_rows(const int32_t *rowptr, const int32_t *colidx, const unsigned char
     }
     const int64_t list_base = (int64_t)out.rows.size();
     out.rows.insert(out.rows.end(), list.begin(), list.end());
+    {
+        // room for the entries plus a fifth for padding, so that the arrays rarely grow by copying
+        int64_t real = 0;
+        for (int32_t j : list) real += len(j);
+        const size_t want = idx_out.size() + (size_t)(real + real / 5 + 4 * count + 16);
+        idx_out.reserve(want);
+        out.vals.reserve(want * es);
+    }
     int64_t pos = 0;
     while (pos < count) {
         UnitDesc u{};
@@ -564,7 +572,9 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
             total += (int64_t)blocks[(size_t)vt].bytes.size();
             s.second_block_cap = std::max<int64_t>(s.second_block_cap, (int64_t)blocks[(size_t)vt].bytes.size());
         }
-        s.tile_meta.assign((size_t)total + 64, 0);        // the kernels may read one piece past an empty block
+        s.tile_meta_bytes = (size_t)total + 64;           // the kernels may read one piece past an empty block
+        s.tile_meta.reset(new unsigned char[s.tile_meta_bytes]);
+        std::memset(s.tile_meta.get() + total, 0, 64);
     }
     for_each_tile(nt, host_threads(in, nt), [&](int64_t vt) {
         const int64_t f0 = s.tile_first_ptr[vt], f1 = s.tile_first_ptr[vt + 1];
@@ -582,7 +592,7 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
             first[q - f0] = (int32_t)((uint32_t)row | (s.spill[row] ? kSpillBit : 0u));
         }
         for (int64_t q = f1 - f0; q < s.first_stride; ++q) first[q] = s.first_rows[f1 - 1];
-        if (!tb.bytes.empty()) std::memcpy(s.tile_meta.data() + d.meta_off, tb.bytes.data(), tb.bytes.size());
+        if (!tb.bytes.empty()) std::memcpy(s.tile_meta.get() + d.meta_off, tb.bytes.data(), tb.bytes.size());
         TileBlock().bytes.swap(tb.bytes);
     });
     {

@@ -1,6 +1,7 @@
 // Internal declarations shared by the inspector (host), the kernels (device) and the C ABI.
 #pragma once
 #include <cstdint>
+#include <memory>
 #include <string>
 #include <vector>
 
@@ -179,7 +180,10 @@ struct Schedule {
     std::vector<int32_t> wf1_unit_ptr, wf1_rows;
     std::vector<uint8_t> spill;
     std::vector<TileDesc> tile_desc;                      // one per tile, see TileDesc
-    std::vector<unsigned char> tile_meta;                 // the tiles' second-phase blocks, back to back
+    // the tiles' second-phase blocks, back to back (not zero-filled on allocation: the host threads
+    // that copy the blocks in are the first to touch its pages)
+    std::unique_ptr<unsigned char[]> tile_meta;
+    size_t tile_meta_bytes = 0;
     std::vector<int32_t> tile_first;                      // the tiles' row ids, first_stride ints per tile
     int32_t first_stride = 0;                             // largest tile, in rows, rounded up to 16
     int64_t second_block_cap = 0;                         // largest second-phase block, bytes
