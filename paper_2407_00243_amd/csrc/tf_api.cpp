@@ -85,21 +85,20 @@ tf_status check_csr_host(int64_t n_rows, int64_t n_cols, int64_t nnz, const int3
     return TF_OK;
 }
 
-template <typename V> hipError_t up(DevBuf &b, const std::vector<V> &v) {
+template <typename V, typename A> hipError_t up(DevBuf &b, const std::vector<V, A> &v) {
     return b.upload(v.data(), v.size() * sizeof(V));
 }
 
 hipError_t upload_pack(tf_plan::PackBufs &b, tf::RowPack &pk) {
     hipError_t e = up(b.units, pk.units);
     if (e == hipSuccess) e = up(b.rows, pk.rows);
-    if (e == hipSuccess) e = pk.idx16.empty() ? up(b.idx, pk.idx32) : up(b.idx, pk.idx16);
+    if (e == hipSuccess) e = up(b.idx, pk.idx32);
     if (e == hipSuccess) e = up(b.vals, pk.vals);
     b.n_units = (int64_t)pk.units.size();
     b.sorted = pk.sorted;
     // the packed entries live on the device from here on; the row lists stay for the schedule view
-    std::vector<int32_t>().swap(pk.idx32);
-    std::vector<uint16_t>().swap(pk.idx16);
-    std::vector<unsigned char>().swap(pk.vals);
+    tf::RawVec<int32_t>().swap(pk.idx32);
+    tf::RawVec<unsigned char>().swap(pk.vals);
     return e;
 }
 

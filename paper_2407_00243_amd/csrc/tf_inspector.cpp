@@ -58,50 +58,87 @@ int pow2_at_least(int64_t x) {
     return g;
 }
 
+// Host threads for per-tile or per-unit work: one for small matrices, else up to 16.
+int host_threads(int64_t nnz, int64_t n_items, int64_t min_items_per_thread) {
+    if (nnz < ((int64_t)1 << 18) || n_items < 4 * min_items_per_thread) return 1;
+    const unsigned hw = std::max(1u, std::thread::hardware_concurrency());
+    return (int)std::min<int64_t>(std::min<unsigned>(hw, 16u), n_items / min_items_per_thread);
+}
+
+// Runs fn(v) for v in [0, count) on `nthreads` host threads, each with a contiguous range (fn
+// writes to places of its own v only, so the outcome does not depend on the thread count).
+template <typename Fn> void for_each_item(int64_t count, int nthreads, Fn fn) {
+    if (nthreads <= 1) {
+        for (int64_t v = 0; v < count; ++v) fn(v);
+        return;
+    }
+    std::atomic<bool> failed{false};
+    std::vector<std::thread> pool;
+    for (int th = 0; th < nthreads; ++th)
+        pool.emplace_back([&, th] {
+            try {
+                for (int64_t v = count * th / nthreads; v < count * (th + 1) / nthreads; ++v) fn(v);
+            } catch (...) {
+                failed = true;
+            }
+        });
+    for (std::thread &t : pool) t.join();
+    if (failed) throw std::bad_alloc();
+}
+
 // Re-packs the rows `list` of the CSR matrix into units of uniform padded length and appends
 // them to `out` (see RowPack).  local(c) maps a column index to what the kernel should index
-// its operand with.
-template <typename IdxVec, typename LocalFn>
+// its operand with.  First the units are cut (row lengths only), then their entries are filled
+// in, unit by unit on the host threads: a unit's place in the arrays follows from the cuts.
+template <typename LocalFn>
 void pack_rows(const int32_t *rowptr, const int32_t *colidx, const unsigned char *vals, int es,
                std::vector<int32_t> list, const PackRules &rules, bool may_sort, LocalFn local,
-               IdxVec &idx_out, RowPack &out) {
+               RowPack &out) {
     auto len = [&](int32_t j) { return (int64_t)rowptr[j + 1] - rowptr[j]; };
     const int64_t count = (int64_t)list.size();
     // empty rows last, so that no unit mixes them with rows that need padding entries
     std::stable_partition(list.begin(), list.end(), [&](int32_t j) { return len(j) > 0; });
+    int64_t real = 0;
+    for (int32_t j : list) real += len(j);
     if (may_sort && count > 0) {
         // padded size in the given order; re-order by length when padding would cost over 15 %
-        int64_t real = 0, padded = 0;
+        int64_t padded = 0;
         for (int64_t p0 = 0; p0 < count; p0 += rules.max_rows) {
             const int64_t p1 = std::min(count, p0 + rules.max_rows);
             int64_t mx = 0;
-            for (int64_t q = p0; q < p1; ++q) {
-                mx = std::max(mx, len(list[q]));
-                real += len(list[q]);
-            }
+            for (int64_t q = p0; q < p1; ++q) mx = std::max(mx, len(list[q]));
             padded += mx * (p1 - p0);
         }
         if (padded > real + real * 15 / 100) {
-            std::stable_sort(list.begin(), list.end(),
-                             [&](int32_t a, int32_t b) { return len(a) > len(b); });
+            // longest first, rows of one length in their given order: by counting when the
+            // lengths are a small range, else by comparison
+            int64_t longest = 0;
+            for (int32_t j : list) longest = std::max(longest, len(j));
+            if (longest <= 4 * count + 1024) {
+                std::vector<int64_t> start((size_t)longest + 2, 0);
+                for (int32_t j : list) ++start[(size_t)(longest - len(j)) + 1];
+                for (size_t b = 1; b < start.size(); ++b) start[b] += start[b - 1];
+                std::vector<int32_t> sorted((size_t)count);
+                for (int32_t j : list) sorted[(size_t)start[(size_t)(longest - len(j))]++] = j;
+                list.swap(sorted);
+            } else {
+                std::stable_sort(list.begin(), list.end(),
+                                 [&](int32_t a, int32_t b) { return len(a) > len(b); });
+            }
             out.sorted = true;
         }
     }
     const int64_t list_base = (int64_t)out.rows.size();
     out.rows.insert(out.rows.end(), list.begin(), list.end());
-    {
-        // room for the entries plus a fifth for padding, so that the arrays rarely grow by copying
-        int64_t real = 0;
-        for (int32_t j : list) real += len(j);
-        const size_t want = idx_out.size() + (size_t)(real + real / 5 + 4 * count + 16);
-        idx_out.reserve(want);
-        out.vals.reserve(want * es);
-    }
+    const size_t first_unit = out.units.size();
+    // every unit starts at a multiple of four entries (16-byte aligned pieces for the kernels'
+    // bulk copies, which may also read up to three entries past a unit's end)
+    int64_t at = (int64_t)out.idx32.size();
     int64_t pos = 0;
     while (pos < count) {
         UnitDesc u{};
         u.row_begin = (int32_t)(list_base + pos);
-        u.entry_base = (int64_t)idx_out.size();
+        u.entry_base = at;
         const int64_t len0 = len(list[pos]);
         int64_t L = len0;
         int64_t take = 1;
@@ -128,33 +165,38 @@ void pack_rows(const int32_t *rowptr, const int32_t *colidx, const unsigned char
         }
         u.n_rows = (int32_t)take;
         u.slots = (int32_t)L;
-        {
-            // every unit starts at a multiple of four entries (16-byte aligned pieces for the
-            // kernels' bulk copies, which may also read up to three entries past a unit's end)
-            const size_t at0 = idx_out.size();
-            const size_t n_ent = (size_t)(take * L);
-            const size_t padded = (at0 + n_ent + 3) / 4 * 4;
-            idx_out.resize(padded, 0);
-            out.vals.resize(padded * es, 0);
-            typename IdxVec::value_type *ip = idx_out.data() + at0;
-            unsigned char *vp = out.vals.data() + at0 * es;
-            for (int64_t q = pos; q < pos + take; ++q) {
-                const int32_t j = list[q];
-                const int64_t k0 = rowptr[j], ln = len(j);
-                for (int64_t s = 0; s < ln; ++s) *ip++ = (typename IdxVec::value_type)local(colidx[k0 + s]);
-                std::memcpy(vp, vals + (size_t)k0 * es, (size_t)ln * es);
-                // padding repeats the last entry's index with value 0 (units of empty rows have L = 0)
-                for (int64_t s = ln; s < L; ++s) *ip++ = (typename IdxVec::value_type)local(colidx[k0 + ln - 1]);
-                vp += (size_t)L * es;
-            }
-        }
         out.units.push_back(u);
+        at = (at + take * L + 3) / 4 * 4;
         pos += take;
     }
-    for (int i = 0; i < 4; ++i) {
-        idx_out.push_back(0);
-        out.vals.resize(out.vals.size() + es, 0);
+    const int64_t end = at + 4;                       // four spare entries behind the last unit
+    out.idx32.resize((size_t)end);
+    out.vals.resize((size_t)end * es);
+    const int64_t n_new = (int64_t)(out.units.size() - first_unit);
+    if (n_new == 0) {
+        std::memset(out.idx32.data() + at, 0, 4 * 4);
+        std::memset(out.vals.data() + (size_t)at * es, 0, (size_t)4 * es);
     }
+    for_each_item(n_new, host_threads(real, n_new, 64), [&](int64_t k) {
+        const UnitDesc &u = out.units[first_unit + (size_t)k];
+        const int64_t next = k + 1 < n_new ? out.units[first_unit + (size_t)k + 1].entry_base : end;
+        const int64_t L = u.slots;
+        int32_t *ip = out.idx32.data() + u.entry_base;
+        unsigned char *vp = out.vals.data() + (size_t)u.entry_base * es;
+        for (int64_t q = 0; q < u.n_rows; ++q) {
+            const int32_t j = out.rows[(size_t)u.row_begin + (size_t)q];
+            const int64_t k0 = rowptr[j], ln = len(j);
+            for (int64_t sl = 0; sl < ln; ++sl) *ip++ = (int32_t)local(colidx[k0 + sl]);
+            std::memcpy(vp, vals + (size_t)k0 * es, (size_t)ln * es);
+            // padding repeats the last entry's index with value 0 (units of empty rows have L = 0)
+            for (int64_t sl = ln; sl < L; ++sl) *ip++ = (int32_t)local(colidx[k0 + ln - 1]);
+            std::memset(vp + (size_t)ln * es, 0, (size_t)(L - ln) * es);
+            vp += (size_t)L * es;
+        }
+        const int64_t filled = u.entry_base + (int64_t)u.n_rows * L;
+        std::memset(out.idx32.data() + filled, 0, (size_t)(next - filled) * 4);
+        std::memset(out.vals.data() + (size_t)filled * es, 0, (size_t)(next - filled) * es);
+    });
 }
 
 }  // namespace
@@ -246,34 +288,6 @@ TileBlock pack_tile(const int32_t *rowptr, const int32_t *colidx, const unsigned
 }
 
 }  // namespace
-
-// Host threads for per-tile work: one for small matrices, else up to 16, at least 16 tiles each.
-static int host_threads(const InspectorInput &in, int64_t n_tiles) {
-    if (in.nnz < ((int64_t)1 << 18) || n_tiles < 64) return 1;
-    const unsigned hw = std::max(1u, std::thread::hardware_concurrency());
-    return (int)std::min<int64_t>(std::min<unsigned>(hw, 16u), n_tiles / 16);
-}
-
-// Runs fn(v) for v in [0, count) on `nthreads` host threads, each with a contiguous range (fn
-// writes to places of its own v only, so the outcome does not depend on the thread count).
-template <typename Fn> void for_each_tile(int64_t count, int nthreads, Fn fn) {
-    if (nthreads <= 1) {
-        for (int64_t v = 0; v < count; ++v) fn(v);
-        return;
-    }
-    std::atomic<bool> failed{false};
-    std::vector<std::thread> pool;
-    for (int th = 0; th < nthreads; ++th)
-        pool.emplace_back([&, th] {
-            try {
-                for (int64_t v = count * th / nthreads; v < count * (th + 1) / nthreads; ++v) fn(v);
-            } catch (...) {
-                failed = true;
-            }
-        });
-    for (std::thread &t : pool) t.join();
-    if (failed) throw std::bad_alloc();
-}
 
 // Units of a packed row list of `count` rows: a unit is one workgroup; short lists are cut into
 // smaller units (down to one row per lane group) so that they still spread over the machine.
@@ -432,7 +446,7 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
             s.tile_first_ptr.push_back((int32_t)filled);
         }
         s.n_coarse_tiles = (int64_t)s.tile_first_ptr.size() - 1;
-        for_each_tile(s.n_coarse_tiles, host_threads(in, s.n_coarse_tiles), [&](int64_t vt) {
+        for_each_item(s.n_coarse_tiles, host_threads(in.nnz, s.n_coarse_tiles, 16), [&](int64_t vt) {
             std::sort(s.first_rows.begin() + s.tile_first_ptr[vt], s.first_rows.begin() + s.tile_first_ptr[vt + 1]);
         });
     } else {
@@ -538,7 +552,7 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
         blocks[(size_t)vt] = pack_tile(in.rowptr, in.colidx, vals, es, tile_rows,
                                        [&](int32_t c) { return local_of[c] * pitch16; });
     };
-    for_each_tile(nt, host_threads(in, nt), classify);
+    for_each_item(nt, host_threads(in.nnz, nt, 16), classify);
     for (int64_t vt = 0; vt < nt; ++vt) {
         const TileResult &tr = res[(size_t)vt];
         const int64_t rows = s.tile_first_ptr[vt + 1] - s.tile_first_ptr[vt];
@@ -555,11 +569,19 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
     }
     s.tile_second_ptr[nt] = (int32_t)s.second_rows.size();
     s.n_fused_rows = (int64_t)s.second_rows.size();
-    if (!(in.flags & TF_FLAG_REORDER)) std::sort(wf1.begin(), wf1.end());
+    if (!(in.flags & TF_FLAG_REORDER) && !std::is_sorted(wf1.begin(), wf1.end())) std::sort(wf1.begin(), wf1.end());
 
     // ---- spill set ----------------------------------------------------------------------
-    for (int32_t j : wf1)
-        for (int64_t q = in.rowptr[j]; q < in.rowptr[j + 1]; ++q) s.spill[in.colidx[q]] = 1;
+    // (several threads may mark the same row: every one of them stores the same byte)
+    for_each_item((int64_t)wf1.size(), host_threads(in.nnz, (int64_t)wf1.size(), 4096), [&](int64_t k) {
+        const int32_t j = wf1[(size_t)k];
+        for (int64_t q = in.rowptr[j]; q < in.rowptr[j + 1]; ++q) {
+            // (a marked row is not written again: the columns of hub rows would otherwise keep
+            // their cache lines travelling between the threads)
+            uint8_t *m = &s.spill[(size_t)in.colidx[q]];
+            if (!__atomic_load_n(m, __ATOMIC_RELAXED)) __atomic_store_n(m, (uint8_t)1, __ATOMIC_RELAXED);
+        }
+    });
     s.n_spill_rows = std::accumulate(s.spill.begin(), s.spill.end(), (int64_t)0);
     // ---- per-tile blocks (see TileDesc) ---------------------------------------------------
     s.tile_desc.resize((size_t)nt);
@@ -576,7 +598,7 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
         s.tile_meta.reset(new unsigned char[s.tile_meta_bytes]);
         std::memset(s.tile_meta.get() + total, 0, 64);
     }
-    for_each_tile(nt, host_threads(in, nt), [&](int64_t vt) {
+    for_each_item(nt, host_threads(in.nnz, nt, 16), [&](int64_t vt) {
         const int64_t f0 = s.tile_first_ptr[vt], f1 = s.tile_first_ptr[vt + 1];
         TileBlock &tb = blocks[(size_t)vt];
         TileDesc &d = s.tile_desc[(size_t)vt];
@@ -606,7 +628,7 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
     // ---- balance: units of the second wavefront --------------------------------------------
     const PackRules wf1_rules = pack_rules(in, (int64_t)wf1.size());
     auto ident = [](int32_t c) { return c; };
-    pack_rows(in.rowptr, in.colidx, vals, es, wf1, wf1_rules, true, ident, s.wf1.idx32, s.wf1);
+    pack_rows(in.rowptr, in.colidx, vals, es, wf1, wf1_rules, true, ident, s.wf1);
     s.wf1_rows = s.wf1.rows;
     s.wf1_unit_ptr.clear();
     for (const UnitDesc &u : s.wf1.units) s.wf1_unit_ptr.push_back(u.row_begin);
@@ -619,7 +641,7 @@ void build_baseline_pack(const InspectorInput &in, Schedule &s) {
     std::iota(all.begin(), all.end(), 0);
     auto ident = [](int32_t c) { return c; };
     pack_rows(in.rowptr, in.colidx, static_cast<const unsigned char *>(in.vals), elem_size(in.dtype),
-              all, pack_rules(in, in.n), true, ident, s.all.idx32, s.all);
+              all, pack_rules(in, in.n), true, ident, s.all);
 }
 
 }  // namespace tf

@@ -2,6 +2,8 @@
 #pragma once
 #include <cstdint>
 #include <memory>
+#include <new>
+#include <utility>
 #include <string>
 #include <vector>
 
@@ -159,14 +161,26 @@ struct UnitDesc {
 // A list of rows of A re-packed for the gather kernels: per unit a uniform padded row length,
 // so the kernels need no row pointers and no per-row bounds.  Padding repeats the row's last
 // column index with value 0.
+// A vector whose resize() leaves the new elements uninitialised: the packed arrays are sized once
+// and then written in full by the host threads, which are also the first to touch their pages.
+template <typename T> struct NoInitAlloc : std::allocator<T> {
+    template <typename U> struct rebind {
+        using other = NoInitAlloc<U>;
+    };
+    template <typename U> void construct(U *p) noexcept { ::new (static_cast<void *>(p)) U; }
+    template <typename U, typename... A> void construct(U *p, A &&...a) {
+        ::new (static_cast<void *>(p)) U(std::forward<A>(a)...);
+    }
+};
+template <typename T> using RawVec = std::vector<T, NoInitAlloc<T>>;
+
 struct RowPack {
     std::vector<UnitDesc> units;
     std::vector<int32_t> rows;           // row ids, list order
-    std::vector<int32_t> idx32;          // global column indices (second wavefront), or
-    std::vector<uint16_t> idx16;         // tile-local indices (fused tiles)
-    std::vector<unsigned char> vals;     // packed values, element size of the plan's dtype
+    RawVec<int32_t> idx32;               // column indices
+    RawVec<unsigned char> vals;          // packed values, element size of the plan's dtype
     bool sorted = false;                 // rows were re-ordered by length
-    int64_t entries() const { return (int64_t)(idx32.size() + idx16.size()); }
+    int64_t entries() const { return (int64_t)idx32.size(); }
 };
 
 // Host-side schedule produced by the inspector.
