@@ -153,7 +153,10 @@ typedef struct tf_schedule_view {
  * execution call the plan serves.  tp may be NULL for defaults.
  * Validates: A square, 0 <= nnz < 2^31, rowptr monotone with rowptr[0] = 0 and rowptr[n] = nnz,
  * 0 <= col < n, bCol > 0, cCol > 0, one D1 row fits the fast memory.
- * Synchronous; allocates host and device memory owned by the plan.  On failure *out is NULL. */
+ * Synchronous; allocates host and device memory owned by the plan.  On failure *out is NULL.
+ * Matrices of 2^18 entries or more are inspected by several host threads (as many as the
+ * machine reports, at most 16; the environment variable TF_HOST_THREADS=k lowers that to k);
+ * the schedule does not depend on their number. */
 tf_status tf_plan_create(const tf_csr *A, int64_t bCol, int64_t cCol, int32_t b_is_sparse,
                          const tf_tile_params *tp, tf_plan **out);
 

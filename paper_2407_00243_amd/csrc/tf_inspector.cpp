@@ -12,6 +12,7 @@
 #include <algorithm>
 #include <atomic>
 #include <chrono>
+#include <cstdlib>
 #include <cstring>
 #include <numeric>
 #include <thread>
@@ -61,8 +62,12 @@ int pow2_at_least(int64_t x) {
 // Host threads for per-tile or per-unit work: one for small matrices, else up to 16.
 int host_threads(int64_t nnz, int64_t n_items, int64_t min_items_per_thread) {
     if (nnz < ((int64_t)1 << 18) || n_items < 4 * min_items_per_thread) return 1;
-    const unsigned hw = std::max(1u, std::thread::hardware_concurrency());
-    return (int)std::min<int64_t>(std::min<unsigned>(hw, 16u), n_items / min_items_per_thread);
+    unsigned hw = std::min(16u, std::max(1u, std::thread::hardware_concurrency()));
+    if (const char *e = std::getenv("TF_HOST_THREADS")) {      // a cap set by the caller's environment
+        const long k = std::strtol(e, nullptr, 10);
+        if (k >= 1) hw = (unsigned)std::min<long>(k, 16);
+    }
+    return (int)std::min<int64_t>(hw, n_items / min_items_per_thread);
 }
 
 // Runs fn(v) for v in [0, count) on `nthreads` host threads, each with a contiguous range (fn

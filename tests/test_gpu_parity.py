@@ -553,3 +553,33 @@ def test_random_shapes_bit_exact(seed):
             assert np.array_equal(D.astype(np.float64), D_ref), (seed, fused)
     finally:
         c.close()
+
+
+def test_plans_built_by_one_and_by_many_host_threads_agree():
+    """A matrix large enough for the inspector's host threads (2^18 entries or more): the plan built
+    with TF_HOST_THREADS=1 and the plan built with the default number of threads must produce
+    the same D bit for bit (integer entries), fused and unfused, equal to the oracle on sampled
+    rows: the packed units and tile blocks are filled in by the threads."""
+    import os
+    import paper_2407_00243_amd as tf
+    A = ti.laplacian_2d(512, np.float32)
+    n, bcol, ccol = A.n_rows, 16, 16
+    prob = ti.Problem("threads", "gemm_spmm", np.dtype(np.float32), A,
+                      ti.dense_small_int(n, bcol, np.float32, 71), ti.dense_small_int(bcol, ccol, np.float32, 72))
+    out = []
+    for threads in ("1", None):
+        if threads:
+            os.environ["TF_HOST_THREADS"] = threads
+        try:
+            c = _case(prob, ct_size=65536, p=1, flags=tf.TF_FLAG_REORDER)
+        finally:
+            os.environ.pop("TF_HOST_THREADS", None)
+        try:
+            out.append((c.run(fused=True), c.run(fused=False)))
+        finally:
+            c.close()
+    assert np.array_equal(out[0][0], out[1][0]) and np.array_equal(out[0][1], out[1][1])
+    assert np.array_equal(out[0][0], out[0][1])
+    rows = np.random.default_rng(7).choice(n, 400, replace=False)
+    D_ref, _ = oracle.chain_rows(prob.A, prob.B, prob.C, rows)
+    assert np.array_equal(out[1][0][rows].astype(np.float64), D_ref)

@@ -167,7 +167,8 @@ def test_graph_grown_tiles_fill_the_workgroups_evenly(width, dtype):
 def test_large_matrix_schedule_built_by_several_threads():
     """A matrix of a quarter of a million rows is classified and packed by several host threads;
     the schedule must be valid, must not depend on how the tiles were dealt out (two builds
-    agree) and, for consecutive tiles, must equal the oracle's Algorithm 1."""
+    agree, and so does a build by a single thread) and, for consecutive tiles, must equal the
+    oracle's Algorithm 1."""
     A = ti.laplacian_2d(512, np.float32)
     s1 = plan_schedule(A, 64, 64, False, ct_size=65536, p=1, flags=tf.TF_FLAG_REORDER)
     s2 = plan_schedule(A, 64, 64, False, ct_size=65536, p=1, flags=tf.TF_FLAG_REORDER)
@@ -175,6 +176,16 @@ def test_large_matrix_schedule_built_by_several_threads():
         assert np.array_equal(s1[key], s2[key]), key
     assert s1["fused_nnz"] == s2["fused_nnz"] and s1["eq2_cost_max"] == s2["eq2_cost_max"]
     check_schedule_general(A, s1)
+    import os
+    os.environ["TF_HOST_THREADS"] = "1"            # read at every plan creation
+    try:
+        s3 = plan_schedule(A, 64, 64, False, ct_size=65536, p=1, flags=tf.TF_FLAG_REORDER)
+    finally:
+        del os.environ["TF_HOST_THREADS"]
+    for key in ("tile_first_ptr", "first_rows", "second_rows", "tile_second_ptr", "wf1_rows",
+                "wf1_unit_ptr", "spill"):
+        assert np.array_equal(s1[key], s3[key]), key
+    assert s1["fused_nnz"] == s3["fused_nnz"] and s1["second_block_bytes"] == s3["second_block_bytes"]
     B = ti.banded(300000, 3, np.float64, 3)
     s = plan_schedule(B, 16, 16, False, ct_size=512, p=1)
     assert s["n_tiles"] >= 64
