@@ -746,20 +746,36 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
                 }
             }
         };
-        // The spilled rows of a block go to the D1 workspace as soon as the wave that produced
-        // them has written them to the tile (no barrier: it reads back its own writes), whole
-        // rows at a time; this mostly LDS and store work runs while other waves multiply.
-        auto spill_block = [&](int lb) {
-            T *__restrict__ D1 = static_cast<T *>(a.D1);
-            const int rpp = 64 / G;                         // rows per pass (G <= 64 lanes per row)
-            for (int p0 = 0; p0 < 16; p0 += rpp) {
-                const int i = lb * 16 + p0 + lane / G;
-                const uint32_t enc = i < rows ? (uint32_t)first[i] : 0u;
-                const int col = VV * (lane % G);
-                if ((enc & kSpillBit) && col < w) {
-                    T x[VV];
-                    load_pack<T, VV>(x, tileD1 + i * ldl + col);
-                    store_pack<T, VV>(D1 + (int64_t)(enc & ~kSpillBit) * a.ccol + c0 + col, x);
+        // The spilled rows of a block go to the D1 workspace straight from the accumulators of
+        // the wave that produced them (as the unfused product stores its rows): lane (g, r) holds
+        // columns 16 nb + 4 g .. + 3 of row r, so the four lanes of a row store 64 contiguous bytes
+        // per block of columns.  `enc` is the lane's row id with the spill bit, 0 past the tile's end.
+        // (Reading the rows back from the LDS tile, whole rows per store, cost a chain of two LDS
+        // round trips per pass of four rows.)
+        auto row_enc = [&](int lb) -> uint32_t {
+            const int i = lb * 16 + r;
+            return i < rows ? (uint32_t)first[i] : 0u;
+        };
+        auto spill_block = [&](uint32_t enc, typename Tr<T>::Acc(&acc)[NB]) {
+            if (!(enc & kSpillBit)) return;
+            T *dst = static_cast<T *>(a.D1) + (int64_t)(enc & ~kSpillBit) * a.ccol + c0 + 4 * g;
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+#pragma unroll
+                for (int h = 0; h < 4 / V; ++h) {
+                    const int col = 16 * nb + 4 * g + V * h;
+                    if (FAST) {
+                        if (col < w) {
+                            T tmp[V];
+#pragma unroll
+                            for (int i = 0; i < V; ++i) tmp[i] = acc[nb][V * h + i];
+                            store_pack<T, V>(dst + 16 * nb + V * h, tmp);
+                        }
+                    } else {
+#pragma unroll
+                        for (int i = 0; i < V; ++i)
+                            if (col + i < w) dst[16 * nb + V * h + i] = acc[nb][V * h + i];
+                    }
                 }
             }
         };
@@ -776,6 +792,7 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
                 // compiler reuses the accumulators' registers for the buffer being filled and
                 // sinks the loads to the end of the step, which halves the distance they run ahead
                 __builtin_amdgcn_sched_barrier(0);
+                const uint32_t enc = row_enc(lb);
                 typename Tr<T>::Acc acc[NB];
                 if constexpr (CREG) {
                     mfma_frag_reg<T, NB, KSF>(acc, creg, fb[FI]);
@@ -786,7 +803,7 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
                     mfma_frag<T, NB, KSF>(acc, Cl, fb[FI], lane);
                 }
                 write_block(lb, acc);
-                spill_block(lb);
+                spill_block(enc, acc);
             };
             if (is_mfma) {
                 for (int lb = wave; lb < nblk; lb += ND * nmw) {
@@ -810,7 +827,7 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
                 mfma_row_block<T, NB, FAST>(acc, Cl, B + row_of(first, rows, lb) * a.bcol, true,
                                             a.bcol, lane);
                 write_block(lb, acc);
-                spill_block(lb);
+                spill_block(row_enc(lb), acc);
             }
         }
         if constexpr (SLDS) stage_write<kStagePieces>(st, sm.second, blk, d.s_bytes, stid, snt);
