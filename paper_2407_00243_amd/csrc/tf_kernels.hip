@@ -503,15 +503,16 @@ __device__ __forceinline__ SecondBlock<T> second_block(const unsigned char *sb, 
     return b;
 }
 
-// After the tile's D1 rows are complete in LDS: copies the spilled rows to the D1 workspace
-// and computes the tile's fused rows of D, all operands out of LDS.  Lane group grp of ngrp owns
+// After the tile's D1 rows are complete in LDS: computes the tile's fused rows of D, all
+// operands out of LDS.  Lane group grp of ngrp owns
 // the rows grp, grp + ngrp, ...; lane gl of the group owns VV columns from VV gl on.
 //
 // A unit's rows all have `stride` entry slots (even; the real length `len` may be one less)
 // and are walked R rows at a time, two slots per step.  Nothing but LDS latency limits this
 // loop, so the entries (index pair, value pair) of the next step are read while the operands of
 // the current step are on their way.
-// (The spilled rows of the tile have been stored by the waves that produced them.)
+// (The spilled rows of the tile have been stored during the first phase, by the waves or lane
+// groups that produced them.)
 template <typename T, int VV, int R, int W = 1>
 __device__ __forceinline__ void fused_tail(const FusedLaunch &a, const TileDesc &d,
                                            const unsigned char *sb,
@@ -636,11 +637,12 @@ __device__ __forceinline__ void fused_tail(const FusedLaunch &a, const TileDesc 
 constexpr int kStagePieces = 3;     // 16-byte pieces of a second-phase block in flight per thread
 
 // First wavefront, dense B.  A workgroup walks through its tiles; per tile
-//   phase 1  multiplies the tile's rows of B by the C slice with MFMA into the LDS tile, while
-//            the tile's second-phase block and the next tile's row ids travel to LDS;
+//   phase 1  multiplies the tile's rows of B by the C slice with MFMA into the LDS tile (spilled
+//            rows also go to the D1 workspace, straight from the accumulators), while the
+//            tile's second-phase block and the next tile's row ids travel to LDS;
 //   barrier;
-//   phase 2  starts the loads of the next tile's first rows of B, copies the spilled rows to
-//            the D1 workspace and computes the tile's fused rows of D out of LDS;
+//   phase 2  starts the loads of the next tile's first rows of B and computes the tile's fused
+//            rows of D out of LDS;
 //   barrier (the LDS tile is rewritten by the next tile).
 // KS > 0: bCol = 4 V KS exactly and the B rows of the next two 16-row blocks of a wave are in
 // flight while the current block is multiplied; KS = 0: any bCol, no prefetch.
