@@ -55,8 +55,8 @@ def tile_params(cfg, width=None, dtype=None):
 # WRITE_SIZE, scaled by what the same counters read for a plain copy), keyed by workload;
 # None until measured.  See profiles/.
 MEASURED_TRAFFIC_BYTES = {
-    # profiles/k_fused_gemm_spmm_cfg2_2dlaplacian.md: FETCH_SIZE 37718.9 KiB x 2.000 + WRITE_SIZE 76090.4 KiB
-    "cfg2 GeMM-SpMM fp32 2D Laplacian n=262144 64->64": int((2.0 * 37718.9 + 76090.4) * 1024),
+    # profiles/k_fused_gemm_spmm_cfg2_2dlaplacian.md: FETCH_SIZE 37712.9 KiB x 2.000 + WRITE_SIZE 76090.4 KiB
+    "cfg2 GeMM-SpMM fp32 2D Laplacian n=262144 64->64": int((2.0 * 37712.9 + 76090.4) * 1024),
     # profiles/k_fused_spmm_spmm_cfg4_3dlaplacian.md: FETCH_SIZE 125704.6 KiB x 2.000 + WRITE_SIZE 168471.5 KiB
     "cfg4 SpMM-SpMM fp64 3D Laplacian n=262144 262144->64": int((2.0 * 125704.6 + 168471.5) * 1024),
 }
