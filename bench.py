@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the fused chain D = A(BC) on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5] [--no-cpu] [--skip-unread] [tile options]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5] [--no-cpu] [tile options]
 
 A step is one fused execution (first wavefront + second wavefront) of the workload; the
 schedule is built once before the timed region and its time is reported separately, as the
@@ -10,6 +10,12 @@ inputs are resident in device memory before timing starts.  Successive steps rot
 several independent buffer sets (operands, outputs and plan workspaces) so that together
 they exceed the 256 MB last-level cache: the reported throughput is the cache-cold one.
 
+The headline workload is the largest configuration (3: the GCN layer on an R-MAT graph of 2^20
+vertices); the paper reports on every matrix of both families (Section 4.1), so the other four
+configurations are measured in the same process and reported under "per_config" (left out with
+--config K, which benchmarks configuration K alone).  Plans are created with the library's
+defaults (no tile parameters) unless tile options are given.
+
 Prints ONE JSON line on stdout; everything else goes to stderr.
 """
 from __future__ import annotations
@@ -17,6 +23,7 @@ from __future__ import annotations
 import argparse
 import json
 import os
+import re
 import statistics
 import sys
 import time
@@ -27,39 +34,37 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_PEAK_TFLOPS = {"f32": 157.3, "f64": 78.6}
+HEADLINE_CONFIG = 3
 
-# Tile parameters used per configuration: graph-grown tiles as large as the LDS allows for the
-# stencils (2, 4), consecutive tiles of the given size for the band (1) and the graphs (3, 5).
-TILE_PARAMS = {
-    1: dict(ct_size=64, p=1),
-    2: dict(ct_size=65536, p=1, flags=4),
-    3: dict(ct_size=128, p=1),
-    4: dict(ct_size=65536, p=1, flags=4),
-    5: dict(ct_size=2048, p=1),
-}
-
+# Steps for the configurations under per_config: their steps take 15 to 600 us, so the driver's
+# 20 steps would make a timed region of a millisecond or less.
+PER_CONFIG_STEPS = {1: 400, 2: 300, 4: 200, 5: 100}
 
 
 def tile_params(cfg, width=None, dtype=None):
-    """Tile parameters of a configuration as benchmarked.  Config 2 at its own width and precision
-    has its tiles fitted to half of the LDS, so that two workgroups share a compute unit (measured:
-    first wavefront 48.8 us against 52.1 us); on the other points of the experiment grid, where
-    the C slice takes LDS as well, that setting was not measured to help and is left out."""
-    params = dict(TILE_PARAMS[cfg])
-    if cfg == 2 and width is None and dtype is None:
-        params["fast_mem_bytes"] = 80 * 1024
-    return params
+    """Tile parameters of a configuration as benchmarked: none, the library chooses
+    (tf_plan_create with defaults)."""
+    return {}
 
 
-# HBM traffic per launch of the dominant kernel from rocprofv3 --pmc runs (FETCH_SIZE and
-# WRITE_SIZE, scaled by what the same counters read for a plain copy), keyed by workload;
-# None until measured.  See profiles/.
-MEASURED_TRAFFIC_BYTES = {
-    # profiles/k_fused_gemm_spmm_cfg2_2dlaplacian.md: FETCH_SIZE 37712.9 KiB x 2.000 + WRITE_SIZE 76090.4 KiB
-    "cfg2 GeMM-SpMM fp32 2D Laplacian n=262144 64->64": int((2.0 * 37712.9 + 76090.4) * 1024),
-    # profiles/k_fused_spmm_spmm_cfg4_3dlaplacian.md: FETCH_SIZE 125704.6 KiB x 2.000 + WRITE_SIZE 168471.5 KiB
-    "cfg4 SpMM-SpMM fp64 3D Laplacian n=262144 262144->64": int((2.0 * 125704.6 + 168471.5) * 1024),
-}
+def measured_traffic():
+    """HBM traffic per launch of the dominant kernels from rocprofv3 --pmc runs: the table of
+    profiles/traffic.md (config | kernel | FETCH_SIZE KiB | WRITE_SIZE KiB | fetch scale | write
+    scale | commit), bytes = (fetch x scale + write x scale) x 1024.  {} if the file is missing."""
+    out = {}
+    path = os.path.join(ROOT, "profiles", "traffic.md")
+    if not os.path.exists(path):
+        return out
+    for line in open(path):
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) < 7 or not re.match(r"^cfg\d", cells[0]):
+            continue
+        try:
+            fetch, write, fs, ws = (float(cells[i]) for i in (2, 3, 4, 5))
+        except ValueError:
+            continue
+        out[(cells[0], cells[1])] = dict(bytes=int((fetch * fs + write * ws) * 1024), commit=cells[6])
+    return out
 
 
 def log(*a):
@@ -69,16 +74,21 @@ def log(*a):
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=42)
+    ap.add_argument("--steps", type=int, default=40)
     ap.add_argument("--warmup", type=int, default=6)
-    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5")
+    ap.add_argument("--config", type=int, default=None,
+                    help="benchmark configuration 1..5 alone (default: 3 as the headline, the "
+                         "other four under per_config)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--no-per-config", action="store_true", help="headline configuration only")
     ap.add_argument("--sets", type=int, default=0, help="buffer sets to rotate over (0 = auto)")
     ap.add_argument("--ct-size", type=int, default=None)
     ap.add_argument("--p", type=int, default=None)
     ap.add_argument("--col-slice", type=int, default=None)
     ap.add_argument("--fast-mem", type=int, default=None)
+    ap.add_argument("--gather-slices", type=int, default=None)
     ap.add_argument("--reorder", type=int, default=None, help="1: graph-grown tiles, 0: consecutive")
+    ap.add_argument("--no-split", action="store_true", help="TF_FLAG_NO_SPLIT (step 1 only)")
     ap.add_argument("--width", type=int, default=None,
                     help="experiment grid: bCol = cCol (cCol only for a sparse B) instead of the "
                          "configuration's own")
@@ -96,39 +106,16 @@ def parse():
     return ap.parse_args()
 
 
-def main():
-    args = parse()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        log("bench.py: this build runs on ONE GPU only (the path is a single-GPU kernel pipeline; "
-            "it would shard by row blocks aligned to tile boundaries with one exchange of spilled rows "
-            "between the wavefronts).  Re-run with --gpus 1.")
-        sys.exit(2)
-
+def measure(cfg, args, steps, warmup, headline):
+    """Builds configuration `cfg`, times `steps` fused steps (and as many unfused ones) between two
+    synchronisations, then the wavefronts one by one.  Returns the result dictionary."""
     import numpy as np
     import torch
-
-    if args.calibrate_copy:
-        torch.cuda.set_device(0)
-        nel = args.calibrate_copy * 1024 * 1024 // 4
-        src = torch.ones(nel, dtype=torch.float32, device="cuda")
-        dst = torch.empty_like(src)
-        for _ in range(10):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        print(json.dumps({"calibrate_copy_mib": args.calibrate_copy, "copies": 10}))
-        return
 
     import paper_2407_00243_amd as tf
     import tf_inputs as ti
 
-    if not os.path.exists(tf.library_path()):
-        import __graft_entry__
-        __graft_entry__.build()
-    tf.load_library()
-    torch.cuda.set_device(0)
     stream = torch.cuda.current_stream().cuda_stream
-
-    cfg = args.config
     t0 = time.time()
     prob = ti.config(cfg, width=args.width,
                      dtype={None: None, "f32": np.float32, "f64": np.float64}[args.dtype])
@@ -139,15 +126,18 @@ def main():
     tdtype = torch.float32 if es == 4 else torch.float64
     params = tile_params(cfg, args.width, args.dtype)
     for k, v in (("ct_size", args.ct_size), ("p", args.p), ("col_slice", args.col_slice),
-                 ("fast_mem_bytes", args.fast_mem)):
+                 ("fast_mem_bytes", args.fast_mem), ("gather_slices", args.gather_slices)):
         if v is not None:
             params[k] = v
+    flags = params.get("flags", 0)
     if args.reorder is not None:
-        params["flags"] = (params.get("flags", 0) & ~tf.TF_FLAG_REORDER) | \
-            (tf.TF_FLAG_REORDER if args.reorder else 0)
-
+        flags = (flags & ~tf.TF_FLAG_REORDER) | (tf.TF_FLAG_REORDER if args.reorder else 0)
     if args.skip_unread:
-        params["flags"] = params.get("flags", 0) | tf.TF_FLAG_SKIP_UNREAD
+        flags |= tf.TF_FLAG_SKIP_UNREAD
+    if args.no_split:
+        flags |= tf.TF_FLAG_NO_SPLIT
+    if flags:
+        params["flags"] = flags
 
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
     n, bcol, ccol = prob.n, prob.bcol, prob.ccol
@@ -157,13 +147,14 @@ def main():
     n_sets = args.sets or max(2, int(np.ceil(3 * 256e6 / set_bytes)))
     n_sets = min(n_sets, 8)
 
-    # buffer sets: each has its own operands, output and plan (workspace + copy of A)
+    # buffer sets: each has its own operands, output and plan (workspaces + copy of A)
     sets = []
     plan_seconds = []
     for i in range(n_sets):
         t1 = time.perf_counter()
         plan = tf.Plan(prob.A, bcol, ccol, sparse, **params)
         plan_seconds.append(time.perf_counter() - t1)
+        plan.prepare_unfused()
         if sparse:
             B = tf.DeviceCsr(prob.B.n_rows, prob.B.n_cols, dev(prob.B.rowptr), dev(prob.B.colidx),
                              dev(prob.B.vals))
@@ -174,24 +165,27 @@ def main():
         sets.append((plan, B, C, D))
     sched = sets[0][0].schedule()
     torch.cuda.synchronize()
-    log(f"[bench] plan: t={sched['t']} tiles={sched['n_tiles']} cs={sched['col_slice']} "
-        f"fused rows={sched['fused_ratio_rows']:.3f} fused nnz={sched['fused_ratio_nnz']:.3f} "
-        f"spill={sched['n_spill_rows'] / max(n, 1):.3f} wf1 units={sched['n_wf1_units']} "
+    log(f"[bench] plan: t={sched['t']} tiles={sched['n_tiles']} grown={sched['grown_tiles']} "
+        f"cs={sched['col_slice']} fused rows={sched['fused_ratio_rows']:.3f} "
+        f"fused nnz={sched['fused_ratio_nnz']:.3f} direct={sched['n_direct_rows']} "
+        f"demoted={sched['n_demoted_rows']} streams={sched['first_wavefront_streams']} "
+        f"spill={sched['n_spill_rows'] / max(n, 1):.3f} d1 slices={sched['d1_slices']} "
+        f"wf1 units={sched['n_wf1_units']} "
         f"plan {min(plan_seconds) * 1e3:.1f} ms ({sched['plan_seconds'] * 1e3:.1f} ms schedule)")
 
     flops = ti.useful_flops(prob)
     q_alg = sched["alg_bytes"] + (b_bytes if sparse else 0)
     q_unf = sched["alg_bytes_unfused"] + (b_bytes if sparse else 0)
 
-    def timed(fn, steps, warmup):
-        for i in range(warmup):
+    def timed(fn, k, w):
+        for i in range(w):
             fn(sets[i % n_sets])
         torch.cuda.synchronize()
         t = time.perf_counter()
-        for i in range(steps):
+        for i in range(k):
             fn(sets[i % n_sets])
         torch.cuda.synchronize()
-        return (time.perf_counter() - t) / steps * 1e3
+        return (time.perf_counter() - t) / k * 1e3
 
     def event_times(fn, reps, rotate=True):
         out = []
@@ -210,16 +204,16 @@ def main():
     wf0 = lambda s: s[0].run_wavefront(0, s[1], s[2], s[3], stream)
     wf1 = lambda s: s[0].run_wavefront(1, s[1], s[2], s[3], stream)
 
-    # ---- the timed region of the contract: exactly K steps between two synchronisations
-    ms_fused = timed(fused, args.steps, args.warmup)
-    ms_unfused = timed(unfused, args.steps, max(2, args.warmup // 2))
+    # ---- the timed region of the contract: exactly `steps` steps between two synchronisations
+    ms_fused = timed(fused, steps, warmup)
+    ms_unfused = timed(unfused, steps, max(2, warmup // 2))
     med_fused = statistics.median(event_times(fused, 7))
     med_unfused = statistics.median(event_times(unfused, 7))
     warm_fused = statistics.median(event_times(fused, 9, rotate=False)[2:])
     warm_unfused = statistics.median(event_times(unfused, 9, rotate=False)[2:])
 
     graph_ms = None
-    if args.graph:
+    if args.graph and headline:
         side = torch.cuda.Stream()
 
         def graphs_of(fn):
@@ -233,21 +227,21 @@ def main():
             return out
 
         def timed_graphs(gs):
-            for i in range(args.warmup):
+            for i in range(warmup):
                 gs[i % n_sets].replay()
             torch.cuda.synchronize()
             t = time.perf_counter()
-            for i in range(args.steps):
+            for i in range(steps):
                 gs[i % n_sets].replay()
             torch.cuda.synchronize()
-            return (time.perf_counter() - t) / args.steps * 1e3
+            return (time.perf_counter() - t) / steps * 1e3
 
         graph_ms = {"fused": timed_graphs(graphs_of(fused)),
                     "unfused": timed_graphs(graphs_of(unfused))}
 
     # ---- per-kernel durations over the same rotation, HIP events on the launch stream
     def avg_kernel_ms(fn, before=None):
-        reps = max(args.steps, 2 * n_sets)
+        reps = max(steps, 2 * n_sets)
         e0 = [torch.cuda.Event(enable_timing=True) for _ in range(reps)]
         e1 = [torch.cuda.Event(enable_timing=True) for _ in range(reps)]
         for i in range(reps):
@@ -268,10 +262,7 @@ def main():
     c_bytes = bcol * ccol * es
     q_wf0 = b_bytes + c_bytes + fused_nnz * (4 + es) + 4 * nf + nf * ccol * es + ns * ccol * es
     q_wf1 = q_alg - q_wf0
-    if sparse:
-        gemm_flops = 0
-    else:
-        gemm_flops = 2 * n * bcol * ccol
+    gemm_flops = 0 if sparse else 2 * n * bcol * ccol
     dom_is_wf0 = ms_wf0 >= ms_wf1
     dom_ms, dom_q = (ms_wf0, q_wf0) if dom_is_wf0 else (ms_wf1, q_wf1)
     dname = "f32" if es == 4 else "f64"
@@ -285,15 +276,59 @@ def main():
         roofline = dict(bound="hbm", achieved=dom_q / (dom_ms * 1e-3) / 1e9, peak=HBM_PEAK_GBS,
                         unit="GB/s")
     roofline["frac"] = roofline["achieved"] / roofline["peak"]
-    roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get(workload)
-    roofline["kernel"] = ("k_fused_" + ("spmm_spmm" if sparse else "gemm_spmm")) if dom_is_wf0 \
-        else "k_packed_spmm"
+    if not dom_is_wf0:
+        kernel = "k_packed_spmm"
+    elif sched["first_wavefront_streams"]:
+        kernel = "k_csr_spmm" if sparse else "k_gemm"
+    else:
+        kernel = "k_fused_" + ("spmm_spmm" if sparse else "gemm_spmm")
+    traffic = measured_traffic().get((f"cfg{cfg}", kernel))
+    roofline["traffic"] = traffic["bytes"] if traffic else None
+    roofline["traffic_commit"] = traffic["commit"] if traffic else None
+    roofline["kernel"] = kernel
     roofline["kernel_ms"] = dom_ms
     roofline["alg_bytes_per_launch"] = int(dom_q)
 
-    # ---- CPU oracle on the host cores (bounded: config 2 whole, others a row sample)
-    cpu = None
-    if not args.no_cpu:
+    out = {
+        "workload": workload,
+        "dtype": dname,
+        "steps": steps,
+        "ms_per_step": ms_fused,
+        "value": flops / (ms_fused * 1e-3) / 1e9,
+        "tile_params": params,
+        "buffer_sets": n_sets,
+        "useful_flops": int(flops),
+        "hbm_alg_gbs": q_alg / (ms_fused * 1e-3) / 1e9,
+        "hbm_alg_frac": q_alg / (ms_fused * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "alg_bytes": int(q_alg),
+        "alg_bytes_unfused": int(q_unf),
+        "unfused_ms_per_step": ms_unfused,
+        "speedup_vs_unfused": ms_unfused / ms_fused,
+        "median7_ms": {"fused": med_fused, "unfused": med_unfused},
+        "warm_ms": {"fused": warm_fused, "unfused": warm_unfused},
+        "graph_ms": graph_ms,
+        "kernels_ms": {"wavefront0": ms_wf0, "wavefront1": ms_wf1},
+        "fused_ratio": {"eq3": sched["fused_ratio_eq3"], "rows": sched["fused_ratio_rows"],
+                        "nnz": sched["fused_ratio_nnz"]},
+        "spill_fraction": sched["n_spill_rows"] / max(n, 1),
+        "first_rows_fraction": sched["n_first_rows"] / max(n, 1),
+        "schedule": {"t": sched["t"], "tiles": sched["n_tiles"], "col_slice": sched["col_slice"],
+                     "grown_tiles": sched["grown_tiles"], "fast_mem_bytes": sched["fast_mem_bytes"],
+                     "wf1_units": sched["n_wf1_units"], "eq2_cost_max": sched["eq2_cost_max"],
+                     "direct_rows": sched["n_direct_rows"], "demoted_rows": sched["n_demoted_rows"],
+                     "first_wavefront_streams": sched["first_wavefront_streams"],
+                     "d1_slices": sched["d1_slices"]},
+        "plan_ms": min(plan_seconds) * 1e3,
+        "schedule_ms": sched["plan_seconds"] * 1e3,
+        # scheduler time / (baseline time - fused time), as the paper counts it (Section 4, scheduler
+        # overhead); plan_ms also holds the uploads and the baseline's own packed copy of A
+        "amortisation_runs": (sched["plan_seconds"] * 1e3 / (ms_unfused - ms_fused))
+        if ms_unfused > ms_fused else None,
+        "roofline": roofline,
+    }
+
+    # ---- CPU oracle on the host cores (bounded: small configs whole, others a row sample)
+    if headline and not args.no_cpu:
         import oracle
         t1 = time.perf_counter()
         if cfg in (1, 2, 4):
@@ -312,52 +347,93 @@ def main():
             sample_flops = 2 * int(lens.sum()) * (2 * ccol + per_dep)    # D and W passes
             sample = f"{rows.size} sampled rows of D with the D1 rows they need (D and W)"
         dt = time.perf_counter() - t1
-        cpu = dict(value=sample_flops / dt / 1e9, unit="GFLOP/s", cores=oracle.num_threads(),
-                   kind="oracle", sample=sample, seconds=dt)
+        out["cpu_baseline"] = dict(value=sample_flops / dt / 1e9, unit="GFLOP/s",
+                                   cores=oracle.num_threads(), kind="oracle", sample=sample,
+                                   seconds=dt)
+    for s in sets:
+        s[0].close()
+    del sets
+    torch.cuda.empty_cache()
+    return out
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        log("bench.py: this build runs on ONE GPU only (the path is a single-GPU kernel pipeline; "
+            "it would shard by row blocks aligned to tile boundaries with one exchange of spilled rows "
+            "between the wavefronts).  Re-run with --gpus 1.")
+        sys.exit(2)
+
+    import torch
+
+    if args.calibrate_copy:
+        torch.cuda.set_device(0)
+        nel = args.calibrate_copy * 1024 * 1024 // 4
+        src = torch.ones(nel, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_mib": args.calibrate_copy, "copies": 10}))
+        return
+
+    import paper_2407_00243_amd as tf
+
+    if not os.path.exists(tf.library_path()):
+        import __graft_entry__
+        __graft_entry__.build()
+    tf.load_library()
+    torch.cuda.set_device(0)
+
+    cfg = args.config or HEADLINE_CONFIG
+    head = measure(cfg, args, args.steps, args.warmup, headline=True)
+    per_config = None
+    if args.config is None and not args.no_per_config and args.width is None and args.dtype is None:
+        per_config = {}
+        for other in (1, 2, 4, 5):
+            r = measure(other, args, max(args.steps, PER_CONFIG_STEPS[other]), args.warmup,
+                        headline=False)
+            per_config[f"cfg{other}"] = {
+                "workload": r["workload"], "dtype": r["dtype"], "steps": r["steps"],
+                "fused_ms": r["ms_per_step"], "unfused_ms": r["unfused_ms_per_step"],
+                "speedup_vs_unfused": r["speedup_vs_unfused"],
+                "useful_gflops": r["value"], "hbm_alg_gbs": r["hbm_alg_gbs"],
+                "hbm_alg_frac": r["hbm_alg_frac"], "kernels_ms": r["kernels_ms"],
+                "dominant_kernel": r["roofline"]["kernel"],
+                "dominant_kernel_bound": r["roofline"]["bound"],
+                "dominant_kernel_frac": r["roofline"]["frac"],
+                "dominant_kernel_traffic": r["roofline"]["traffic"],
+                "fused_ratio_rows": r["fused_ratio"]["rows"], "fused_ratio_nnz": r["fused_ratio"]["nnz"],
+                "spill_fraction": r["spill_fraction"], "schedule": r["schedule"],
+                "schedule_ms": r["schedule_ms"], "amortisation_runs": r["amortisation_runs"],
+            }
 
     out = {
         "metric": "useful GFLOP/s of fused D=A(BC) (unfused-FLOP count / fused time), cache-cold",
-        "value": flops / (ms_fused * 1e-3) / 1e9,
+        "value": head["value"],
         "unit": "GFLOP/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": ms_fused,
+        "ms_per_step": head["ms_per_step"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": dname,
+        "dtype": head["dtype"],
         "data": "synthetic",
-        "config": {"workload": workload, "tile_params": params, "buffer_sets": n_sets,
-                   "useful_flops": int(flops)},
-        "hbm_alg_gbs": q_alg / (ms_fused * 1e-3) / 1e9,
-        "hbm_alg_frac": q_alg / (ms_fused * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "alg_bytes": int(q_alg),
-        "alg_bytes_unfused": int(q_unf),
-        "unfused_ms_per_step": ms_unfused,
-        "speedup_vs_unfused": ms_unfused / ms_fused,
-        "median7_ms": {"fused": med_fused, "unfused": med_unfused},
-        "warm_ms": {"fused": warm_fused, "unfused": warm_unfused},
-        "graph_ms": graph_ms,
-        "kernels_ms": {"wavefront0": ms_wf0, "wavefront1": ms_wf1},
-        "fused_ratio": {"eq3": sched["fused_ratio_eq3"], "rows": sched["fused_ratio_rows"],
-                        "nnz": sched["fused_ratio_nnz"]},
-        "spill_fraction": sched["n_spill_rows"] / max(n, 1),
-        "first_rows_fraction": sched["n_first_rows"] / max(n, 1),
-        "schedule": {"t": sched["t"], "tiles": sched["n_tiles"], "col_slice": sched["col_slice"],
-                     "wf1_units": sched["n_wf1_units"], "eq2_cost_max": sched["eq2_cost_max"]},
-        "plan_ms": min(plan_seconds) * 1e3,
-        "schedule_ms": sched["plan_seconds"] * 1e3,
-        # scheduler time / (baseline time - fused time), as the paper counts it (Section 4, scheduler
-        # overhead); plan_ms also holds the uploads and the baseline's own packed copy of A
-        "amortisation_runs": (sched["plan_seconds"] * 1e3 / (ms_unfused - ms_fused))
-        if ms_unfused > ms_fused else None,
-        "paper_context": "paper: 1.97x over unfused, 1.64x over MKL (geomean, 40/64-core CPUs)",
-        "roofline": roofline,
-        "cpu_baseline": cpu,
+        "config": {"workload": head["workload"], "tile_params": head["tile_params"],
+                   "buffer_sets": head["buffer_sets"], "useful_flops": head["useful_flops"]},
     }
-    for s in sets:
-        s[0].close()
+    for k in ("hbm_alg_gbs", "hbm_alg_frac", "alg_bytes", "alg_bytes_unfused", "unfused_ms_per_step",
+              "speedup_vs_unfused", "median7_ms", "warm_ms", "graph_ms", "kernels_ms", "fused_ratio",
+              "spill_fraction", "first_rows_fraction", "schedule", "plan_ms", "schedule_ms",
+              "amortisation_runs"):
+        out[k] = head[k]
+    out["paper_context"] = "paper: 1.97x over unfused, 1.64x over MKL (geomean, 40/64-core CPUs)"
+    out["roofline"] = head["roofline"]
+    out["cpu_baseline"] = head.get("cpu_baseline")
+    out["per_config"] = per_config
     print(json.dumps(out), flush=True)
 
 

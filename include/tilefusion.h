@@ -17,7 +17,8 @@
  *     summed in an unspecified order.
  *   - D is overwritten (the listings of Section 3.2 accumulate into zeroed outputs).
  *   - The caller owns A, B, C and D.  The plan owns a device copy of A (pattern and values), the
- *     schedule and a workspace for the D1 rows that cross tiles.
+ *     schedule and a workspace with one slot for every D1 row that crosses tiles (no other D1
+ *     row ever reaches device memory: Section 3.1, one synchronisation between two wavefronts).
  *   - Errors are reported by return code; tf_last_error() gives a message for the calling
  *     thread's most recent failure.  No call throws or aborts.
  */
@@ -55,15 +56,30 @@ typedef struct tf_csr {
     int32_t on_device;  /* 0 = host pointers, 1 = device pointers */
 } tf_csr;
 
-/* Inputs of the scheduler (Algorithm 1) besides the pattern.  Zero selects the default. */
+/* Inputs of the scheduler (Algorithm 1) besides the pattern.  Zero selects the default.
+ * With ct_size = 0 and p = 0 and neither TF_FLAG_REORDER nor TF_FLAG_NO_SPLIT (in particular with
+ * tp = NULL) the tiling is left to the library: ctSize 2048, p = a quarter of the compute units,
+ * half of the LDS per tile where two workgroups per compute unit pay (dense B, small bCol x cCol);
+ * tiles of consecutive rows as in Algorithm 1 unless they fuse under half of the entries of a
+ * matrix whose rows stay near the diagonal and graph-grown tiles spill fewer D1 rows; and where
+ * the fused rows that read the fast memory hold under 2 % of the entries (graphs) they are left
+ * to the second wavefront, so that the first wavefront needs no tile in fast memory at all.
+ * With ct_size or p given, step 1 is Algorithm 1 to the letter. */
 typedef struct tf_tile_params {
     int32_t ct_size;         /* coarse tile size ctSize (Section 3.1.1); default 2048           */
-    int32_t p;               /* wanted number of tiles per wavefront ("cores"); default 32      */
+    int32_t p;               /* wanted number of tiles per wavefront ("cores"); default 32 when
+                                ct_size is given, else a quarter of the compute units            */
     int64_t fast_mem_bytes;  /* fast memory of one tile: the LDS a workgroup may use;
                                 default = the device's LDS per workgroup (160 KiB on gfx950)    */
     int32_t col_slice;       /* columns of C/D handled by one workgroup; default = cCol, capped
                                 at what the kernels cover; a last narrower slice is allowed     */
     uint32_t flags;          /* TF_FLAG_* */
+    int32_t gather_slices;   /* column slices of the D1 workspace, each gathered by its own XCDs
+                                in the second wavefront: 1, 2, 4 or 8, slices of a power of two
+                                of columns, at least 16 and at least 64 bytes.  Default: 1 for
+                                matrices whose rows stay near the diagonal, more for matrices
+                                whose rows reach far (graphs), see tf_schedule_view.d1_slices   */
+    int32_t reserved0;
 } tf_tile_params;
 
 /* Skip step 2 (tile splitting): tiles that do not fit the fast memory make plan creation fail. */
@@ -91,6 +107,10 @@ typedef struct tf_tile_params {
  * operation, D is unchanged.  The unfused calls still compute all of D1, and after a fused call
  * the workspace rows of skipped D1 rows are not written. */
 #define TF_FLAG_SKIP_UNREAD 16u
+/* The plan serves the fused calls only: the packed copy of all rows of A that the unfused
+ * baseline runs on is not built (saves its time and device memory); tf_unfused_* then fail with
+ * TF_EINVAL. */
+#define TF_FLAG_NO_BASELINE 32u
 
 typedef struct tf_plan tf_plan; /* opaque, library-owned */
 
@@ -139,11 +159,33 @@ typedef struct tf_schedule_view {
     double eq2_cost_max;        /* largest Eq. 2 data-movement cost over the tiles (elements)  */
     double plan_seconds;        /* host time spent building the schedule (without the packed
                                    copy of A that only the unfused baseline uses)              */
-    int64_t alg_bytes;          /* algorithmic HBM bytes of one fused execution                */
-    int64_t alg_bytes_unfused;  /* the same for the unfused two-kernel execution               */
+    int64_t alg_bytes;          /* algorithmic HBM bytes of one fused execution: A, B, C and D once,
+                                   every spilled D1 row written once and read once.  A CSR B is
+                                   not known to the plan and is NOT included: the caller adds
+                                   4 (n + 1) + nnz(B) (4 + element size)                         */
+    int64_t alg_bytes_unfused;  /* the same for the unfused two-kernel execution (all of D1
+                                   written once and read once)                                   */
     int64_t second_block_bytes; /* largest per-tile block of packed entries (fused rows)       */
     int64_t lds_launch_bytes;   /* LDS one fused workgroup is launched with (0: schedule only) */
     int64_t n_first_rows;       /* D1 rows the first wavefront produces (length of first_rows) */
+    const int32_t *spill_slot;  /* n entries: slot of the D1 row in the workspace, -1 = not spilled */
+    int64_t n_direct_rows;      /* fused rows of D that are their own D1 row times a single diagonal
+                                   entry, or empty: stored from the registers that hold the D1 row
+                                   (they are listed in second_rows like every fused row)         */
+    int32_t d1_slices;          /* workspace layout: d1_slices column slices of d1_slice_cols     */
+    int32_t d1_slice_cols;      /* columns, slice after slice, each d1_rows x d1_slice_cols       */
+    int64_t d1_rows;            /* row-major: element (slot, c) is at (c / d1_slice_cols) d1_rows
+                                   d1_slice_cols + slot d1_slice_cols + c mod d1_slice_cols       */
+    int32_t first_wavefront_streams; /* 1: no fused row reads the LDS tile (all are direct rows), so
+                                   the first wavefront runs without tiles in LDS, streaming through
+                                   the rows like the plain first operation                        */
+    int32_t grown_tiles;        /* 1: tiles were grown along the dependence graph (TF_FLAG_REORDER,
+                                   or the library's own choice), 0: ranges of consecutive rows   */
+    int64_t n_demoted_rows;     /* rows that their tile could have fused but that the library left
+                                   to the second wavefront (only when the tiling was left to the
+                                   library, see tf_plan_create); 0 = step 1 is maximal            */
+    int32_t far_rows;           /* 1: the rows of A reach far from the diagonal (a graph)         */
+    int32_t automatic;          /* 1: the tiling was left to the library                          */
 } tf_schedule_view;
 
 /* Inspector: builds the fused schedule for the pattern of A (Algorithm 1: step 1, coarse tile
@@ -176,13 +218,18 @@ tf_status tf_gemm_spmm(const tf_plan *plan, const void *B, const void *C, void *
                        void *hip_stream);
 
 /* Fused execution with CSR B (Section 3.2, fused SpMM-SpMM listing).  B must be on the device,
- * n x bCol with the plan's bCol and dtype; C is bCol x cCol.  B may alias A's arrays. */
+ * n x bCol with the plan's bCol and dtype; C is bCol x cCol.  B may alias A's arrays.
+ * B's arrays live on the device and are NOT validated by the execution calls (only its shape
+ * and element type are): a well-formed CSR (monotone rowptr with rowptr[0] = 0, 0 <= column <
+ * bCol) is the caller's precondition; tf_csr_validate checks it where that is in doubt. */
 tf_status tf_spmm_spmm(const tf_plan *plan, const tf_csr *B, const void *C, void *D,
                        void *hip_stream);
 
 /* The unfused two-kernel baseline on the same plan (Section 4.1: an unfused parallel
- * implementation with the same optimisations): D1 = B C for all rows into the plan's
- * workspace, then D = A D1 for all rows.  Same argument rules as the fused calls. */
+ * implementation with the same optimisations): D1 = B C for all rows into a workspace of n rows,
+ * then D = A D1 for all rows.  Same argument rules as the fused calls, except that the first
+ * unfused call on a plan allocates that workspace (call tf_plan_prepare_unfused beforehand where
+ * the call itself must not allocate, e.g. under stream capture). */
 tf_status tf_unfused_gemm_spmm(const tf_plan *plan, const void *B, const void *C, void *D,
                                void *hip_stream);
 tf_status tf_unfused_spmm_spmm(const tf_plan *plan, const tf_csr *B, const void *C, void *D,
@@ -195,9 +242,20 @@ tf_status tf_unfused_spmm_spmm(const tf_plan *plan, const tf_csr *B, const void 
 tf_status tf_run_wavefront(const tf_plan *plan, int32_t wavefront, const void *B_dense,
                            const tf_csr *B_csr, const void *C, void *D, void *hip_stream);
 
-/* Device pointer of the plan's D1 workspace (n x cCol, row-major).  After a fused execution
- * only the spilled rows hold D1; after an unfused execution all rows do.  For tests. */
+/* Allocates the n x cCol workspace of the unfused baseline if it does not exist yet. */
+tf_status tf_plan_prepare_unfused(const tf_plan *plan);
+
+/* Device pointer of the plan's D1 workspace: after a fused execution slot spill_slot[i] holds D1
+ * row i, in the layout that tf_schedule_view describes (d1_slices, d1_slice_cols, d1_rows).
+ * tf_plan_workspace_unfused: the baseline's workspace, same layout with n rows and slot = row
+ * (NULL before the first unfused call or tf_plan_prepare_unfused).  For tests. */
 tf_status tf_plan_workspace(const tf_plan *plan, void **d1_device);
+tf_status tf_plan_workspace_unfused(const tf_plan *plan, void **d1_device);
+
+/* Checks a CSR matrix given with host or device arrays (device arrays are copied to the host):
+ * rowptr[0] = 0, rowptr monotone, rowptr[n_rows] = nnz, 0 <= column < n_cols.  TF_OK or
+ * TF_EBADCSR.  Synchronous; meant for a CSR B before it is handed to tf_spmm_spmm. */
+tf_status tf_csr_validate(const tf_csr *M);
 
 /* Message for the most recent failure on the calling thread ("" if none). */
 const char *tf_last_error(void);

@@ -17,6 +17,7 @@ TF_FLAG_SCHEDULE_ONLY = 2
 TF_FLAG_REORDER = 4
 TF_FLAG_C_TRANSPOSED = 8
 TF_FLAG_SKIP_UNREAD = 16
+TF_FLAG_NO_BASELINE = 32
 
 _STATUS = {0: "TF_OK", 1: "TF_EINVAL", 2: "TF_EBADCSR", 3: "TF_ENOMEM", 4: "TF_EHIP",
            5: "TF_EUNSUPPORTED", 6: "TF_EMISMATCH"}
@@ -43,7 +44,8 @@ class tf_csr(ctypes.Structure):
 class tf_tile_params(ctypes.Structure):
     _fields_ = [("ct_size", ctypes.c_int32), ("p", ctypes.c_int32),
                 ("fast_mem_bytes", ctypes.c_int64), ("col_slice", ctypes.c_int32),
-                ("flags", ctypes.c_uint32)]
+                ("flags", ctypes.c_uint32), ("gather_slices", ctypes.c_int32),
+                ("reserved0", ctypes.c_int32)]
 
 
 class tf_schedule_view(ctypes.Structure):
@@ -70,12 +72,19 @@ class tf_schedule_view(ctypes.Structure):
                 ("eq2_cost_max", ctypes.c_double), ("plan_seconds", ctypes.c_double),
                 ("alg_bytes", ctypes.c_int64), ("alg_bytes_unfused", ctypes.c_int64),
                 ("second_block_bytes", ctypes.c_int64), ("lds_launch_bytes", ctypes.c_int64),
-                ("n_first_rows", ctypes.c_int64)]
+                ("n_first_rows", ctypes.c_int64),
+                ("spill_slot", ctypes.POINTER(ctypes.c_int32)), ("n_direct_rows", ctypes.c_int64),
+                ("d1_slices", ctypes.c_int32), ("d1_slice_cols", ctypes.c_int32),
+                ("d1_rows", ctypes.c_int64), ("first_wavefront_streams", ctypes.c_int32),
+                ("grown_tiles", ctypes.c_int32), ("n_demoted_rows", ctypes.c_int64),
+                ("far_rows", ctypes.c_int32), ("automatic", ctypes.c_int32)]
 
 
 EXPORTS = ["tf_plan_create", "tf_plan_destroy", "tf_plan_schedule", "tf_plan_workspace",
-           "tf_gemm_spmm", "tf_spmm_spmm", "tf_unfused_gemm_spmm", "tf_unfused_spmm_spmm",
-           "tf_run_wavefront", "tf_last_error", "tf_version"]
+           "tf_gemm_spmm", "tf_spmm_spmm", "tf_unfused_gemm_spmm",
+           "tf_unfused_spmm_spmm", "tf_run_wavefront", "tf_plan_prepare_unfused", "tf_plan_workspace_unfused",
+           "tf_csr_validate", "tf_last_error", "tf_version"]
+_INT_RETURNS = [e for e in EXPORTS if e not in ("tf_last_error", "tf_version")]
 
 
 def library_path() -> str:
@@ -102,7 +111,10 @@ def load_library():
     lib.tf_spmm_spmm.argtypes = [vp, ctypes.POINTER(tf_csr), vp, vp, vp]
     lib.tf_unfused_spmm_spmm.argtypes = [vp, ctypes.POINTER(tf_csr), vp, vp, vp]
     lib.tf_run_wavefront.argtypes = [vp, i32, vp, ctypes.POINTER(tf_csr), vp, vp, vp]
-    for name in EXPORTS[:9]:
+    lib.tf_plan_prepare_unfused.argtypes = [vp]
+    lib.tf_plan_workspace_unfused.argtypes = [vp, ctypes.POINTER(vp)]
+    lib.tf_csr_validate.argtypes = [ctypes.POINTER(tf_csr)]
+    for name in _INT_RETURNS:
         getattr(lib, name).restype = ctypes.c_int
     lib.tf_last_error.restype = ctypes.c_char_p
     lib.tf_version.restype = ctypes.c_char_p
@@ -166,7 +178,8 @@ def _host_csr_struct(A, keep: list) -> tf_csr:
 
 
 def tf_plan_create(A, bcol: int, ccol: int, b_is_sparse: bool, ct_size: int = 0, p: int = 0,
-                   fast_mem_bytes: int = 0, col_slice: int = 0, flags: int = 0) -> int:
+                   fast_mem_bytes: int = 0, col_slice: int = 0, flags: int = 0,
+                   gather_slices: int = 0) -> int:
     """A: host CSR (anything with n_rows, n_cols, rowptr, colidx, vals as numpy arrays), a
     DeviceCsr, or a ready tf_csr struct.  Returns the opaque plan handle."""
     lib = load_library()
@@ -177,7 +190,7 @@ def tf_plan_create(A, bcol: int, ccol: int, b_is_sparse: bool, ct_size: int = 0,
         a = A.as_struct()
     else:
         a = _host_csr_struct(A, keep)
-    tp = tf_tile_params(ct_size, p, fast_mem_bytes, col_slice, flags)
+    tp = tf_tile_params(ct_size, p, fast_mem_bytes, col_slice, flags, gather_slices, 0)
     out = ctypes.c_void_p()
     _check(lib.tf_plan_create(ctypes.byref(a), bcol, ccol, 1 if b_is_sparse else 0,
                               ctypes.byref(tp), ctypes.byref(out)))
@@ -208,6 +221,7 @@ def tf_plan_schedule(plan: int) -> dict:
     out["wf1_unit_ptr"] = _np_copy(v.wf1_unit_ptr, nu + 1, np.int32)
     out["wf1_rows"] = _np_copy(v.wf1_rows, v.n_wf1_rows, np.int32)
     out["spill"] = _np_copy(v.spill, v.n, np.uint8)
+    out["spill_slot"] = _np_copy(v.spill_slot, v.n, np.int32)
     return out
 
 
@@ -215,6 +229,24 @@ def tf_plan_workspace(plan: int) -> int:
     out = ctypes.c_void_p()
     _check(load_library().tf_plan_workspace(plan, ctypes.byref(out)))
     return out.value or 0
+
+
+def tf_plan_workspace_unfused(plan: int) -> int:
+    out = ctypes.c_void_p()
+    _check(load_library().tf_plan_workspace_unfused(plan, ctypes.byref(out)))
+    return out.value or 0
+
+
+def tf_plan_prepare_unfused(plan: int) -> None:
+    _check(load_library().tf_plan_prepare_unfused(plan))
+
+
+def tf_csr_validate(M) -> None:
+    """M: host CSR (numpy arrays), a DeviceCsr or a tf_csr struct; raises TfError if malformed."""
+    keep: list = []
+    m = M if isinstance(M, tf_csr) else (M.as_struct() if isinstance(M, DeviceCsr)
+                                         else _host_csr_struct(M, keep))
+    _check(load_library().tf_csr_validate(ctypes.byref(m)))
 
 
 def tf_gemm_spmm(plan: int, B, C, D, stream=None) -> None:
@@ -275,6 +307,12 @@ class Plan:
 
     def workspace(self) -> int:
         return tf_plan_workspace(self.handle)
+
+    def workspace_unfused(self) -> int:
+        return tf_plan_workspace_unfused(self.handle)
+
+    def prepare_unfused(self) -> None:
+        tf_plan_prepare_unfused(self.handle)
 
     def close(self) -> None:
         if self.handle:

@@ -1,10 +1,11 @@
 // C ABI of the tile-fusion library: argument checks, device memory owned by a plan, and the
 // two-launch execution (first wavefront, then second wavefront, in stream order).
-#include <hip/hip_runtime_api.h>
+#include <hip/hip_runtime.h>
 
 #include <chrono>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -66,9 +67,19 @@ struct tf_plan {
             return d;
         }
     };
-    DevBuf tile_desc, tile_meta, tile_first;
+    DevBuf tile_desc, tile_meta, tile_first, tile_info, tile_scale, row_info, row_scale;
     PackBufs wf1, all;
-    DevBuf d1;
+    DevBuf d1;                             // fused path: one slot per spilled D1 row
+    bool has_baseline = false;             // the packed copy of all rows of A exists
+    int n_cu = 256;
+    // unfused baseline: all n rows of D1, allocated by the first unfused call (or tf_plan_prepare_unfused)
+    mutable std::mutex unf_mutex;
+    mutable DevBuf d1_unf;
+    tf::D1Layout unf_layout() const {
+        tf::D1Layout l = s.d1;
+        l.rows = n > 0 ? n : 1;
+        return l;
+    }
 };
 
 namespace {
@@ -102,6 +113,16 @@ hipError_t upload_pack(tf_plan::PackBufs &b, tf::RowPack &pk) {
     return e;
 }
 
+// column -> (slice, offset inside the slice) of a workspace: a shift and a mask; with one slice the
+// shift empties the column number and the mask keeps it
+int32_t sw_shift(const tf::D1Layout &l) {
+    if (l.n_sl == 1) return 31;
+    int32_t sh = 0;
+    while ((1 << sh) < l.sw) ++sh;
+    return sh;
+}
+int32_t sw_mask(const tf::D1Layout &l) { return l.n_sl == 1 ? 0x7fffffff : l.sw - 1; }
+
 tf::FusedLaunch fused_args(const tf_plan *p, const void *C, void *D) {
     tf::FusedLaunch a{};
     a.dtype = p->dtype;
@@ -114,38 +135,65 @@ tf::FusedLaunch fused_args(const tf_plan *p, const void *C, void *D) {
     a.tile_rows = (int32_t)tf::round_up(p->s.max_tile_rows, tf::lds_row_granule(p->b_is_sparse));
     a.s_cap = (int32_t)p->s.second_block_cap;
     a.s_in_lds = p->s.second_block_in_lds ? 1 : 0;
+    a.need_tile = p->s.n_lds_rows > 0 ? 1 : 0;
     a.lds_bytes = tf::fused_lds_bytes(p->dtype, p->b_is_sparse, a.bcol, a.ccol, a.cs,
-                                      (int)p->s.max_tile_rows, a.s_in_lds ? a.s_cap : 0);
+                                      (int)p->s.max_tile_rows, a.s_in_lds ? a.s_cap : 0, a.need_tile);
     a.tile_desc = static_cast<const tf::TileDesc *>(p->tile_desc.p);
     a.tile_meta = static_cast<const unsigned char *>(p->tile_meta.p);
     a.tile_first = static_cast<const int32_t *>(p->tile_first.p);
+    a.tile_info = static_cast<const uint32_t *>(p->tile_info.p);
+    a.tile_scale = p->s.n_direct_rows > 0 ? p->tile_scale.p : nullptr;
     a.first_stride = p->s.first_stride;
+    a.n_cu = p->n_cu;
     a.C = C;
     a.c_ldk = p->c_transposed ? 1 : a.ccol;
     a.c_ldc = p->c_transposed ? a.bcol : 1;
     a.D = D;
     a.D1 = p->d1.p;
+    a.d1_sw = p->s.d1.sw;
+    a.d1_sw_shift = sw_shift(p->s.d1);
+    a.d1_sw_mask = sw_mask(p->s.d1);
+    a.d1_slice_stride = p->s.d1.slice_stride();
     return a;
 }
 
-tf::PackedSpmmLaunch packed_args(const tf_plan *p, const tf_plan::PackBufs &b, void *D) {
+tf::PackedSpmmLaunch packed_args(const tf_plan *p, const tf_plan::PackBufs &b, const void *X,
+                                 const tf::D1Layout &lay, void *D) {
     tf::PackedSpmmLaunch w{};
     w.dtype = p->dtype;
     w.n_units = b.n_units;
     w.contiguous = b.sorted ? 0 : 1;
-    w.wide = (double)p->n * (double)p->ccol * tf::elem_size(p->dtype) >= 4294967296.0 ? 1 : 0;
+    // operand offsets inside a slice are formed in 32 bits unless the slice spans 4 GiB or more
+    w.wide = (double)lay.slice_stride() * tf::elem_size(p->dtype) >= 4294967296.0 ? 1 : 0;
     w.pack = b.dev();
-    w.X = p->d1.p;
+    w.X = X;
+    w.n_xs = lay.n_sl;
+    w.sw = lay.sw;
+    w.x_slice_stride = lay.slice_stride();
+    w.rows_per_pass = p->s.gather_r;
     w.Y = D;
     w.ccol = (int32_t)p->ccol;
     return w;
 }
 
 tf::PackedSpmmLaunch second_wavefront_args(const tf_plan *p, void *D) {
-    return packed_args(p, p->wf1, D);
+    return packed_args(p, p->wf1, p->d1.p, p->s.d1, D);
 }
 
-tf::PackedSpmmLaunch all_rows_args(const tf_plan *p, void *D) { return packed_args(p, p->all, D); }
+tf::PackedSpmmLaunch all_rows_args(const tf_plan *p, void *D) {
+    return packed_args(p, p->all, p->d1_unf.p, p->unf_layout(), D);
+}
+
+// The unfused baseline's workspace holds all n rows of D1; it is allocated when first needed.
+tf_status prepare_unfused(const tf_plan *p) {
+    if (!p->has_baseline)
+        return fail(TF_EINVAL, "the plan was built with TF_FLAG_NO_BASELINE");
+    std::lock_guard<std::mutex> lock(p->unf_mutex);
+    if (p->d1_unf.p) return TF_OK;
+    hipError_t e = p->d1_unf.alloc((size_t)p->unf_layout().elements() * tf::elem_size(p->dtype));
+    if (e != hipSuccess) return hip_fail(e, "allocating the workspace of the unfused baseline");
+    return TF_OK;
+}
 
 tf_status check_exec(const tf_plan *p, int want_sparse, const void *C, const void *D) {
     if (!p || !C || !D) return fail(TF_EINVAL, "null argument");
@@ -164,6 +212,100 @@ tf_status check_sparse_b(const tf_plan *p, const tf_csr *B) {
     if (B->dtype != p->dtype) return fail(TF_EMISMATCH, "B has a different element type than A");
     if (B->n_rows != p->n || B->n_cols != p->bcol)
         return fail(TF_EMISMATCH, "B is not n x bCol for this plan");
+    return TF_OK;
+}
+
+// Shape of the plain product D1 = B C (k_gemm): the column slice is as wide as one wave's
+// accumulators allow, narrowed until the C slice fits the LDS.  False if it never does.
+bool gemm_shape(const tf_plan *p, tf::GemmLaunch &g) {
+    g.dtype = p->dtype;
+    g.n = p->n;
+    g.bcol = (int32_t)p->bcol;
+    g.ccol = (int32_t)p->ccol;
+    g.cs = p->ccol > tf::kMaxMfmaSliceCols ? tf::kMaxMfmaSliceCols : (int32_t)p->ccol;
+    while (g.cs > 16 && tf::lds_fixed_bytes(p->dtype, 0, g.bcol, g.cs) > p->lds_per_cu)
+        g.cs = (g.cs - 1) / 16 * 16;
+    if (tf::lds_fixed_bytes(p->dtype, 0, g.bcol, g.cs) > p->lds_per_cu) return false;
+    g.n_slices = (int32_t)((p->ccol + g.cs - 1) / g.cs);
+    g.c_ldk = p->c_transposed ? 1 : g.ccol;
+    g.c_ldc = p->c_transposed ? g.bcol : 1;
+    return true;
+}
+void gemm_workspace(tf::GemmLaunch &g, void *ws, const tf::D1Layout &lay) {
+    g.D1 = ws;
+    g.d1_sw = lay.sw;
+    g.d1_sw_shift = sw_shift(lay);
+    g.d1_sw_mask = sw_mask(lay);
+    g.d1_slice_stride = lay.slice_stride();
+}
+tf::CsrSpmmLaunch csr_spmm_args(const tf_plan *p, const tf_csr *B, const void *C, void *ws,
+                                const tf::D1Layout &lay) {
+    tf::CsrSpmmLaunch f{};
+    f.dtype = p->dtype;
+    f.rows_per_wg = tf::kCsrRowsPerWg;
+    f.n_rows = p->n;
+    f.S.rowptr = B->rowptr;
+    f.S.colidx = B->colidx;
+    f.S.vals = B->vals;
+    f.X = C;
+    f.Y = ws;
+    f.ccol = (int32_t)p->ccol;
+    f.y_sw = lay.sw;
+    f.y_sw_shift = sw_shift(lay);
+    f.y_sw_mask = sw_mask(lay);
+    f.y_slice_stride = lay.slice_stride();
+    return f;
+}
+
+// First wavefront into the workspace `ws` (the plan's own, or the static one).  A plan none of
+// whose fused rows reads the LDS tile runs it without tiles, as the plain first operation whose
+// rows go where their info words say; every other plan runs the tiled fused kernel.
+tf_status first_wavefront_dense(const tf_plan *p, const void *B, const void *C, void *D, void *ws,
+                                void *stream) {
+    tf::GemmLaunch g{};
+    if (p->s.streaming && gemm_shape(p, g)) {
+        g.B = B;
+        g.C = C;
+        gemm_workspace(g, ws, p->s.d1);
+        g.row_info = static_cast<const uint32_t *>(p->row_info.p);
+        g.row_scale = p->s.n_direct_rows > 0 ? p->row_scale.p : nullptr;
+        g.D = D;
+        const int e = tf::launch_gemm(g, stream);
+        if (e) return hip_fail((hipError_t)e, "launching the first wavefront");
+        return TF_OK;
+    }
+    tf::FusedLaunch a = fused_args(p, C, D);
+    a.B = B;
+    a.D1 = ws;
+    const int e = tf::launch_fused_gemm_spmm(a, stream);
+    if (e) return hip_fail((hipError_t)e, "launching the first wavefront");
+    return TF_OK;
+}
+tf_status first_wavefront_sparse(const tf_plan *p, const tf_csr *B, const void *C, void *D, void *ws,
+                                 void *stream) {
+    int e;
+    if (p->s.streaming) {
+        tf::CsrSpmmLaunch f = csr_spmm_args(p, B, C, ws, p->s.d1);
+        f.row_info = static_cast<const uint32_t *>(p->row_info.p);
+        f.row_scale = p->s.n_direct_rows > 0 ? p->row_scale.p : nullptr;
+        f.D = D;
+        e = tf::launch_csr_spmm(f, stream);
+    } else {
+        tf::FusedLaunch a = fused_args(p, C, D);
+        a.Bs.rowptr = B->rowptr;
+        a.Bs.colidx = B->colidx;
+        a.Bs.vals = B->vals;
+        a.D1 = ws;
+        e = tf::launch_fused_spmm_spmm(a, stream);
+    }
+    if (e) return hip_fail((hipError_t)e, "launching the first wavefront");
+    return TF_OK;
+}
+tf_status second_wavefront(const tf_plan *p, void *D, void *ws, void *stream) {
+    tf::PackedSpmmLaunch w = second_wavefront_args(p, D);
+    w.X = ws;
+    const int e = tf::launch_packed_spmm(w, stream);
+    if (e) return hip_fail((hipError_t)e, "launching the second wavefront");
     return TF_OK;
 }
 
@@ -206,7 +348,7 @@ tf_status tf_plan_create(const tf_csr *A, int64_t bCol, int64_t cCol, int32_t b_
     if (bCol <= 0 || cCol <= 0) return fail(TF_EINVAL, "bCol and cCol must be positive");
     if (bCol >= (int64_t(1) << 31) || cCol > (1 << 20))
         return fail(TF_EUNSUPPORTED, "bCol or cCol too large");
-    if (tp && (tp->ct_size < 0 || tp->p < 0 || tp->fast_mem_bytes < 0))
+    if (tp && (tp->ct_size < 0 || tp->p < 0 || tp->fast_mem_bytes < 0 || tp->gather_slices < 0))
         return fail(TF_EINVAL, "negative tile parameter");
 
     const bool schedule_only = tp && (tp->flags & TF_FLAG_SCHEDULE_ONLY);
@@ -271,7 +413,9 @@ tf_status tf_plan_create(const tf_csr *A, int64_t bCol, int64_t cCol, int32_t b_
         in.p = tp ? tp->p : 0;
         in.col_slice = tp ? tp->col_slice : 0;
         in.flags = tp ? tp->flags : 0;
+        in.gather_slices = tp ? tp->gather_slices : 0;
         in.n_cu = schedule_only ? 256 : device_compute_units();
+        p->n_cu = in.n_cu;
         const int64_t lds_limit = schedule_only ? 160 * 1024 : device_lds_limit();
         in.fast_mem_bytes = (tp && tp->fast_mem_bytes > 0) ? tp->fast_mem_bytes : lds_limit;
         if (!schedule_only && in.fast_mem_bytes > lds_limit) in.fast_mem_bytes = lds_limit;
@@ -286,13 +430,15 @@ tf_status tf_plan_create(const tf_csr *A, int64_t bCol, int64_t cCol, int32_t b_
             *out = p;
             return TF_OK;
         }
-        tf::build_baseline_pack(in, p->s);
+        p->has_baseline = !(tp && (tp->flags & TF_FLAG_NO_BASELINE));
+        if (p->has_baseline) tf::build_baseline_pack(in, p->s);
         p->lds_per_cu = lds_limit;
         // the launch must fit the device whatever the schedule's own estimate said
         auto launch_lds = [&]() {
             return tf::fused_lds_bytes(p->dtype, p->b_is_sparse, (int)bCol, (int)cCol, p->s.col_slice,
                                        (int)p->s.max_tile_rows,
-                                       p->s.second_block_in_lds ? (int)p->s.second_block_cap : 0);
+                                       p->s.second_block_in_lds ? (int)p->s.second_block_cap : 0,
+                                       p->s.n_lds_rows > 0);
         };
         if (launch_lds() > lds_limit) p->s.second_block_in_lds = false;
         if (launch_lds() > lds_limit)
@@ -306,13 +452,47 @@ tf_status tf_plan_create(const tf_csr *A, int64_t bCol, int64_t cCol, int32_t b_
         p->s.tile_meta.reset();
         ok(up(p->tile_first, p->s.tile_first));
         std::vector<int32_t>().swap(p->s.tile_first);
+        ok(up(p->tile_info, p->s.tile_info));
+        std::vector<uint32_t>().swap(p->s.tile_info);
+        ok(up(p->tile_scale, p->s.tile_scale));
+        tf::RawVec<unsigned char>().swap(p->s.tile_scale);
+        if (p->s.streaming) {
+            ok(up(p->row_info, p->s.row_info));
+            std::vector<uint32_t>().swap(p->s.row_info);
+            ok(up(p->row_scale, p->s.row_scale));
+            tf::RawVec<unsigned char>().swap(p->s.row_scale);
+        }
         ok(upload_pack(p->wf1, p->s.wf1));
-        ok(upload_pack(p->all, p->s.all));
-        ok(p->d1.alloc((size_t)n * cCol * es));
+        if (p->has_baseline) ok(upload_pack(p->all, p->s.all));
+        ok(p->d1.alloc((size_t)p->s.d1.elements() * es));
         if (e != hipSuccess) return hip_fail(e, "allocating the plan's device memory");
         guard.p = nullptr;
         *out = p;
         return TF_OK;
+    } catch (const std::bad_alloc &) {
+        return fail(TF_ENOMEM, "out of host memory");
+    }
+}
+
+tf_status tf_csr_validate(const tf_csr *M) {
+    if (!M || !M->rowptr || M->n_rows < 0 || M->n_cols < 0 || M->nnz < 0 ||
+        (M->nnz > 0 && !M->colidx))
+        return fail(TF_EINVAL, "null argument or negative size");
+    if (M->nnz >= (int64_t(1) << 31)) return fail(TF_EUNSUPPORTED, "indices are 32 bit");
+    try {
+        std::vector<int32_t> h_rowptr, h_colidx;
+        const int32_t *rowptr = M->rowptr, *colidx = M->colidx;
+        if (M->on_device) {
+            h_rowptr.resize((size_t)M->n_rows + 1);
+            h_colidx.resize((size_t)M->nnz);
+            hipError_t e = hipMemcpy(h_rowptr.data(), M->rowptr, (M->n_rows + 1) * 4, hipMemcpyDeviceToHost);
+            if (e == hipSuccess && M->nnz)
+                e = hipMemcpy(h_colidx.data(), M->colidx, M->nnz * 4, hipMemcpyDeviceToHost);
+            if (e != hipSuccess) return hip_fail(e, "copying the matrix to the host");
+            rowptr = h_rowptr.data();
+            colidx = h_colidx.data();
+        }
+        return check_csr_host(M->n_rows, M->n_cols, M->nnz, rowptr, colidx);
     } catch (const std::bad_alloc &) {
         return fail(TF_ENOMEM, "out of host memory");
     }
@@ -374,7 +554,18 @@ tf_status tf_plan_schedule(const tf_plan *p, tf_schedule_view *v) {
         p->schedule_only
             ? 0
             : tf::fused_lds_bytes(p->dtype, p->b_is_sparse, (int)p->bcol, (int)p->ccol, s.col_slice,
-                                  (int)s.max_tile_rows, s.second_block_in_lds ? (int)s.second_block_cap : 0);
+                                  (int)s.max_tile_rows, s.second_block_in_lds ? (int)s.second_block_cap : 0,
+                                  s.n_lds_rows > 0);
+    v->spill_slot = s.spill_slot.data();
+    v->n_direct_rows = s.n_direct_rows;
+    v->d1_slices = s.d1.n_sl;
+    v->d1_slice_cols = s.d1.sw;
+    v->d1_rows = s.d1.rows;
+    v->first_wavefront_streams = s.streaming ? 1 : 0;
+    v->grown_tiles = s.grown_tiles ? 1 : 0;
+    v->n_demoted_rows = s.n_demoted_rows;
+    v->far_rows = s.far_rows ? 1 : 0;
+    v->automatic = s.automatic ? 1 : 0;
     return TF_OK;
 }
 
@@ -384,17 +575,25 @@ tf_status tf_plan_workspace(const tf_plan *p, void **d1_device) {
     return TF_OK;
 }
 
+tf_status tf_plan_prepare_unfused(const tf_plan *p) {
+    if (!p) return fail(TF_EINVAL, "null argument");
+    if (p->schedule_only) return fail(TF_EINVAL, "the plan was built with TF_FLAG_SCHEDULE_ONLY");
+    return prepare_unfused(p);
+}
+
+tf_status tf_plan_workspace_unfused(const tf_plan *p, void **d1_device) {
+    if (!p || !d1_device) return fail(TF_EINVAL, "null argument");
+    *d1_device = p->d1_unf.p;
+    return TF_OK;
+}
+
 tf_status tf_gemm_spmm(const tf_plan *p, const void *B, const void *C, void *D, void *stream) {
     tf_status st = check_exec(p, 0, C, D);
     if (st != TF_OK) return st;
     if (!B || !aligned16(B)) return fail(TF_EINVAL, "B must be a 16-byte aligned device pointer");
-    tf::FusedLaunch a = fused_args(p, C, D);
-    a.B = B;
-    int e = tf::launch_fused_gemm_spmm(a, stream);
-    if (e) return hip_fail((hipError_t)e, "launching the first wavefront");
-    e = tf::launch_packed_spmm(second_wavefront_args(p, D), stream);
-    if (e) return hip_fail((hipError_t)e, "launching the second wavefront");
-    return TF_OK;
+    st = first_wavefront_dense(p, B, C, D, p->d1.p, stream);
+    if (st != TF_OK) return st;
+    return second_wavefront(p, D, p->d1.p, stream);
 }
 
 tf_status tf_spmm_spmm(const tf_plan *p, const tf_csr *B, const void *C, void *D, void *stream) {
@@ -402,15 +601,9 @@ tf_status tf_spmm_spmm(const tf_plan *p, const tf_csr *B, const void *C, void *D
     if (st != TF_OK) return st;
     st = check_sparse_b(p, B);
     if (st != TF_OK) return st;
-    tf::FusedLaunch a = fused_args(p, C, D);
-    a.Bs.rowptr = B->rowptr;
-    a.Bs.colidx = B->colidx;
-    a.Bs.vals = B->vals;
-    int e = tf::launch_fused_spmm_spmm(a, stream);
-    if (e) return hip_fail((hipError_t)e, "launching the first wavefront");
-    e = tf::launch_packed_spmm(second_wavefront_args(p, D), stream);
-    if (e) return hip_fail((hipError_t)e, "launching the second wavefront");
-    return TF_OK;
+    st = first_wavefront_sparse(p, B, C, D, p->d1.p, stream);
+    if (st != TF_OK) return st;
+    return second_wavefront(p, D, p->d1.p, stream);
 }
 
 tf_status tf_run_wavefront(const tf_plan *p, int32_t wavefront, const void *B_dense,
@@ -418,29 +611,16 @@ tf_status tf_run_wavefront(const tf_plan *p, int32_t wavefront, const void *B_de
     if (!p) return fail(TF_EINVAL, "null argument");
     tf_status st = check_exec(p, p->b_is_sparse, C, D);
     if (st != TF_OK) return st;
-    if (wavefront == 1) {
-        int e = tf::launch_packed_spmm(second_wavefront_args(p, D), stream);
-        if (e) return hip_fail((hipError_t)e, "launching the second wavefront");
-        return TF_OK;
-    }
+    if (wavefront == 1) return second_wavefront(p, D, p->d1.p, stream);
     if (wavefront != 0) return fail(TF_EINVAL, "wavefront must be 0 or 1");
-    tf::FusedLaunch a = fused_args(p, C, D);
-    int e;
     if (p->b_is_sparse) {
         st = check_sparse_b(p, B_csr);
         if (st != TF_OK) return st;
-        a.Bs.rowptr = B_csr->rowptr;
-        a.Bs.colidx = B_csr->colidx;
-        a.Bs.vals = B_csr->vals;
-        e = tf::launch_fused_spmm_spmm(a, stream);
-    } else {
-        if (!B_dense || !aligned16(B_dense))
-            return fail(TF_EINVAL, "B must be a 16-byte aligned device pointer");
-        a.B = B_dense;
-        e = tf::launch_fused_gemm_spmm(a, stream);
+        return first_wavefront_sparse(p, B_csr, C, D, p->d1.p, stream);
     }
-    if (e) return hip_fail((hipError_t)e, "launching the first wavefront");
-    return TF_OK;
+    if (!B_dense || !aligned16(B_dense))
+        return fail(TF_EINVAL, "B must be a 16-byte aligned device pointer");
+    return first_wavefront_dense(p, B_dense, C, D, p->d1.p, stream);
 }
 
 tf_status tf_unfused_gemm_spmm(const tf_plan *p, const void *B, const void *C, void *D,
@@ -449,22 +629,13 @@ tf_status tf_unfused_gemm_spmm(const tf_plan *p, const void *B, const void *C, v
     if (st != TF_OK) return st;
     if (!B || !aligned16(B)) return fail(TF_EINVAL, "B must be a 16-byte aligned device pointer");
     tf::GemmLaunch g{};
-    g.dtype = p->dtype;
-    g.n = p->n;
-    g.bcol = (int32_t)p->bcol;
-    g.ccol = (int32_t)p->ccol;
-    // as wide as one wave's accumulators allow, narrowed until the C slice fits the LDS
-    g.cs = p->ccol > tf::kMaxMfmaSliceCols ? tf::kMaxMfmaSliceCols : (int32_t)p->ccol;
-    while (g.cs > 16 && tf::lds_fixed_bytes(p->dtype, 0, g.bcol, g.cs) > p->lds_per_cu)
-        g.cs = (g.cs - 1) / 16 * 16;
-    if (tf::lds_fixed_bytes(p->dtype, 0, g.bcol, g.cs) > p->lds_per_cu)
+    if (!gemm_shape(p, g))
         return fail(TF_EUNSUPPORTED, "bCol is too large for the C slice of the unfused GeMM to fit LDS");
-    g.n_slices = (int32_t)((p->ccol + g.cs - 1) / g.cs);
+    st = prepare_unfused(p);
+    if (st != TF_OK) return st;
     g.B = B;
     g.C = C;
-    g.c_ldk = p->c_transposed ? 1 : g.ccol;
-    g.c_ldc = p->c_transposed ? g.bcol : 1;
-    g.D1 = p->d1.p;
+    gemm_workspace(g, p->d1_unf.p, p->unf_layout());
     int e = tf::launch_gemm(g, stream);
     if (e) return hip_fail((hipError_t)e, "launching the GeMM");
     e = tf::launch_packed_spmm(all_rows_args(p, D), stream);
@@ -478,16 +649,9 @@ tf_status tf_unfused_spmm_spmm(const tf_plan *p, const tf_csr *B, const void *C,
     if (st != TF_OK) return st;
     st = check_sparse_b(p, B);
     if (st != TF_OK) return st;
-    tf::CsrSpmmLaunch f{};
-    f.dtype = p->dtype;
-    f.rows_per_wg = tf::kCsrRowsPerWg;
-    f.n_rows = p->n;
-    f.S.rowptr = B->rowptr;
-    f.S.colidx = B->colidx;
-    f.S.vals = B->vals;
-    f.X = C;
-    f.Y = p->d1.p;
-    f.ccol = (int32_t)p->ccol;
+    st = prepare_unfused(p);
+    if (st != TF_OK) return st;
+    tf::CsrSpmmLaunch f = csr_spmm_args(p, B, C, p->d1_unf.p, p->unf_layout());
     int e = tf::launch_csr_spmm(f, stream);
     if (e) return hip_fail((hipError_t)e, "launching the first SpMM");
     e = tf::launch_packed_spmm(all_rows_args(p, D), stream);

@@ -296,10 +296,10 @@ TileBlock pack_tile(const int32_t *rowptr, const int32_t *colidx, const unsigned
 
 // Units of a packed row list of `count` rows: a unit is one workgroup; short lists are cut into
 // smaller units (down to one row per lane group) so that they still spread over the machine.
-static PackRules pack_rules(const InspectorInput &in, int64_t count) {
+static PackRules pack_rules(const InspectorInput &in, int64_t count, int sw) {
     const int v = vec_elems(in.dtype);
     const int vv = in.ccol % v == 0 ? v : 1;
-    const int groups = kSpmmThreads / lane_group((int)in.ccol, vv);
+    const int groups = kSpmmThreads / lane_group(sw, vv);
     const int64_t want = (count + 1023) / 1024;
     return PackRules{(int)std::min<int64_t>(kUnitRows, std::max<int64_t>(groups, want)), kUnitSlots,
                      groups};
@@ -352,9 +352,27 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
             lds_ldl(in.dtype, in.b_is_sparse, (int)width) * es + s.lds_meta_bytes_per_row + b_stage;
     };
     model(cs);
+    // ---- the caller left the tiling to the library ----------------------------------------
+    // (no tile size, no tile count, no flag that fixes the kind of tiles).  Then: a quarter of the
+    // compute units as the wanted number of tiles (with all of them a small matrix gets tiles of a
+    // handful of rows, which fuse nothing); for a dense B whose C operands sit in registers, half
+    // of the LDS per tile when that still holds kWantedTileRows rows, so that two workgroups share
+    // a compute unit; consecutive or graph-grown tiles, whichever moves fewer bytes; and fused rows
+    // that would keep the whole tile machinery alive for next to no work are left to the second
+    // wavefront (see below).
+    const bool automatic = in.ct_size == 0 && in.p == 0 &&
+                           !(in.flags & (TF_FLAG_REORDER | TF_FLAG_NO_SPLIT));
+    s.automatic = automatic;
+    if (automatic && !in.b_is_sparse && in.fast_mem_bytes >= 128 * 1024) {
+        const bool c_regs = c_in_registers(in.dtype, mfma_blocks((int)cs),
+                                           mfma_ksteps_special(in.dtype, (int)in.bcol, (int)in.ccol, (int)cs));
+        const int64_t half = in.fast_mem_bytes / 2;
+        if (c_regs && s.lds_fixed_bytes + kWantedTileRows * s.lds_bytes_per_row <= half)
+            s.fast_mem_bytes = half;
+    }
     // ---- step 1: tile size --------------------------------------------------------------
     const int64_t ct = in.ct_size > 0 ? in.ct_size : 2048;
-    const int64_t p = in.p > 0 ? in.p : 32;
+    const int64_t p = in.p > 0 ? in.p : (automatic ? std::max(1, in.n_cu / 4) : 32);
     int64_t t = ct;
     if (n > 0 && (n + ct - 1) / ct < p) t = (n + p - 1) / p;
     if (t < 1) t = 1;
@@ -398,14 +416,20 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
     // ---- tiles: lists of first-operation rows -------------------------------------------
     // first_rows holds the rows tile after tile; tile_first_ptr delimits the tiles.
     const bool allow_split = !(in.flags & TF_FLAG_NO_SPLIT);
-    s.first_rows.resize((size_t)n);
-    s.tile_first_ptr.assign(1, 0);
-    if (in.flags & TF_FLAG_REORDER) {
+    struct Tiling {
+        std::vector<int32_t> first_rows, tile_first_ptr;
+        int64_t n_coarse = 0;
+        bool grown = false;
+    };
+    auto make_grown = [&](Tiling &tl) {
         // Tiles grown along the dependence graph: as many rows as fit the fast memory (and at
         // most t), collected breadth first from the lowest row not yet in a tile by following
         // each row's column indices; when a search runs dry the tile goes on from the next
         // free row.  Rows inside a tile are kept in ascending order.
-        int64_t cap = std::min<int64_t>(t, 65536);
+        tl.grown = true;
+        tl.first_rows.resize((size_t)n);
+        tl.tile_first_ptr.assign(1, 0);
+        int64_t cap = std::min<int64_t>(automatic ? 65536 : t, 65536);
         while (cap > 1 && tile_footprint(s, cap) > s.fast_mem_bytes) --cap;
         cap = std::max<int64_t>(1, cap / s.lds_row_granule * s.lds_row_granule);
         if (tile_footprint(s, cap) > s.fast_mem_bytes) cap = 1;
@@ -446,24 +470,117 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
                     }
                 }
             }
-            std::copy(queue.begin(), queue.end(), s.first_rows.begin() + filled);
+            std::copy(queue.begin(), queue.end(), tl.first_rows.begin() + filled);
             filled += (int64_t)queue.size();
-            s.tile_first_ptr.push_back((int32_t)filled);
+            tl.tile_first_ptr.push_back((int32_t)filled);
         }
-        s.n_coarse_tiles = (int64_t)s.tile_first_ptr.size() - 1;
-        for_each_item(s.n_coarse_tiles, host_threads(in.nnz, s.n_coarse_tiles, 16), [&](int64_t vt) {
-            std::sort(s.first_rows.begin() + s.tile_first_ptr[vt], s.first_rows.begin() + s.tile_first_ptr[vt + 1]);
+        tl.n_coarse = (int64_t)tl.tile_first_ptr.size() - 1;
+        for_each_item(tl.n_coarse, host_threads(in.nnz, tl.n_coarse, 16), [&](int64_t vt) {
+            std::sort(tl.first_rows.begin() + tl.tile_first_ptr[vt], tl.first_rows.begin() + tl.tile_first_ptr[vt + 1]);
         });
-    } else {
+    };
+    auto make_consecutive = [&](Tiling &tl) {
         // Algorithm 1: uniform tiles of t consecutive rows (step 1), halved until they fit (step 2)
+        tl.first_rows.resize((size_t)n);
+        tl.tile_first_ptr.assign(1, 0);
         std::vector<Range> tiles;
         for (int64_t i0 = 0; i0 < n; i0 += t) {
-            ++s.n_coarse_tiles;
+            ++tl.n_coarse;
             split_tile(s, Range{i0, std::min(n, i0 + t)}, allow_split, tiles);
         }
-        std::iota(s.first_rows.begin(), s.first_rows.end(), 0);
-        for (const Range &r : tiles) s.tile_first_ptr.push_back((int32_t)r.i1);
+        std::iota(tl.first_rows.begin(), tl.first_rows.end(), 0);
+        for (const Range &r : tiles) tl.tile_first_ptr.push_back((int32_t)r.i1);
+    };
+    // What a tiling is worth, without packing anything: the stored entries of the rows it fuses
+    // (all of them, and those of rows that are not direct rows) and the number of D1 rows it spills.
+    struct Worth {
+        int64_t fused_nnz = 0, lds_nnz = 0, lds_rows = 0, spill_rows = 0;
+    };
+    auto evaluate = [&](const Tiling &tl) {
+        const int64_t ntl = (int64_t)tl.tile_first_ptr.size() - 1;
+        std::vector<int32_t> tile_of((size_t)n);
+        for (int64_t vt = 0; vt < ntl; ++vt)
+            for (int64_t q = tl.tile_first_ptr[vt]; q < tl.tile_first_ptr[vt + 1]; ++q)
+                tile_of[tl.first_rows[q]] = (int32_t)vt;
+        std::vector<uint8_t> spilled((size_t)n, 0);
+        std::vector<Worth> part((size_t)ntl);
+        for_each_item(ntl, host_threads(in.nnz, ntl, 16), [&](int64_t vt) {
+            Worth &w = part[(size_t)vt];
+            for (int64_t fq = tl.tile_first_ptr[vt]; fq < tl.tile_first_ptr[vt + 1]; ++fq) {
+                const int64_t j = tl.first_rows[fq];
+                const int64_t k0 = in.rowptr[j], k1 = in.rowptr[j + 1];
+                bool inside = k1 - k0 < 32768;
+                for (int64_t q = k0; inside && q < k1; ++q) inside = tile_of[in.colidx[q]] == (int32_t)vt;
+                if (inside) {
+                    w.fused_nnz += k1 - k0;
+                    if (!(k1 == k0 || (k1 - k0 == 1 && in.colidx[k0] == (int32_t)j))) {
+                        w.lds_nnz += k1 - k0;
+                        ++w.lds_rows;
+                    }
+                } else {
+                    for (int64_t q = k0; q < k1; ++q) {
+                        uint8_t *m = &spilled[(size_t)in.colidx[q]];
+                        if (!__atomic_load_n(m, __ATOMIC_RELAXED)) __atomic_store_n(m, (uint8_t)1, __ATOMIC_RELAXED);
+                    }
+                }
+            }
+        });
+        Worth w;
+        for (const Worth &pw : part) {
+            w.fused_nnz += pw.fused_nnz;
+            w.lds_nnz += pw.lds_nnz;
+            w.lds_rows += pw.lds_rows;
+        }
+        w.spill_rows = std::accumulate(spilled.begin(), spilled.end(), (int64_t)0);
+        return w;
+    };
+    // Rows that reach far (graphs): mean distance, over a sample of the entries, between a row and
+    // the columns it holds, in bytes of D1 rows, against the 4 MiB of one XCD's L2.
+    bool far_rows = false;
+    if (n > 0 && in.nnz > 0) {
+        const int64_t stride = std::max<int64_t>(1, n / 65536);
+        double dist = 0.0;
+        int64_t cnt = 0;
+        for (int64_t j = 0; j < n; j += stride)
+            for (int64_t q = in.rowptr[j]; q < in.rowptr[j + 1]; ++q) {
+                dist += std::abs((double)in.colidx[q] - (double)j);
+                ++cnt;
+            }
+        far_rows = cnt > 0 && dist / (double)cnt * (double)in.ccol * es > 4.0 * 1048576.0;
     }
+    s.far_rows = far_rows;
+    bool demote_lds_rows = false;
+    Tiling tiling;
+    if (in.flags & TF_FLAG_REORDER) {
+        make_grown(tiling);
+    } else {
+        make_consecutive(tiling);
+        if (automatic && in.nnz > 0) {
+            Worth w = evaluate(tiling);
+            // consecutive tiles that fuse less than half of the work of a matrix whose rows stay
+            // near the diagonal (a stencil in natural ordering): try tiles grown along the graph
+            // and keep them if they spill fewer D1 rows, i.e. move fewer bytes
+            if (!far_rows && 2 * w.fused_nnz < in.nnz) {
+                Tiling grown;
+                make_grown(grown);
+                const Worth wg = evaluate(grown);
+                if (wg.spill_rows < w.spill_rows) {
+                    tiling = std::move(grown);
+                    w = wg;
+                }
+            }
+            // Fused rows that read the LDS tile make every workgroup keep a tile in LDS and pass
+            // two barriers per tile.  When they hold under 2 % of the entries that machinery costs
+            // more than the D1 round trip it saves (measured on the graph configurations: a
+            // handful of such rows, first wavefront 0.44 ms with tiles against 0.31 ms without):
+            // they are left to the second wavefront and the first wavefront streams.
+            demote_lds_rows = w.lds_rows > 0 && 50 * w.lds_nnz < in.nnz;
+        }
+    }
+    s.first_rows = std::move(tiling.first_rows);
+    s.tile_first_ptr = std::move(tiling.tile_first_ptr);
+    s.n_coarse_tiles = tiling.n_coarse;
+    s.grown_tiles = tiling.grown;
     const int64_t nt = (int64_t)s.tile_first_ptr.size() - 1;
     for (int64_t vt = 0; vt < nt; ++vt) {
         const int64_t rows = s.tile_first_ptr[vt + 1] - s.tile_first_ptr[vt];
@@ -509,11 +626,17 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
         s.first_rows.resize((size_t)kept);
     }
     std::vector<int32_t> tile_of((size_t)n), local_of((size_t)n, 0);
+    // kept[row]: the tile produces the D1 row (always, unless unread rows are skipped);
+    // direct_kind[row]: 1 = the row of D is the D1 row times its only entry, the diagonal one;
+    // 2 = the row of D is empty; both leave from the registers that hold the D1 row
+    std::vector<uint8_t> kept((size_t)n, 0), direct_kind((size_t)n, 0);
     for (int64_t vt = 0; vt < nt; ++vt) {
         for (int64_t q = member_ptr[vt]; q < member_ptr[vt + 1]; ++q)
             tile_of[member_rows[q]] = (int32_t)vt;
-        for (int64_t q = s.tile_first_ptr[vt]; q < s.tile_first_ptr[vt + 1]; ++q)
+        for (int64_t q = s.tile_first_ptr[vt]; q < s.tile_first_ptr[vt + 1]; ++q) {
             local_of[s.first_rows[q]] = (int32_t)(q - s.tile_first_ptr[vt]);
+            kept[s.first_rows[q]] = 1;
+        }
     }
     std::vector<int32_t> seen((size_t)n, -1);      // Eq. 2: distinct columns per tile
     // Per tile: which of its rows are fused, and their packed block.  Tiles are independent (a fused
@@ -521,8 +644,8 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
     // lets several host threads share the tiles of a large matrix; the results are put together
     // in tile order afterwards, so the schedule does not depend on the number of threads.
     struct TileResult {
-        std::vector<int32_t> wf1;
-        int64_t tile_nnz = 0, uc = 0, nj = 0;
+        std::vector<int32_t> wf1, direct;
+        int64_t tile_nnz = 0, uc = 0, nj = 0, demoted = 0;
     };
     std::vector<TileResult> res((size_t)nt);
     auto classify = [&](int64_t vt) {
@@ -539,8 +662,19 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
                     break;
                 }
             }
+            const int64_t ln = in.rowptr[j + 1] - in.rowptr[j];
+            const bool direct = kept[j] && (ln == 0 || (ln == 1 && in.colidx[in.rowptr[j]] == (int32_t)j));
+            if (inside && demote_lds_rows && !direct) {
+                inside = false;
+                ++tr.demoted;
+            }
             if (inside) {
-                tile_rows.push_back((int32_t)j);
+                if (direct) {
+                    direct_kind[j] = ln == 0 ? 2 : 1;
+                    tr.direct.push_back((int32_t)j);
+                } else {
+                    tile_rows.push_back((int32_t)j);
+                }
                 for (int64_t q = in.rowptr[j]; q < in.rowptr[j + 1]; ++q) {
                     const int32_t c = in.colidx[q];
                     if (seen[c] != (int32_t)vt) {
@@ -553,7 +687,7 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
                 tr.wf1.push_back((int32_t)j);
             }
         }
-        tr.nj = (int64_t)tile_rows.size();
+        tr.nj = (int64_t)(tile_rows.size() + tr.direct.size());
         blocks[(size_t)vt] = pack_tile(in.rowptr, in.colidx, vals, es, tile_rows,
                                        [&](int32_t c) { return local_of[c] * pitch16; });
     };
@@ -565,6 +699,10 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
         s.tile_second_ptr[vt] = (int32_t)s.second_rows.size();
         s.second_rows.insert(s.second_rows.end(), blocks[(size_t)vt].rows.begin(),
                              blocks[(size_t)vt].rows.end());
+        s.second_rows.insert(s.second_rows.end(), tr.direct.begin(), tr.direct.end());
+        s.n_demoted_rows += tr.demoted;
+        s.n_lds_rows += (int64_t)blocks[(size_t)vt].rows.size();
+        s.n_direct_rows += (int64_t)tr.direct.size();
         // Eq. 2 (diagnostic): (nz + uc + t + |J|) * cCol + idx, counted in elements; for a dense B
         // the tile's rows x bCol block of B is added to nz, a sparse B is unknown here.
         const double nz = (double)tr.tile_nnz + (in.b_is_sparse ? 0.0 : (double)rows * in.bcol);
@@ -574,7 +712,7 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
     }
     s.tile_second_ptr[nt] = (int32_t)s.second_rows.size();
     s.n_fused_rows = (int64_t)s.second_rows.size();
-    if (!(in.flags & TF_FLAG_REORDER) && !std::is_sorted(wf1.begin(), wf1.end())) std::sort(wf1.begin(), wf1.end());
+    if (!s.grown_tiles && !std::is_sorted(wf1.begin(), wf1.end())) std::sort(wf1.begin(), wf1.end());
 
     // ---- spill set ----------------------------------------------------------------------
     // (several threads may mark the same row: every one of them stores the same byte)
@@ -588,10 +726,69 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
         }
     });
     s.n_spill_rows = std::accumulate(s.spill.begin(), s.spill.end(), (int64_t)0);
+    if (s.n_spill_rows > (int64_t)kInfoSlotMask) {
+        err = "more than 2^29 D1 rows cross tiles";
+        return TF_EUNSUPPORTED;
+    }
+    // Only the rows in the spill set reach device memory (one barrier: nothing else crosses tiles),
+    // so the workspace has one slot per such row, in row order.
+    s.spill_slot.assign((size_t)n, -1);
+    {
+        int32_t slot = 0;
+        for (int64_t i = 0; i < n; ++i)
+            if (s.spill[(size_t)i]) s.spill_slot[(size_t)i] = slot++;
+    }
+    // ---- layout of the workspace = column slices of the gather kernel ---------------------
+    // On a matrix whose rows reach far (a graph) every XCD's L2 sees the same hot rows of D1 and
+    // holds them all, whole: the eight caches together are worth one.  With n_sl slices each XCD
+    // gathers sw-wide pieces of the rows, so the hot set is spread over the caches, at the price of
+    // reading the packed entries of A once per slice.  Matrices whose rows stay near the diagonal
+    // (stencils, bands) keep one slice: their operands are in the L2 anyway.
+    {
+        const int vv = in.ccol % v == 0 ? v : 1;
+        int n_sl = 1;
+        auto usable = [&](int k) {
+            if (k == 1) return true;
+            if (vv == 1 || in.ccol % k) return false;
+            // (the MFMA phase stores 16-column blocks that start at multiples of the fused column
+            // slice: they must not straddle a slice of the workspace)
+            if (s.n_slices > 1 && cs % 16 != 0) return false;
+            const int64_t sw = in.ccol / k;
+            return sw % 16 == 0 && (sw & (sw - 1)) == 0 && sw * es >= 64;
+        };
+        if (in.gather_slices > 0) {
+            if ((in.gather_slices != 1 && in.gather_slices != 2 && in.gather_slices != 4 &&
+                 in.gather_slices != 8) || !usable(in.gather_slices)) {
+                err = "gather_slices must be 1, 2, 4 or 8 and leave slices of a power of two of columns, "
+                      "at least 16 and at least 64 bytes";
+                return TF_EINVAL;
+            }
+            n_sl = in.gather_slices;
+        } else if (!wf1.empty()) {
+            const double row_bytes = (double)in.ccol * es;
+            const bool large = (double)s.n_spill_rows * row_bytes > 64.0 * 1048576.0;
+            if (far_rows && large)
+                for (int k = 8; k > 1; k /= 2)
+                    if (usable(k) && in.ccol / k * es >= kGatherSliceBytes) {
+                        n_sl = k;
+                        break;
+                    }
+        }
+        s.d1.n_sl = n_sl;
+        s.d1.sw = (int32_t)(in.ccol / n_sl);
+        s.d1.rows = std::max<int64_t>(1, s.n_spill_rows);
+        const int groups = kSpmmThreads / lane_group(s.d1.sw, vv);
+        s.gather_r = groups >= 64 ? 1 : groups >= 32 ? 2 : 4;
+    }
     // ---- per-tile blocks (see TileDesc) ---------------------------------------------------
     s.tile_desc.resize((size_t)nt);
     s.first_stride = (int32_t)round_up(std::max<int64_t>(s.max_tile_rows, 1), 16);
     s.tile_first.assign((size_t)nt * s.first_stride, 0);
+    s.tile_info.assign((size_t)nt * s.first_stride, 0u);
+    if (s.n_direct_rows > 0) {
+        s.tile_scale.resize((size_t)nt * s.first_stride * es);
+        std::memset(s.tile_scale.data(), 0, s.tile_scale.size());
+    }
     {
         int64_t total = 0;
         for (int64_t vt = 0; vt < nt; ++vt) {
@@ -614,14 +811,46 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
         d.s_bytes = (int32_t)tb.bytes.size();
         d.reserved = 0;
         int32_t *first = s.tile_first.data() + (size_t)vt * s.first_stride;
+        uint32_t *info = s.tile_info.data() + (size_t)vt * s.first_stride;
         for (int64_t q = f0; q < f1; ++q) {
             const int32_t row = s.first_rows[q];
-            first[q - f0] = (int32_t)((uint32_t)row | (s.spill[row] ? kSpillBit : 0u));
+            first[q - f0] = row;
+            uint32_t w = s.spill[row] ? (kInfoSpill | (uint32_t)s.spill_slot[row]) : 0u;
+            if (direct_kind[row] == 1) {
+                w |= kInfoDirect;
+                std::memcpy(s.tile_scale.data() + ((size_t)vt * s.first_stride + (size_t)(q - f0)) * es,
+                            vals + (size_t)in.rowptr[row] * es, (size_t)es);
+            } else if (direct_kind[row] == 2) {
+                w |= kInfoZero;
+            }
+            info[q - f0] = w;
         }
+        // (padding repeats the last row, with an empty info word)
         for (int64_t q = f1 - f0; q < s.first_stride; ++q) first[q] = s.first_rows[f1 - 1];
         if (!tb.bytes.empty()) std::memcpy(s.tile_meta.get() + d.meta_off, tb.bytes.data(), tb.bytes.size());
         TileBlock().bytes.swap(tb.bytes);
     });
+    // A plan none of whose fused rows reads the LDS tile needs no tiles at execution: the first
+    // wavefront streams through the rows; the same words again, by row.  (Not when unread D1 rows
+    // are skipped: the streaming kernels produce every row.)
+    s.streaming = s.n_lds_rows == 0 && !(in.flags & TF_FLAG_SKIP_UNREAD) && n > 0;
+    if (s.streaming) {
+        s.row_info.assign((size_t)n, 0u);
+        if (s.n_direct_rows > 0) {
+            s.row_scale.resize((size_t)n * es);
+            std::memset(s.row_scale.data(), 0, s.row_scale.size());
+        }
+        for_each_item(nt, host_threads(in.nnz, nt, 16), [&](int64_t vt) {
+            const int64_t f0 = s.tile_first_ptr[vt], f1 = s.tile_first_ptr[vt + 1];
+            for (int64_t q = f0; q < f1; ++q) {
+                const int32_t row = s.first_rows[q];
+                const size_t at = (size_t)vt * s.first_stride + (size_t)(q - f0);
+                s.row_info[(size_t)row] = s.tile_info[at];
+                if (s.n_direct_rows > 0)
+                    std::memcpy(s.row_scale.data() + (size_t)row * es, s.tile_scale.data() + at * es, (size_t)es);
+            }
+        });
+    }
     {
         // LDS actually needed with the second-phase blocks staged: everything but the estimate
         const int64_t rows_cap = round_up(s.max_tile_rows, s.lds_row_granule);
@@ -631,9 +860,9 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
     }
 
     // ---- balance: units of the second wavefront --------------------------------------------
-    const PackRules wf1_rules = pack_rules(in, (int64_t)wf1.size());
-    auto ident = [](int32_t c) { return c; };
-    pack_rows(in.rowptr, in.colidx, vals, es, wf1, wf1_rules, true, ident, s.wf1);
+    const PackRules wf1_rules = pack_rules(in, (int64_t)wf1.size(), s.d1.sw);
+    auto slot_of = [&](int32_t c) { return s.spill_slot[(size_t)c]; };
+    pack_rows(in.rowptr, in.colidx, vals, es, wf1, wf1_rules, true, slot_of, s.wf1);
     s.wf1_rows = s.wf1.rows;
     s.wf1_unit_ptr.clear();
     for (const UnitDesc &u : s.wf1.units) s.wf1_unit_ptr.push_back(u.row_begin);
@@ -646,7 +875,7 @@ void build_baseline_pack(const InspectorInput &in, Schedule &s) {
     std::iota(all.begin(), all.end(), 0);
     auto ident = [](int32_t c) { return c; };
     pack_rows(in.rowptr, in.colidx, static_cast<const unsigned char *>(in.vals), elem_size(in.dtype),
-              all, pack_rules(in, in.n), true, ident, s.all);
+              all, pack_rules(in, in.n, s.d1.sw), true, ident, s.all);
 }
 
 }  // namespace tf

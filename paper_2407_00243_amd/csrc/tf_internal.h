@@ -21,7 +21,31 @@ constexpr int kUnitRows = 64;            // most rows in one unit of a packed ro
 constexpr int kUnitSlots = 2048;         // most padded entries (rows x slots) in one such unit (they are staged in LDS)
 constexpr int kSplitMinSlots = 128;      // rows at least this long are split over several lane groups
 constexpr int kSplitPartSlots = 96;      // target slots per part of a split row
-constexpr uint32_t kSpillBit = 0x80000000u;
+constexpr int kGatherSliceBytes = 128;    // narrowest column slice of the gather kernel chosen by default, bytes
+
+// Per D1 row of a tile, beside its row id: one info word.  kInfoSpill: the row is also stored to
+// the D1 workspace, at the slot in the low bits (a row that the second wavefront reads).
+// kInfoDirect: the row of D with the same id is fused and has exactly one stored entry, on the
+// diagonal, so it is the D1 row times that entry (tile_scale) and leaves from the registers that
+// hold the D1 row; kInfoZero: the row of D with the same id is empty and is stored as zeros.
+// 0 for padding rows.
+constexpr uint32_t kInfoSpill = 0x80000000u;
+constexpr uint32_t kInfoDirect = 0x40000000u;
+constexpr uint32_t kInfoZero = 0x20000000u;
+constexpr uint32_t kInfoSlotMask = 0x1fffffffu;
+
+// Where the D1 rows that cross tiles live in device memory: `n_sl` column slices of `sw` columns
+// each (the last may be narrower in use, never in storage), slice after slice, each slice a dense
+// array of `rows` rows of sw elements.  Element (slot, col) is at
+// (col / sw) * rows * sw + slot * sw + col % sw.  One slice = plain row-major.  Slices are what one
+// XCD of the gather kernel works on: its L2 then holds sw-wide pieces of the rows instead of whole
+// rows, and the hot rows of an irregular matrix are not replicated in all eight L2 caches.
+struct D1Layout {
+    int32_t sw = 0, n_sl = 1;
+    int64_t rows = 0;
+    int64_t slice_stride() const { return rows * sw; }
+    int64_t elements() const { return (int64_t)n_sl * rows * sw; }
+};
 
 // Lanes that share one row in the gather kernels: each lane owns vv columns (vv = elements per
 // 16 bytes when rows are 16-byte aligned, else 1); the group is the smallest power of two of
@@ -121,7 +145,7 @@ struct FusedLdsLayout {
     int64_t first0, first1, second, bext, bidx, bval, cslice, tile, total;
 };
 inline FusedLdsLayout fused_lds_layout(int dtype, int b_is_sparse, int bcol, int ccol, int cs,
-                                       int max_tile_rows, int s_lds) {
+                                       int max_tile_rows, int s_lds, bool need_tile = true) {
     FusedLdsLayout l{};
     const int es = elem_size(dtype);
     const int64_t rows16 = round_up(max_tile_rows, 16);       // the row id buffers are padded
@@ -139,12 +163,13 @@ inline FusedLdsLayout fused_lds_layout(int dtype, int b_is_sparse, int bcol, int
     const bool c_regs = !b_is_sparse && c_in_registers(dtype, mfma_blocks(cs),
                                                        mfma_ksteps_special(dtype, bcol, ccol, cs));
     l.tile = l.cslice + (c_regs ? 0 : cbytes);
-    l.total = l.tile + rows_cap * lds_ldl(dtype, b_is_sparse, cs) * es;
+    // (a plan none of whose fused rows reads the tile keeps no tile at all)
+    l.total = l.tile + (need_tile ? rows_cap * lds_ldl(dtype, b_is_sparse, cs) * es : 0);
     return l;
 }
 inline int64_t fused_lds_bytes(int dtype, int b_is_sparse, int bcol, int ccol, int cs,
-                               int max_tile_rows, int s_lds) {
-    return fused_lds_layout(dtype, b_is_sparse, bcol, ccol, cs, max_tile_rows, s_lds).total;
+                               int max_tile_rows, int s_lds, bool need_tile = true) {
+    return fused_lds_layout(dtype, b_is_sparse, bcol, ccol, cs, max_tile_rows, s_lds, need_tile).total;
 }
 
 // One unit of a packed row list: n_rows rows, all padded to `slots` entries, stored row after
@@ -199,6 +224,22 @@ struct Schedule {
     std::unique_ptr<unsigned char[]> tile_meta;
     size_t tile_meta_bytes = 0;
     std::vector<int32_t> tile_first;                      // the tiles' row ids, first_stride ints per tile
+    std::vector<uint32_t> tile_info;                      // info word per D1 row of a tile (kInfo*), same stride
+    RawVec<unsigned char> tile_scale;                     // diagonal entry of the direct rows (plan's dtype), same stride; empty when there are none
+    std::vector<int32_t> spill_slot;                      // per row: its slot in the D1 workspace, -1 when not spilled
+    D1Layout d1;                                          // workspace of the fused path (rows = spilled rows)
+    int64_t n_direct_rows = 0;                            // fused rows that leave from registers (diagonal-only or empty)
+    int64_t n_lds_rows = 0;                               // fused rows computed out of the LDS tile
+    int32_t gather_r = 4;                                 // rows per lane group and pass of the gather kernel
+    // When no fused row reads the LDS tile the first wavefront streams through the rows without
+    // tiles: the info words and diagonal entries again, indexed by row (empty otherwise).
+    std::vector<uint32_t> row_info;
+    RawVec<unsigned char> row_scale;
+    bool streaming = false;
+    bool automatic = false;        // the caller left the tiling to the library
+    bool far_rows = false;         // rows reach far from the diagonal (a graph), see build_schedule
+    bool grown_tiles = false;      // tiles grown along the dependence graph
+    int64_t n_demoted_rows = 0;    // rows that a tile could have fused but that were left to the second wavefront
     int32_t first_stride = 0;                             // largest tile, in rows, rounded up to 16
     int64_t second_block_cap = 0;                         // largest second-phase block, bytes
     bool second_block_in_lds = true;                      // it fits beside the largest tile
@@ -223,6 +264,7 @@ struct InspectorInput {
     int64_t fast_mem_bytes;
     int32_t col_slice;
     uint32_t flags;
+    int32_t gather_slices;            // column slices of the D1 workspace and of the gather kernel; 0 = chosen here
     int32_t n_cu;                     // compute units of the device the plan will run on
 };
 
@@ -259,24 +301,34 @@ struct FusedLaunch {
     const TileDesc *tile_desc;
     const unsigned char *tile_meta;
     const int32_t *tile_first;        // row ids of tile v at tile_first + v * first_stride
+    const uint32_t *tile_info;        // info words (kInfo*), same indexing
+    const void *tile_scale;           // diagonal entries of direct rows, same indexing; nullptr: no direct rows
     int32_t first_stride;
+    int32_t need_tile;                // 0: no tile of the plan has fused rows that read the LDS tile
+    int32_t n_cu;                     // compute units of the device
     const void *B;                    // dense B (gemm) or nullptr
     CsrDev Bs;                        // sparse B (spmm)
     const void *C;
     int32_t c_ldk, c_ldc;             // dense B: element (k, c) of the multiplier is C[k c_ldk + c c_ldc]
     void *D;
     void *D1;
+    int32_t d1_sw_shift, d1_sw_mask;  // column -> (slice, offset) of the D1 workspace (one slice: 31, 0x7fffffff)
+    int32_t d1_sw;
+    int64_t d1_slice_stride;          // elements
 };
 
 // Y[row] = sum over the packed entries of the row of val * X[idx]; one unit per workgroup.
 struct PackedSpmmLaunch {
     int32_t dtype;
     int64_t n_units;
-    int32_t contiguous;               // 1: neighbouring units share an XCD; 0: round robin
+    int32_t contiguous;               // 1: neighbouring units share an XCD; 0: round robin (one slice only)
     int32_t wide;                     // 1: X spans 4 GiB or more (64-bit operand offsets)
-    PackDev pack;                     // int32 indices
-    const void *X;
-    void *Y;
+    PackDev pack;                     // int32 indices: rows (slots) of X
+    const void *X;                    // D1 workspace in the layout below
+    int32_t n_xs, sw;                 // column slices (1, 2, 4 or 8; each handled by 8 / n_xs XCDs) of sw columns
+    int64_t x_slice_stride;           // elements between the slices of X
+    int32_t rows_per_pass;            // R of the kernel instantiation: 1, 2 or 4
+    void *Y;                          // row-major, ccol columns
     int32_t ccol;
 };
 
@@ -287,8 +339,13 @@ struct CsrSpmmLaunch {
     int32_t rows_per_wg;
     CsrDev S;
     const void *X;
-    void *Y;
+    void *Y;                          // D1 workspace layout: slices of y_sw columns
     int32_t ccol;
+    int32_t y_sw_shift, y_sw_mask, y_sw;
+    int64_t y_slice_stride;
+    const uint32_t *row_info;         // as in GemmLaunch
+    const void *row_scale;
+    void *D;
 };
 
 struct GemmLaunch {
@@ -297,7 +354,14 @@ struct GemmLaunch {
     int32_t bcol, ccol, cs, n_slices;
     const void *B, *C;
     int32_t c_ldk, c_ldc;             // element (k, c) of the multiplier is C[k c_ldk + c c_ldc]
-    void *D1;
+    void *D1;                         // workspace layout: slices of d1_sw columns
+    int32_t d1_sw_shift, d1_sw_mask, d1_sw;
+    int64_t d1_slice_stride;
+    // first wavefront of a plan without an LDS tile (else nullptr): info word per row (kInfo*),
+    // diagonal entry of the direct rows (nullptr: none), and D
+    const uint32_t *row_info;
+    const void *row_scale;
+    void *D;
 };
 
 // Each returns hipError_t as int (0 = success).  `stream` is a hipStream_t.

@@ -4,13 +4,16 @@
 //   k_fused_spmm_spmm   first wavefront, CSR B     (Section 3.2, fused SpMM-SpMM listing)
 //   k_packed_spmm       second wavefront (rows whose D1 rows come from device memory); also the
 //                       SpMM of the unfused baseline
-//   k_gemm              D1 = B C for all rows: the GeMM of the unfused baseline
+//   k_gemm              D1 = B C for all rows: the GeMM of the unfused baseline, and the first
+//                       wavefront of a dense-B plan that needs no tile in LDS
+//   k_csr_spmm          D1 = B C for a CSR B, likewise
 //
 // A fused workgroup owns one tile (a list of D1 rows) and one column slice.  It produces the
 // tile's D1 rows into LDS -- by MFMA for a dense B, by a row gather over C for a CSR B -- stores
-// the rows flagged "spill" to device memory as well, and after one workgroup barrier computes
-// the tile's fused rows of D straight out of LDS.  Nothing is accumulated with atomics: every
-// output element is written by exactly one lane.
+// the rows flagged "spill" to the D1 workspace as well, and after one workgroup barrier computes
+// the tile's fused rows of D straight out of LDS.  Fused rows of D that are a multiple of their
+// own D1 row (only a diagonal entry) or empty leave from the registers that hold the D1 row.
+// Nothing is accumulated with atomics: every output element is written by exactly one lane.
 //
 // Wave size is 64.  Lanes run across columns (16 bytes per lane where alignment allows), row
 // groups across the rest of the wave.
@@ -419,7 +422,7 @@ __device__ __forceinline__ TileWalk tile_walk(int n_tiles, int n_slices) {
 
 // LDS of a fused workgroup, as laid out by fused_lds_layout.
 struct FusedSmem {
-    int32_t *first[2];            // row ids (bit 31 = spill) of the current and of the next tile
+    int32_t *first[2];            // row ids of the current and of the next tile
     unsigned char *second;        // staged second-phase block (or unused)
     int32_t *bext, *bidx;         // CSR B: (first entry, length) of the rows of B of this tile and of the
     unsigned char *bval;          //        next (bext_stride ints apart), column indices and values
@@ -673,7 +676,7 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
     // that every load is unconditional (first[] is padded to a multiple of 16 rows)
     auto row_of = [&](const int32_t *first, int rows, int lb) -> int64_t {
         const int lr = lb * 16 + r;
-        return (int64_t)((uint32_t)first[lr < rows ? lr : rows - 1] & ~kSpillBit);
+        return (int64_t)first[lr < rows ? lr : rows - 1];
     };
 
     TileDesc d = a.tile_desc[tw.tile];
@@ -748,39 +751,63 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
                 }
             }
         };
-        // The spilled rows of a block go to the D1 workspace straight from the accumulators of
-        // the wave that produced them (as the unfused product stores its rows): lane (g, r) holds
-        // columns 16 nb + 4 g .. + 3 of row r, so the four lanes of a row store 64 contiguous bytes
-        // per block of columns.  `enc` is the lane's row id with the spill bit, 0 past the tile's end.
+        // Rows that leave from the accumulators of the wave that produced them (as the unfused
+        // product stores its rows): lane (g, r) holds columns 16 nb + 4 g .. + 3 of row r, so the four
+        // lanes of a row store 64 contiguous bytes per block of columns.  `info` is the lane's info
+        // word (0 past the tile's end), fetched from device memory before the multiplications.
+        //  - spilled rows go to their slot of the D1 workspace (column slices of d1_sw columns);
+        //  - direct rows of D (the D1 row times the diagonal entry `sc`) and empty rows of D go to D.
         // (Reading the rows back from the LDS tile, whole rows per store, cost a chain of two LDS
         // round trips per pass of four rows.)
-        auto row_enc = [&](int lb) -> uint32_t {
-            const int i = lb * 16 + r;
-            return i < rows ? (uint32_t)first[i] : 0u;
+        const int64_t info_base = (int64_t)tw.tile * a.first_stride;
+        auto row_info = [&](int lb) -> uint32_t { return a.tile_info[info_base + lb * 16 + r]; };
+        auto row_scale = [&](int lb) -> T {
+            return a.tile_scale ? static_cast<const T *>(a.tile_scale)[info_base + lb * 16 + r] : T(0);
         };
-        auto spill_block = [&](uint32_t enc, typename Tr<T>::Acc(&acc)[NB]) {
-            if (!(enc & kSpillBit)) return;
-            T *dst = static_cast<T *>(a.D1) + (int64_t)(enc & ~kSpillBit) * a.ccol + c0 + 4 * g;
+        auto store_cols = [&](T *dst, int nb, const T (&x)[4]) {      // dst: the lane's first column of block nb
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
+            for (int h = 0; h < 4 / V; ++h) {
+                const int col = 16 * nb + 4 * g + V * h;
+                if (FAST) {
+                    if (col < w) {
+                        T tmp[V];
 #pragma unroll
-                for (int h = 0; h < 4 / V; ++h) {
-                    const int col = 16 * nb + 4 * g + V * h;
-                    if (FAST) {
-                        if (col < w) {
-                            T tmp[V];
-#pragma unroll
-                            for (int i = 0; i < V; ++i) tmp[i] = acc[nb][V * h + i];
-                            store_pack<T, V>(dst + 16 * nb + V * h, tmp);
-                        }
-                    } else {
-#pragma unroll
-                        for (int i = 0; i < V; ++i)
-                            if (col + i < w) dst[16 * nb + V * h + i] = acc[nb][V * h + i];
+                        for (int i = 0; i < V; ++i) tmp[i] = x[V * h + i];
+                        store_pack<T, V>(dst + V * h, tmp);
                     }
+                } else {
+#pragma unroll
+                    for (int i = 0; i < V; ++i)
+                        if (col + i < w) dst[V * h + i] = x[V * h + i];
                 }
             }
         };
+        auto spill_block = [&](uint32_t info, typename Tr<T>::Acc(&acc)[NB]) {
+            if (!(info & kInfoSpill)) return;
+            T *slot = static_cast<T *>(a.D1) + (int64_t)(info & kInfoSlotMask) * a.d1_sw + 4 * g;
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                const int cb = c0 + 16 * nb;                        // wave-uniform
+                T x[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) x[i] = acc[nb][i];
+                store_cols(slot + (int64_t)(cb >> a.d1_sw_shift) * a.d1_slice_stride + (cb & a.d1_sw_mask),
+                           nb, x);
+            }
+        };
+        auto direct_block = [&](uint32_t info, T sc, int64_t row, typename Tr<T>::Acc(&acc)[NB]) {
+            if (!(info & (kInfoDirect | kInfoZero))) return;
+            T *dst = static_cast<T *>(a.D) + row * a.ccol + c0 + 4 * g;
+            if (info & kInfoZero) sc = T(0);
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                T x[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) x[i] = (info & kInfoZero) ? T(0) : sc * acc[nb][i];
+                store_cols(dst + 16 * nb, nb, x);
+            }
+        };
+        const bool has2 = d.n_second > 0;       // fused rows that read the LDS tile
         if constexpr (KS > 0) {
             // One block per step: start the loads of the block ND - 1 steps ahead, multiply,
             // write the results to the LDS tile.  The B buffers rotate by name (the loop is
@@ -793,8 +820,9 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
                 // the loads go out before the multiplications, not after them: left alone the
                 // compiler reuses the accumulators' registers for the buffer being filled and
                 // sinks the loads to the end of the step, which halves the distance they run ahead
+                const uint32_t info = row_info(lb);
+                const T sc = row_scale(lb);
                 __builtin_amdgcn_sched_barrier(0);
-                const uint32_t enc = row_enc(lb);
                 typename Tr<T>::Acc acc[NB];
                 if constexpr (CREG) {
                     mfma_frag_reg<T, NB, KSF>(acc, creg, fb[FI]);
@@ -804,8 +832,9 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
                     asm volatile("" ::: "memory");
                     mfma_frag<T, NB, KSF>(acc, Cl, fb[FI], lane);
                 }
-                write_block(lb, acc);
-                spill_block(enc, acc);
+                if (has2) write_block(lb, acc);
+                spill_block(info, acc);
+                direct_block(info, sc, row_of(first, rows, lb), acc);
             };
             if (is_mfma) {
                 for (int lb = wave; lb < nblk; lb += ND * nmw) {
@@ -825,11 +854,14 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
             }
         } else {
             for (int lb = wave; lb < nblk; lb += nwaves) {
+                const uint32_t info = row_info(lb);
+                const T sc = row_scale(lb);
                 typename Tr<T>::Acc acc[NB];
                 mfma_row_block<T, NB, FAST>(acc, Cl, B + row_of(first, rows, lb) * a.bcol, true,
                                             a.bcol, lane);
-                write_block(lb, acc);
-                spill_block(row_enc(lb), acc);
+                if (has2) write_block(lb, acc);
+                spill_block(info, acc);
+                direct_block(info, sc, row_of(first, rows, lb), acc);
             }
         }
         if constexpr (SLDS) stage_write<kStagePieces>(st, sm.second, blk, d.s_bytes, stid, snt);
@@ -852,7 +884,9 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
         // When the slice is a whole number of double packs each lane takes two packs of a row
         // (half as many lanes per row, twice as many rows per wave): the index and address work of
         // a step is shared by twice as many columns.
-        if (FAST && G >= 2 && w % (2 * VV) == 0) {
+        if (!has2) {
+            // nothing reads the LDS tile: the workgroup streams on
+        } else if (FAST && G >= 2 && w % (2 * VV) == 0) {
             const int G2 = G / 2;
             const int gl2 = (int)threadIdx.x % G2;
             if (2 * VV * gl2 < w)
@@ -862,7 +896,8 @@ __global__ __launch_bounds__(kFusedThreads) void k_fused_gemm_spmm(const FusedLa
             fused_tail<T, VV, 3>(a, d, SLDS ? sm.second : blk, tileD1, ldl, c0, gl, grp, ngrp);
         }
         if (!has_next) break;
-        __syncthreads();
+        // (the next tile rewrites the LDS tile and the staged block; its row ids are in the other buffer)
+        if (has2) __syncthreads();
         d = nd;
         tw.tile = ntile;
         par ^= 1;
@@ -929,13 +964,15 @@ __device__ __forceinline__ void stage_entries(int rows, const int32_t *ext, int3
     __syncthreads();
 }
 
-template <typename T, int VV, int RP, typename OutFn>
+// pre(pos) is called before the gathers of a row go out and its result handed to out(pos, pre, acc):
+// what a finished row needs to know from device memory is then fetched along with the operands.
+template <typename T, int VV, int RP, typename PreFn, typename OutFn>
 __device__ __forceinline__ void gather_staged_rows(int rows, const int32_t *ext, const int32_t *eidx,
                                                    const T *eval,
                                                    const int32_t *__restrict__ colidx,
                                                    const T *__restrict__ vals, const T *Xl,
                                                    int64_t ldx, bool active, int grp, int ngrp,
-                                                   OutFn out) {
+                                                   PreFn pre, OutFn out) {
     constexpr int CAP = kSparseEntryCap;
     typedef int32_t Idx4 __attribute__((ext_vector_type(4)));
     for (int base = grp; base < rows; base += ngrp * RP) {
@@ -951,8 +988,10 @@ __device__ __forceinline__ void gather_staged_rows(int rows, const int32_t *ext,
         if (!active) continue;
         T acc[RP][VV];
         int32_t ci[RP][CAP];
+        decltype(pre(0)) pr[RP];
 #pragma unroll
         for (int r = 0; r < RP; ++r) {
+            pr[r] = pre(pos[r]);
 #pragma unroll
             for (int i = 0; i < VV; ++i) acc[r][i] = T(0);
             const Idx4 *p = reinterpret_cast<const Idx4 *>(eidx + pos[r] * CAP);
@@ -1013,7 +1052,7 @@ __device__ __forceinline__ void gather_staged_rows(int rows, const int32_t *ext,
 #pragma unroll
                 for (int i = 0; i < VV; ++i) acc[r][i] = a1[0][i];
             }
-            if (ok[r]) out(pos[r], acc[r]);
+            if (ok[r]) out(pos[r], pr[r], acc[r]);
         }
     }
 }
@@ -1049,7 +1088,7 @@ __global__ __launch_bounds__(kFusedSparseThreads) void k_fused_spmm_spmm(const F
     __syncthreads();
     // extents of the first tile's rows of B; those of every later tile are fetched during the
     // second phase of the tile before it
-    auto row_id = [](const int32_t *ids, int i) { return (int64_t)((uint32_t)ids[i] & ~kSpillBit); };
+    auto row_id = [](const int32_t *ids, int i) { return (int64_t)ids[i]; };
     stage_extents(d.n_rows, sm.bext, a.Bs.rowptr, [&](int i) { return row_id(sm.first[0], i); });
     __syncthreads();
     for (;;) {
@@ -1060,6 +1099,7 @@ __global__ __launch_bounds__(kFusedSparseThreads) void k_fused_spmm_spmm(const F
         const TileDesc nd = a.tile_desc[has_next ? ntile : tw.tile];
         const unsigned char *blk = a.tile_meta + d.meta_off;
         Staged<kStagePieces> st;
+        const bool has2 = d.n_second > 0;       // fused rows that read the LDS tile
         const int nfirst_pieces = has_next ? ((nd.n_rows + 15) >> 4) * 4 : 0;
         if constexpr (SLDS) stage_issue<kStagePieces>(st, blk, d.s_bytes, threadIdx.x, blockDim.x);
         const Piece *nsrc = reinterpret_cast<const Piece *>(
@@ -1073,14 +1113,33 @@ __global__ __launch_bounds__(kFusedSparseThreads) void k_fused_spmm_spmm(const F
             const int32_t *ext_cur = sm.bext + par * sm.bext_stride;
             stage_entries<T>(rows, ext_cur, sm.bidx, eval, a.Bs.colidx, bvals);
             T *tile_lane = tileD1 + VV * gl;
-            T *D1l = static_cast<T *>(a.D1) + c0 + VV * gl;
+            // the lane's columns of a workspace row (slices of d1_sw columns) and of a row of D
+            const int colg = c0 + VV * gl;
+            T *D1l = static_cast<T *>(a.D1) + (int64_t)(colg >> a.d1_sw_shift) * a.d1_slice_stride +
+                     (colg & a.d1_sw_mask);
+            T *Dl = static_cast<T *>(a.D) + colg;
+            const uint32_t *info_t = a.tile_info + (int64_t)tw.tile * a.first_stride;
+            const T *scale_t = a.tile_scale
+                                   ? static_cast<const T *>(a.tile_scale) + (int64_t)tw.tile * a.first_stride
+                                   : nullptr;
+            struct RowInfo {
+                uint32_t info;
+                T sc;
+            };
             gather_staged_rows<T, VV, 1>(
                 rows, ext_cur, sm.bidx, eval, a.Bs.colidx, bvals, C + c0 + VV * gl, ccol,
-                VV * gl < w, grp, ngrp, [&](int pos, const T(&acc)[VV]) {
-                    store_pack<T, VV>(tile_lane + (int64_t)pos * ldl, acc);
-                    const uint32_t enc = (uint32_t)first[pos];
-                    if (enc & kSpillBit)
-                        store_pack<T, VV>(D1l + (int64_t)(enc & ~kSpillBit) * ccol, acc);
+                VV * gl < w, grp, ngrp,
+                [&](int pos) { return RowInfo{info_t[pos], scale_t ? scale_t[pos] : T(0)}; },
+                [&](int pos, const RowInfo &ri, const T(&acc)[VV]) {
+                    if (has2) store_pack<T, VV>(tile_lane + (int64_t)pos * ldl, acc);
+                    if (ri.info & kInfoSpill)
+                        store_pack<T, VV>(D1l + (int64_t)(ri.info & kInfoSlotMask) * a.d1_sw, acc);
+                    if (ri.info & (kInfoDirect | kInfoZero)) {
+                        T x[VV];
+#pragma unroll
+                        for (int i = 0; i < VV; ++i) x[i] = (ri.info & kInfoZero) ? T(0) : ri.sc * acc[i];
+                        store_pack<T, VV>(Dl + (int64_t)first[pos] * ccol, x);
+                    }
                 });
         }
 
@@ -1108,7 +1167,9 @@ __global__ __launch_bounds__(kFusedSparseThreads) void k_fused_spmm_spmm(const F
         }
         // (two packs of one row per lane when the slice allows, else one pack of two rows: the same
         // registers, half the index and address work per column)
-        if (FAST && G >= 2 && w % (2 * VV) == 0) {
+        if (!has2) {
+            // nothing reads the LDS tile
+        } else if (FAST && G >= 2 && w % (2 * VV) == 0) {
             const int G2 = G / 2;
             const int gl2 = (int)threadIdx.x % G2;
             if (2 * VV * gl2 < w)
@@ -1143,31 +1204,50 @@ __global__ __launch_bounds__(kFusedSparseThreads) void k_fused_spmm_spmm(const F
     }
 }
 
-// Packed-row SpMM: Y[row][:] = sum over the row's packed entries of val * X[idx][:], one unit per
-// workgroup (second wavefront, and the second operation of the unfused baseline).
+// Packed-row SpMM: Y[row][:] = sum over the row's packed entries of val * X[idx][:], one unit
+// (and one column slice) per workgroup: the second wavefront, and the second operation of the
+// unfused baseline.  X is the D1 workspace: n_xs column slices of sw columns, idx is a row (slot)
+// of it.
+//
+// With one slice a workgroup handles whole rows.  With n_xs = 2, 4 or 8 slices, workgroup b (which
+// the hardware places on XCD b % 8) handles slice (b % 8) % n_xs of unit (b / 8) (8 / n_xs) +
+// (b % 8) / n_xs: an XCD only ever touches one slice of X, so its L2 holds sw-wide pieces of the
+// hot rows instead of whole rows, and the eight caches hold different data.
+//
 // The entries of a unit are contiguous (n_rows x slots): the workgroup first copies them to LDS
 // with coalesced 16-byte loads, then every lane group reads the entries of its rows from there
 // (an LDS broadcast) instead of fetching each index and value through the vector memory path
-// once per lane.  Units whose rows are split hand their partial sums through LDS and add them
-// in a fixed order.
-template <typename T, bool FAST, bool WIDE>
+// once per lane.  A lane group works on R rows at a time and keeps E entries of each in flight.
+// Units whose rows are split hand their partial sums through LDS and add them in a fixed order.
+template <typename T, bool FAST, bool WIDE, int R>
 __global__ __launch_bounds__(kSpmmThreads) void k_packed_spmm(const PackedSpmmLaunch a) {
     constexpr int VV = FAST ? Tr<T>::V : 1;
-    constexpr int R = kRowsPerPass, E = kEntriesPerPass;
+    constexpr int E = R >= 4 ? 4 : 8;
     __shared__ __align__(16) int32_t idx_s[kUnitSlots + 4];
     __shared__ __align__(16) T val_s[kUnitSlots + 4];
     T *red = val_s;                                     // split units do not stage their entries
-    const int64_t u = a.contiguous ? xcd_contiguous(blockIdx.x, a.n_units) : (int64_t)blockIdx.x;
+    int64_t u;
+    int slice = 0;
+    if (a.n_xs == 1) {
+        u = a.contiguous ? xcd_contiguous(blockIdx.x, a.n_units) : (int64_t)blockIdx.x;
+    } else {
+        const int x = blockIdx.x & 7, per = 8 / a.n_xs;
+        slice = x % a.n_xs;
+        u = (int64_t)(blockIdx.x >> 3) * per + x / a.n_xs;
+    }
     if (u >= a.n_units) return;
     const UnitDesc d = a.pack.units[u];
     const int ccol = a.ccol;
-    const int G = min(64, pow2_at_least((ccol + VV - 1) / VV));
+    const int c0 = slice * a.sw;
+    const int w = min(a.sw, ccol - c0);                 // columns of this slice
+    const int G = min(64, pow2_at_least((a.sw + VV - 1) / VV));
     const int gl = threadIdx.x % G, grp = threadIdx.x / G, ngrp = blockDim.x / G;
     const int32_t *__restrict__ rows = a.pack.rows;
     const int32_t *__restrict__ idx = static_cast<const int32_t *>(a.pack.idx);
     const T *__restrict__ val = static_cast<const T *>(a.pack.vals);
-    const T *__restrict__ X = static_cast<const T *>(a.X);
-    T *__restrict__ Y = static_cast<T *>(a.Y);
+    const T *__restrict__ X = static_cast<const T *>(a.X) + (int64_t)slice * a.x_slice_stride;
+    const uint32_t ldx = (uint32_t)a.sw;
+    T *__restrict__ Y = static_cast<T *>(a.Y) + c0;
     if (d.split <= 1) {
         const int n_ent = d.n_rows * d.slots;
         {
@@ -1191,9 +1271,9 @@ __global__ __launch_bounds__(kSpmmThreads) void k_packed_spmm(const PackedSpmmLa
         }
         __syncthreads();
         const int L = d.slots;
-        for (int cb = 0; cb < ccol; cb += G * VV) {
+        for (int cb = 0; cb < w; cb += G * VV) {
             const int col = cb + VV * gl;
-            const bool active = col < ccol;
+            const bool active = col < w;
             const uint32_t lane_off = active ? (uint32_t)col : 0u;      // idle lanes read column 0
             for (int i0 = grp; i0 < d.n_rows; i0 += ngrp * R) {
                 int at[R];
@@ -1214,8 +1294,12 @@ __global__ __launch_bounds__(kSpmmThreads) void k_packed_spmm(const PackedSpmmLa
                 for (int r = 0; r < R; ++r)
 #pragma unroll
                     for (int i = 0; i < VV; ++i) acc[r][i] = T(0);
-                int sl = 0;
-                for (; sl + E <= L; sl += E) {
+                // E entries of each of the R rows per pass, from slot sl on.  The last pass of a row
+                // may reach past the row's end: its surplus slots re-read the last entry (same
+                // address: no extra traffic) with a zero value, so that the whole remainder is one
+                // round trip to memory instead of one per entry (most rows of a graph are short).
+                auto pass = [&](auto masked_c, int sl) {
+                    constexpr bool MASKED = decltype(masked_c)::value;
                     uint32_t c[R][E];
                     T v[R][E];
                     T x[R][E][VV];
@@ -1223,37 +1307,28 @@ __global__ __launch_bounds__(kSpmmThreads) void k_packed_spmm(const PackedSpmmLa
                     for (int r = 0; r < R; ++r)
 #pragma unroll
                         for (int e = 0; e < E; ++e) {
-                            c[r][e] = (uint32_t)idx_s[at[r] + sl + e];
-                            v[r][e] = val_s[at[r] + sl + e];
+                            const bool in = !MASKED || sl + e < L;
+                            const int at_e = at[r] + (in ? sl + e : L - 1);
+                            c[r][e] = (uint32_t)idx_s[at_e];
+                            v[r][e] = in ? val_s[at_e] : T(0);
                         }
 #pragma unroll
                     for (int r = 0; r < R; ++r)
 #pragma unroll
-                        for (int e = 0; e < E; ++e)
-                            load_x<T, VV, WIDE>(x[r][e], X, c[r][e], (uint32_t)ccol, lane_off);
+                        for (int e = 0; e < E; ++e) load_x<T, VV, WIDE>(x[r][e], X, c[r][e], ldx, lane_off);
 #pragma unroll
                     for (int r = 0; r < R; ++r)
 #pragma unroll
-                        for (int e = 0; e < E; ++e)
+                        for (int e = 0; e < E; ++e) {
+                            // (a surplus slot adds nothing, whatever the operand holds)
+                            if (MASKED && sl + e >= L) continue;
 #pragma unroll
                             for (int i = 0; i < VV; ++i) acc[r][i] += v[r][e] * x[r][e][i];
-                }
-                for (; sl < L; ++sl) {
-                    uint32_t c[R];
-                    T v[R];
-                    T x[R][VV];
-#pragma unroll
-                    for (int r = 0; r < R; ++r) {
-                        c[r] = (uint32_t)idx_s[at[r] + sl];
-                        v[r] = val_s[at[r] + sl];
-                    }
-#pragma unroll
-                    for (int r = 0; r < R; ++r) load_x<T, VV, WIDE>(x[r], X, c[r], (uint32_t)ccol, lane_off);
-#pragma unroll
-                    for (int r = 0; r < R; ++r)
-#pragma unroll
-                        for (int i = 0; i < VV; ++i) acc[r][i] += v[r] * x[r][i];
-                }
+                        }
+                };
+                int sl = 0;
+                for (; sl + E <= L; sl += E) pass(std::false_type(), sl);
+                if (sl < L) pass(std::true_type(), sl);
                 if (active) {
 #pragma unroll
                     for (int r = 0; r < R; ++r)
@@ -1264,9 +1339,9 @@ __global__ __launch_bounds__(kSpmmThreads) void k_packed_spmm(const PackedSpmmLa
         }
         return;
     }
-    for (int cb = 0; cb < ccol; cb += G * VV) {
+    for (int cb = 0; cb < w; cb += G * VV) {
         const int col = cb + VV * gl;
-        const bool active = col < ccol;
+        const bool active = col < w;
         const uint32_t lane_off = active ? (uint32_t)col : 0u;      // idle lanes read column 0
         {
             // group -> (row, part); `split` groups share a row, each takes a range of the slots
@@ -1281,25 +1356,25 @@ __global__ __launch_bounds__(kSpmmThreads) void k_packed_spmm(const PackedSpmmLa
                 const int32_t *__restrict__ ip = idx + at;
                 const T *__restrict__ vp = val + at;
                 int sl = s0;
-                for (; sl + 4 <= s1; sl += 4) {
-                    uint32_t c[4];
-                    T v[4];
-                    T x[4][VV];
+                for (; sl + 8 <= s1; sl += 8) {
+                    uint32_t c[8];
+                    T v[8];
+                    T x[8][VV];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
+                    for (int e = 0; e < 8; ++e) {
                         c[e] = (uint32_t)ip[sl + e];
                         v[e] = vp[sl + e];
                     }
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) load_x<T, VV, WIDE>(x[e], X, c[e], (uint32_t)ccol, lane_off);
+                    for (int e = 0; e < 8; ++e) load_x<T, VV, WIDE>(x[e], X, c[e], ldx, lane_off);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e)
+                    for (int e = 0; e < 8; ++e)
 #pragma unroll
                         for (int i = 0; i < VV; ++i) acc[i] += v[e] * x[e][i];
                 }
                 for (; sl < s1; ++sl) {
                     T x[VV];
-                    load_x<T, VV, WIDE>(x, X, (uint32_t)ip[sl], (uint32_t)ccol, lane_off);
+                    load_x<T, VV, WIDE>(x, X, (uint32_t)ip[sl], ldx, lane_off);
                     const T v = vp[sl];
 #pragma unroll
                     for (int i = 0; i < VV; ++i) acc[i] += v * x[i];
@@ -1322,8 +1397,10 @@ __global__ __launch_bounds__(kSpmmThreads) void k_packed_spmm(const PackedSpmmLa
     }
 }
 
-// CSR SpMM over a caller-supplied matrix (the first operation of the unfused SpMM-SpMM
-// baseline): Y[j][:] = sum_k S.vals[k] X[S.colidx[k]][:], consecutive rows per workgroup.
+// CSR SpMM over a caller-supplied matrix: Y[j][:] = sum_k S.vals[k] X[S.colidx[k]][:], consecutive
+// rows per workgroup.  The first operation of the unfused SpMM-SpMM baseline (row_info = nullptr:
+// every row goes to the workspace, slot = row), and the first wavefront of a CSR-B plan that needs
+// no tile in LDS (row_info set, see k_gemm).
 template <typename T, bool FAST>
 __global__ __launch_bounds__(kSpmmThreads) void k_csr_spmm(const CsrSpmmLaunch a) {
     constexpr int VV = FAST ? Tr<T>::V : 1;
@@ -1348,16 +1425,49 @@ __global__ __launch_bounds__(kSpmmThreads) void k_csr_spmm(const CsrSpmmLaunch a
     stage_entries<T>(rows, ext_s, idx_s, val_s, a.S.colidx, vals);
     for (int cb = 0; cb < ccol; cb += G * VV) {
         const int col = cb + VV * gl;
-        gather_staged_rows<T, VV, 2>(rows, ext_s, idx_s, val_s, a.S.colidx, vals, X + col, ccol,
-                                     col < ccol, grp, ngrp, [&](int pos, const T(&acc)[VV]) {
-                                         store_pack<T, VV>(Y + (r0 + pos) * ccol + col, acc);
-                                     });
+        // the lane's columns of a row of the workspace (slices of y_sw columns)
+        T *Yl = Y + (int64_t)(col >> a.y_sw_shift) * a.y_slice_stride + (col & a.y_sw_mask);
+        if (!a.row_info) {
+            gather_staged_rows<T, VV, 2>(rows, ext_s, idx_s, val_s, a.S.colidx, vals, X + col, ccol,
+                                         col < ccol, grp, ngrp, [](int) { return 0; },
+                                         [&](int pos, int, const T(&acc)[VV]) {
+                                             store_pack<T, VV>(Yl + (r0 + pos) * a.y_sw, acc);
+                                         });
+        } else {
+            // first wavefront of a plan without an LDS tile: what happens to a finished D1 row is
+            // told by its info word (see k_gemm)
+            struct RowInfo {
+                uint32_t info;
+                T sc;
+            };
+            const T *scale = static_cast<const T *>(a.row_scale);
+            T *Dl = static_cast<T *>(a.D) + col;
+            gather_staged_rows<T, VV, 2>(
+                rows, ext_s, idx_s, val_s, a.S.colidx, vals, X + col, ccol, col < ccol, grp, ngrp,
+                [&](int pos) { return RowInfo{a.row_info[r0 + pos], scale ? scale[r0 + pos] : T(0)}; },
+                [&](int pos, const RowInfo &ri, const T(&acc)[VV]) {
+                    if (ri.info & kInfoSpill)
+                        store_pack<T, VV>(Yl + (int64_t)(ri.info & kInfoSlotMask) * a.y_sw, acc);
+                    if (ri.info & (kInfoDirect | kInfoZero)) {
+                        T x[VV];
+#pragma unroll
+                        for (int i = 0; i < VV; ++i) x[i] = (ri.info & kInfoZero) ? T(0) : ri.sc * acc[i];
+                        store_pack<T, VV>(Dl + (r0 + pos) * ccol, x);
+                    }
+                });
+        }
     }
 }
 
-// D1 = B C for all rows (unfused baseline): one 16-row block per wave at a time, the next
-// block's rows of B in flight while the current one is multiplied (KS > 0, as above).
-template <typename T, int NB, int KS, bool FAST>
+// D1 = B C for all rows, one 16-row block per wave at a time, the next block's rows of B in
+// flight while the current one is multiplied (KS > 0, as above).
+// INFO = false: the GeMM of the unfused baseline; every row goes to the workspace, slot = row.
+// INFO = true: the first wavefront of a plan none of whose fused rows reads the LDS tile (a graph:
+// the only rows that fuse hold just a diagonal entry, or nothing).  Then no tile has to sit in LDS
+// and the workgroups stream through the rows like the plain product; what happens to a finished
+// D1 row is told by its info word (kInfo*): stored to its workspace slot when the second wavefront
+// reads it, stored to D times the diagonal entry (or as zeros) when the row of D is fused.
+template <typename T, int NB, int KS, bool FAST, bool INFO>
 __global__ __launch_bounds__(kFusedThreads) void k_gemm(const GemmLaunch a) {
     const int slice = blockIdx.y;
     const int c0 = slice * a.cs;
@@ -1375,13 +1485,54 @@ __global__ __launch_bounds__(kFusedThreads) void k_gemm(const GemmLaunch a) {
     const int64_t per_wg = (nblk + gridDim.x - 1) / gridDim.x;
     const int64_t lb0 = (int64_t)blockIdx.x * per_wg;
     const int64_t lb1 = lb0 + per_wg < nblk ? lb0 + per_wg : nblk;
-    auto write_block = [&](int64_t lb, typename Tr<T>::Acc(&acc)[NB]) {
+    struct RowInfo {
+        uint32_t info;
+        T sc;
+    };
+    // (fetched before the multiplications of the block, used after them)
+    auto row_info = [&](int64_t lb) -> RowInfo {
+        RowInfo ri{0u, T(0)};
+        if constexpr (INFO) {
+            const int64_t row = lb * 16 + r;
+            const int64_t rc = row < a.n ? row : a.n - 1;
+            ri.info = row < a.n ? a.row_info[rc] : 0u;
+            if (a.row_scale) ri.sc = static_cast<const T *>(a.row_scale)[rc];
+        }
+        return ri;
+    };
+    auto write_block = [&](int64_t lb, const RowInfo &ri, typename Tr<T>::Acc(&acc)[NB]) {
         const int64_t row = lb * 16 + r;
-        if (row < a.n) {
+        if (row >= a.n) return;
+        if constexpr (!INFO) {
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
                 const int col = 16 * nb + 4 * g;
-                store_acc4<T, FAST>(D1 + row * a.ccol + c0 + col, acc[nb], col, w);
+                const int cb = c0 + 16 * nb;        // the workspace is cut into slices of d1_sw columns
+                store_acc4<T, FAST>(D1 + (int64_t)(cb >> a.d1_sw_shift) * a.d1_slice_stride +
+                                        row * a.d1_sw + (cb & a.d1_sw_mask) + 4 * g,
+                                    acc[nb], col, w);
+            }
+        } else {
+            if (ri.info & kInfoSpill) {
+                const int64_t slot = (int64_t)(ri.info & kInfoSlotMask);
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) {
+                    const int col = 16 * nb + 4 * g;
+                    const int cb = c0 + 16 * nb;
+                    store_acc4<T, FAST>(D1 + (int64_t)(cb >> a.d1_sw_shift) * a.d1_slice_stride +
+                                            slot * a.d1_sw + (cb & a.d1_sw_mask) + 4 * g,
+                                        acc[nb], col, w);
+                }
+            }
+            if (ri.info & (kInfoDirect | kInfoZero)) {
+                T *dst = static_cast<T *>(a.D) + row * a.ccol + c0 + 4 * g;
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) {
+                    typename Tr<T>::Acc x;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) x[i] = (ri.info & kInfoZero) ? T(0) : ri.sc * acc[nb][i];
+                    store_acc4<T, FAST>(dst + 16 * nb, x, 16 * nb + 4 * g, w);
+                }
             }
         }
     };
@@ -1399,19 +1550,21 @@ __global__ __launch_bounds__(kFusedThreads) void k_gemm(const GemmLaunch a) {
             if constexpr (KSF * Tr<T>::V * NB * (sizeof(T) / 4) > 64) asm volatile("" ::: "memory");
             const int64_t nrow = (lb + nwaves) * 16 + r;
             load_b_frag<T, KSF>(nxt, B + (nrow < a.n ? nrow : a.n - 1) * a.bcol, g);
+            const RowInfo ri = row_info(lb);
             __builtin_amdgcn_sched_barrier(0);      // keep the prefetch ahead of the MFMAs
             typename Tr<T>::Acc acc[NB];
             mfma_frag<T, NB, KSF>(acc, Cl, cur, lane);
-            write_block(lb, acc);
+            write_block(lb, ri, acc);
             cur = nxt;
         }
     } else {
         for (int64_t lb = lb0 + wave; lb < lb1; lb += nwaves) {
             const int64_t row = lb * 16 + r;
             const bool valid = row < a.n;
+            const RowInfo ri = row_info(lb);
             typename Tr<T>::Acc acc[NB];
             mfma_row_block<T, NB, FAST>(acc, Cl, B + (valid ? row : 0) * a.bcol, valid, a.bcol, lane);
-            write_block(lb, acc);
+            write_block(lb, ri, acc);
         }
     }
 }
@@ -1449,11 +1602,13 @@ template <typename K> FusedShape fused_shape(K kernel, int64_t lds_bytes, int ma
     return s;
 }
 
-// Persistent workgroups of the fused kernels: as many per XCD as its 32 CUs hold at once (one or
-// two per CU, by LDS), a multiple of the number of slices, no more than there are (tile, slice) pairs.
+// Persistent workgroups of the fused kernels: as many per XCD as its CUs (an eighth of the
+// device's) hold at once (one or more per CU, by LDS and registers), a multiple of the number of
+// slices, no more than there are (tile, slice) pairs.
 int64_t fused_grid(const FusedLaunch &a, int wg_per_cu) {
     const int64_t per = (a.n_tiles + 7) / 8;
-    int64_t wg_per_xcd = std::min<int64_t>(per * a.n_slices, 32 * (int64_t)wg_per_cu);
+    const int64_t cu_per_xcd = std::max(1, a.n_cu / 8);
+    int64_t wg_per_xcd = std::min<int64_t>(per * a.n_slices, cu_per_xcd * (int64_t)wg_per_cu);
     wg_per_xcd = std::max<int64_t>(a.n_slices, wg_per_xcd / a.n_slices * a.n_slices);
     return 8 * wg_per_xcd;
 }
@@ -1488,6 +1643,7 @@ int run_fused_gemm2(const FusedLaunch &a, hipStream_t st) {
     FusedShape shape;
     if (int e = fused_setup(ks, k_fused_gemm_spmm<T, NB, KS, FAST, SLDS>, a.lds_bytes, kFusedThreads, shape))
         return e;
+    (void)hipGetLastError();      // an error left by an earlier, unrelated call is not this launch's
     k_fused_gemm_spmm<T, NB, KS, FAST, SLDS>
         <<<dim3((unsigned)fused_grid(a, shape.wg_per_cu)), dim3(shape.threads), a.lds_bytes, st>>>(a);
     return (int)hipGetLastError();
@@ -1503,6 +1659,7 @@ template <typename T, bool FAST, bool SLDS> int run_fused_spmm2(const FusedLaunc
     FusedShape shape;
     if (int e = fused_setup(ks, k_fused_spmm_spmm<T, FAST, SLDS>, a.lds_bytes, kFusedSparseThreads, shape))
         return e;
+    (void)hipGetLastError();
     k_fused_spmm_spmm<T, FAST, SLDS>
         <<<dim3((unsigned)fused_grid(a, shape.wg_per_cu)), dim3(shape.threads), a.lds_bytes, st>>>(a);
     return (int)hipGetLastError();
@@ -1511,14 +1668,15 @@ template <typename T, bool FAST> int run_fused_spmm(const FusedLaunch &a, hipStr
     return a.s_in_lds ? run_fused_spmm2<T, FAST, true>(a, st) : run_fused_spmm2<T, FAST, false>(a, st);
 }
 
-template <typename T, int NB, int KS, bool FAST> int run_gemm(const GemmLaunch &a, hipStream_t st) {
+template <typename T, int NB, int KS, bool FAST, bool INFO>
+int run_gemm2(const GemmLaunch &a, hipStream_t st) {
     const int64_t lds = lds_fixed_bytes(a.dtype, 0, a.bcol, a.cs);
     static std::mutex m;
     static int64_t raised = -1;
     {
         std::lock_guard<std::mutex> lock(m);
         if (lds > raised) {
-            const int e = raise_lds_limit(k_gemm<T, NB, KS, FAST>, lds);
+            const int e = raise_lds_limit(k_gemm<T, NB, KS, FAST, INFO>, lds);
             if (e) return e;
             raised = lds;
         }
@@ -1527,8 +1685,13 @@ template <typename T, int NB, int KS, bool FAST> int run_gemm(const GemmLaunch &
     const int64_t nblk = (a.n + 15) / 16;
     int64_t gx = (nblk + nwaves - 1) / nwaves;
     gx = gx < 1 ? 1 : (gx > 1024 ? 1024 : gx);
-    k_gemm<T, NB, KS, FAST><<<dim3((unsigned)gx, (unsigned)a.n_slices), dim3(kFusedThreads), lds, st>>>(a);
+    (void)hipGetLastError();
+    k_gemm<T, NB, KS, FAST, INFO>
+        <<<dim3((unsigned)gx, (unsigned)a.n_slices), dim3(kFusedThreads), lds, st>>>(a);
     return (int)hipGetLastError();
+}
+template <typename T, int NB, int KS, bool FAST> int run_gemm(const GemmLaunch &a, hipStream_t st) {
+    return a.row_info ? run_gemm2<T, NB, KS, FAST, true>(a, st) : run_gemm2<T, NB, KS, FAST, false>(a, st);
 }
 
 // Calls f(NB, KS) with compile-time constants: NB accumulator blocks for the slice width, and
@@ -1606,20 +1769,26 @@ int launch_fused_spmm_spmm(const FusedLaunch &a, void *stream) {
 int launch_packed_spmm(const PackedSpmmLaunch &a, void *stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (a.n_units == 0) return 0;
-    const bool fast = spmm_fast(a.dtype, a.ccol, a.ccol);
-    const dim3 grid((unsigned)((a.n_units + 7) / 8 * 8)), block(kSpmmThreads);
-#define TF_GO(T)                                                                        \
-    do {                                                                                \
-        if (a.wide) {                                                                   \
-            if (fast) k_packed_spmm<T, true, true><<<grid, block, 0, st>>>(a);          \
-            else k_packed_spmm<T, false, true><<<grid, block, 0, st>>>(a);              \
-        } else {                                                                        \
-            if (fast) k_packed_spmm<T, true, false><<<grid, block, 0, st>>>(a);         \
-            else k_packed_spmm<T, false, false><<<grid, block, 0, st>>>(a);             \
-        }                                                                               \
+    if (a.n_xs != 1 && a.n_xs != 2 && a.n_xs != 4 && a.n_xs != 8) return (int)hipErrorInvalidValue;
+    const bool fast = spmm_fast(a.dtype, a.ccol, a.sw);
+    // one workgroup per unit and slice; with slices, 8 / n_xs units per round of eight workgroups
+    const int64_t rounds = a.n_xs == 1 ? (a.n_units + 7) / 8 : (a.n_units * a.n_xs + 7) / 8;
+    const dim3 grid((unsigned)(rounds * 8)), block(kSpmmThreads);
+    (void)hipGetLastError();
+#define TF_GO2(T, W)                                                                     \
+    do {                                                                                 \
+        if (!fast) k_packed_spmm<T, false, W, 4><<<grid, block, 0, st>>>(a);             \
+        else if (a.rows_per_pass == 1) k_packed_spmm<T, true, W, 1><<<grid, block, 0, st>>>(a); \
+        else if (a.rows_per_pass == 2) k_packed_spmm<T, true, W, 2><<<grid, block, 0, st>>>(a); \
+        else k_packed_spmm<T, true, W, 4><<<grid, block, 0, st>>>(a);                    \
+    } while (0)
+#define TF_GO(T)                                                                         \
+    do {                                                                                 \
+        if (a.wide) TF_GO2(T, true); else TF_GO2(T, false);                              \
     } while (0)
     if (a.dtype == TF_F32) TF_GO(float); else TF_GO(double);
 #undef TF_GO
+#undef TF_GO2
     return (int)hipGetLastError();
 }
 
@@ -1631,6 +1800,7 @@ int launch_csr_spmm(const CsrSpmmLaunch &a, void *stream) {
     const bool fast = spmm_fast(a.dtype, a.ccol, a.ccol);
     const int64_t n_wg = (a.n_rows + a.rows_per_wg - 1) / a.rows_per_wg;
     const dim3 grid((unsigned)((n_wg + 7) / 8 * 8)), block(kSpmmThreads);
+    (void)hipGetLastError();
     if (a.dtype == TF_F32) {
         if (fast) k_csr_spmm<float, true><<<grid, block, 0, st>>>(a);
         else k_csr_spmm<float, false><<<grid, block, 0, st>>>(a);

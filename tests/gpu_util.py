@@ -17,6 +17,22 @@ def dev_csr(M):
     return tf.DeviceCsr(M.n_rows, M.n_cols, dev(M.rowptr), dev(M.colidx), dev(M.vals))
 
 
+def read_workspace(plan, s, ccol, dtype, unfused=False):
+    """Host copy of a plan's D1 workspace as a (rows x cCol) array, slot by slot: the device array
+    is d1_slices column slices of d1_slice_cols columns, slice after slice."""
+    import ctypes
+    rows = s["n"] if unfused else s["d1_rows"]
+    n_sl, sw = s["d1_slices"], s["d1_slice_cols"]
+    raw = np.empty(n_sl * rows * sw, dtype=dtype)
+    hip = ctypes.CDLL("libamdhip64.so")
+    hip.hipMemcpy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int]
+    ptr = plan.workspace_unfused() if unfused else plan.workspace()
+    assert ptr, "the workspace does not exist"
+    assert hip.hipMemcpy(raw.ctypes.data, ptr, raw.nbytes, 2) == 0          # device to host
+    out = raw.reshape(n_sl, rows, sw).transpose(1, 0, 2).reshape(rows, n_sl * sw)
+    return np.ascontiguousarray(out[:, :ccol])
+
+
 class Case:
     """One problem resident on the GPU with a plan; `run(fused)` returns D as numpy."""
 

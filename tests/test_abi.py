@@ -35,6 +35,6 @@ def test_binding_has_the_same_names():
 def test_struct_layouts_match_the_header():
     # sizes follow from the field lists in the header (LP64)
     assert ctypes.sizeof(binding.tf_csr) == 3 * 8 + 3 * 8 + 2 * 4
-    assert ctypes.sizeof(binding.tf_tile_params) == 4 + 4 + 8 + 4 + 4
+    assert ctypes.sizeof(binding.tf_tile_params) == 4 + 4 + 8 + 4 + 4 + 4 + 4
     assert ctypes.sizeof(binding.tf_schedule_view) == 2 * 8 + 6 * 4 + 2 * 8 + 4 * 8 + 8 + 3 * 8 + \
-        4 * 8 + 3 * 8 + 3 * 8 + 2 * 4 + 2 * 8 + 2 * 8 + 2 * 8 + 8
+        4 * 8 + 3 * 8 + 3 * 8 + 2 * 4 + 2 * 8 + 2 * 8 + 2 * 8 + 8 + 8 + 8 + 2 * 4 + 8 + 2 * 4 + 8 + 2 * 4

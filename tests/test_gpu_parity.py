@@ -373,7 +373,6 @@ def test_wavefronts_one_by_one_and_the_workspace(kind):
     """tf_run_wavefront(0) writes exactly the fused rows of D and leaves the spilled D1 rows in
     the plan's workspace; tf_run_wavefront(1) then writes exactly the remaining rows.  Integer
     entries: everything is compared bit for bit with the oracle's D1 = B C and D = A D1."""
-    import ctypes
     import torch
     import paper_2407_00243_amd as tf
     dtype = np.float64
@@ -401,17 +400,119 @@ def test_wavefronts_one_by_one_and_the_workspace(kind):
         got = D.cpu().numpy()
         assert np.array_equal(got[fused], D_ref[fused])
         assert np.all(np.isnan(got[~fused]))
-        ws = np.empty((n, ccol), dtype=np.float64)
-        hip = ctypes.CDLL("libamdhip64.so")
-        hip.hipMemcpy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int]
-        assert hip.hipMemcpy(ws.ctypes.data, c.plan.workspace(), ws.nbytes, 2) == 0   # device to host
+        from gpu_util import read_workspace
+        ws = read_workspace(c.plan, s, ccol, np.float64)
         spill = s["spill"].astype(bool)
-        assert np.array_equal(ws[spill], D1_ref[spill])
+        slot = s["spill_slot"]
+        # one slot per spilled row, in row order, none for the others
+        assert ws.shape[0] == max(1, spill.sum()) == s["d1_rows"]
+        assert np.array_equal(slot[spill], np.arange(spill.sum())) and np.all(slot[~spill] == -1)
+        assert np.array_equal(ws[slot[spill]], D1_ref[spill])
         c.plan.run_wavefront(1, None, c.C, D, stream)
         torch.cuda.synchronize()
         assert np.array_equal(D.cpu().numpy(), D_ref)
     finally:
         c.close()
+
+
+# ---------------------------------------------------------------- column slices of the workspace
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("kind", ["gemm_spmm", "spmm_spmm"])
+@pytest.mark.parametrize("ccol,slices", [(128, 8), (128, 4), (128, 2), (64, 4), (64, 2), (32, 2),
+                                         (256, 8), (48, 1)])
+def test_gather_slices_bit_exact(dtype, kind, ccol, slices):
+    """The D1 workspace cut into column slices, each gathered by its own XCDs: a graph-like matrix
+    (rows that reach anywhere, hub rows that are split over many lane groups, rows with only a
+    diagonal entry and empty rows, which leave from registers) with small-integer entries, so that
+    the fused path, the unfused path and the oracle agree bit for bit; the workspaces hold D1 in
+    the sliced layout."""
+    from gpu_util import read_workspace
+    n, bcol = 900, 32
+    A = ti.random_hub_csr(n, dtype, 71)
+    if kind == "gemm_spmm":
+        B = ti.dense_small_int(n, bcol, dtype, 72)
+        D1_ref = oracle.gemm(B, ti.dense_small_int(bcol, ccol, dtype, 73))
+    else:
+        B = ti.random_pattern_csr(n, bcol, 0.2, dtype, 72, int_values=True, empty_row_prob=0.05)
+        D1_ref = oracle.spmm(B.rowptr, B.colidx, B.vals, ti.dense_small_int(bcol, ccol, dtype, 73))
+    C = ti.dense_small_int(bcol, ccol, dtype, 73)
+    prob = ti.Problem("slices", kind, np.dtype(dtype), A, B, C)
+    D_ref, _ = oracle.chain(A, B, C)
+    if slices > 1 and ccol // slices * np.dtype(dtype).itemsize < 64:
+        pytest.skip("slices narrower than 64 bytes are not offered")
+    c = _case(prob, ct_size=128, p=1, gather_slices=slices)
+    try:
+        s = c.plan.schedule()
+        check_schedule(A, s, 128, 1)
+        assert s["d1_slices"] == slices and s["d1_slice_cols"] * slices == ccol
+        assert s["n_direct_rows"] > 0 and s["n_wf1_rows"] > 0
+        D = c.run(fused=True)
+        assert np.array_equal(D.astype(np.float64), D_ref)
+        spill = s["spill"].astype(bool)
+        ws = read_workspace(c.plan, s, ccol, dtype)
+        assert np.array_equal(ws[s["spill_slot"][spill]].astype(np.float64), D1_ref[spill])
+        D = c.run(fused=False)
+        assert np.array_equal(D.astype(np.float64), D_ref)
+        ws = read_workspace(c.plan, s, ccol, dtype, unfused=True)
+        assert np.array_equal(ws.astype(np.float64), D1_ref)
+    finally:
+        c.close()
+
+
+@pytest.mark.parametrize("cfg,width", [(3, 128), (3, 64), (5, 32), (5, 128)])
+@pytest.mark.parametrize("slices", [0, 1, 2, 4, 8])
+def test_graph_configs_with_gather_slices(cfg, width, slices):
+    """Small versions of the graph configurations for every slice count that fits (0 = the
+    inspector's own choice), fused and unfused, against the oracle at the stated tolerance."""
+    prob = ti.config(cfg, scale_down=13, width=width)
+    if slices > 1 and width // slices * prob.dtype.itemsize < 64:
+        pytest.skip("slices narrower than 64 bytes are not offered")
+    for fused in (True, False):
+        s, D, err = _parity(prob, fused=fused, ct_size=256, p=1, gather_slices=slices)
+    assert s["n_direct_rows"] > 0
+    empty = np.diff(prob.A.rowptr) == 0
+    assert np.all(D[empty] == 0)
+    # the same plan with the tiled kernels (a plan that skips unread D1 rows never streams)
+    import paper_2407_00243_amd as tf
+    s2, D2, _ = _parity(prob, fused=True, ct_size=256, p=1, gather_slices=slices,
+                        flags=tf.TF_FLAG_SKIP_UNREAD)
+    assert s2["first_wavefront_streams"] == 0 and np.all(D2[empty] == 0)
+
+
+def test_rows_that_leave_from_registers():
+    """Fused rows with a single diagonal entry are the D1 row times that entry, empty rows are
+    zeros: both are stored by the lanes that hold the D1 row and are listed as fused rows; a plan
+    none of whose fused rows reads the LDS tile keeps no tile (smaller LDS per workgroup)."""
+    import paper_2407_00243_amd as tf
+    n, bcol, ccol = 500, 16, 32
+    rng = np.random.default_rng(5)
+    # diagonal entries only, with every third row empty
+    keep = np.arange(n) % 3 != 0
+    rowptr = np.concatenate([[0], np.cumsum(keep)]).astype(np.int32)
+    diag = ti.Csr(n, n, rowptr, np.nonzero(keep)[0].astype(np.int32),
+                  rng.integers(-2, 3, size=int(keep.sum())).astype(np.float64))
+    for kind in ("gemm_spmm", "spmm_spmm"):
+        if kind == "gemm_spmm":
+            B = ti.dense_small_int(n, bcol, np.float64, 6)
+        else:
+            B = ti.random_pattern_csr(n, bcol, 0.3, np.float64, 6, int_values=True)
+        C = ti.dense_small_int(bcol, ccol, np.float64, 7)
+        prob = ti.Problem("diag", kind, np.dtype(np.float64), diag, B, C)
+        D_ref, _ = oracle.chain(diag, B, C)
+        c = _case(prob, ct_size=64, p=1)
+        try:
+            s = c.plan.schedule()
+            check_schedule(diag, s, 64, 1)
+            assert s["n_fused_rows"] == n == s["n_direct_rows"] and s["n_spill_rows"] == 0
+            assert s["first_wavefront_streams"] == 1
+            with tf.Plan(ti.banded(n, 2, np.float64, 3), bcol, ccol, kind == "spmm_spmm", ct_size=64,
+                         p=1) as other:
+                assert s["lds_launch_bytes"] < other.schedule()["lds_launch_bytes"]
+            assert np.array_equal(c.run(fused=True), D_ref)
+            assert np.array_equal(c.run(fused=False), D_ref)
+        finally:
+            c.close()
 
 
 # ---------------------------------------------------------------- invariants on the GPU
@@ -583,3 +684,63 @@ def test_plans_built_by_one_and_by_many_host_threads_agree():
     rows = np.random.default_rng(7).choice(n, 400, replace=False)
     D_ref, _ = oracle.chain_rows(prob.A, prob.B, prob.C, rows)
     assert np.array_equal(out[1][0][rows].astype(np.float64), D_ref)
+
+
+# ---------------------------------------------------------------- the paper's experiment grid
+
+GRID_SCALE = {1: 3000, 2: 96, 3: 13, 4: 20, 5: 13}
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("width", [32, 64, 128])
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_experiment_grid_with_default_plans(cfg, width, dtype):
+    """Section 4.1 runs every matrix with 32, 64 and 128 columns in single and double precision:
+    every configuration at reduced size over that grid, with the plans the library makes when no
+    tile parameter is given, fused and unfused, against the oracle."""
+    prob = ti.config(cfg, scale_down=GRID_SCALE[cfg], width=width, dtype=dtype)
+    for fused in (True, False):
+        s, D, err = _parity(prob, fused=fused)
+    assert s["automatic"] == 1
+    check_schedule_general(prob.A, s)
+    empty = np.diff(prob.A.rowptr) == 0
+    assert np.all(D[empty] == 0)
+
+
+# ---------------------------------------------------------------- workspaces of 4 GiB and more
+
+def test_workspace_slices_of_four_gib_and_more():
+    """Operand offsets inside a slice of the D1 workspace are formed in 32 bits unless the slice
+    spans 4 GiB or more; this case has such slices on both paths: 10.5 million rows with two
+    columns anywhere in the matrix (nearly nine rows in ten are read by a row of another tile),
+    128 fp32 columns, the workspace kept in one slice.  Rows of D sampled over the whole matrix
+    against the oracle; every row must have been written."""
+    import torch
+    from gpu_util import Case, TOL
+    n, bcol, ccol = 10_500_000, 16, 128
+    rng = np.random.default_rng(77)
+    colidx = rng.integers(0, n, size=2 * n).astype(np.int32)
+    A = ti.Csr(n, n, np.arange(0, 2 * n + 1, 2, dtype=np.int32), colidx,
+               rng.uniform(-1.0, 1.0, size=2 * n).astype(np.float32))
+    prob = ti.Problem("wide", "gemm_spmm", np.dtype(np.float32), A,
+                      ti.dense_normal(n, bcol, np.float32, 78), ti.dense_normal(bcol, ccol, np.float32, 79))
+    print("wide: plan", flush=True)
+    c = Case(prob, ct_size=2048, p=1, gather_slices=1)
+    try:
+        s = c.plan.schedule()
+        assert s["d1_slices"] == 1 and s["d1_rows"] * ccol * 4 >= 1 << 32       # fused workspace
+        rows = np.unique(np.concatenate([[0, 1, n - 2, n - 1], rng.integers(0, n, size=400)]))
+        D_ref, W = oracle.chain_rows(A, prob.B, prob.C, rows)
+        stream = torch.cuda.current_stream().cuda_stream
+        idx = torch.from_numpy(rows).cuda()
+        for fused in (True, False):
+            print(f"wide: fused={fused}", flush=True)
+            D = torch.full((n, ccol), float("nan"), dtype=torch.float32, device="cuda")
+            (c.plan.run if fused else c.plan.run_unfused)(c.B, c.C, D, stream)
+            torch.cuda.synchronize()
+            assert bool(torch.isfinite(D).all()), "a row of D was not written"
+            err = oracle.rowwise_rel_err(D[idx].cpu().numpy(), D_ref, W)
+            assert err <= TOL[np.dtype(np.float32)], (fused, err)
+            del D
+    finally:
+        c.close()

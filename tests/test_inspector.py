@@ -289,3 +289,58 @@ def test_error_paths():
         with pytest.raises(tf.TfError) as e:
             tf.tf_gemm_spmm(pl.handle, 16, 16, 16)
         assert e.value.status_name == "TF_EINVAL"
+
+
+# ---------------------------------------------------------------- the tiling left to the library
+
+def test_defaults_leave_the_tiling_to_the_library_stencils_and_band():
+    """tf_plan_create without tile parameters on the band and stencil configurations at full size:
+    the band keeps Algorithm 1's consecutive tiles (p = a quarter of 256 compute units gives t =
+    64, three quarters of the rows fuse); the stencils in natural ordering, where consecutive
+    tiles that fit the fast memory fuse nothing, get graph-grown tiles.  Fused shares are at least
+    those of the hand-picked parameters the benchmark used before the library chose by itself."""
+    floor = {1: 0.75, 2: 0.80, 4: 0.54}
+    for cfg in (1, 2, 4):
+        prob = ti.config(cfg)
+        s = plan_schedule(prob.A, prob.bcol, prob.ccol, prob.kind == "spmm_spmm")
+        check_schedule_general(prob.A, s)
+        assert s["automatic"] == 1 and s["far_rows"] == 0 and s["n_demoted_rows"] == 0
+        assert s["grown_tiles"] == (0 if cfg == 1 else 1)
+        assert s["fused_ratio_nnz"] >= floor[cfg], (cfg, s["fused_ratio_nnz"])
+        assert s["first_wavefront_streams"] == 0 and s["d1_slices"] == 1
+        if cfg == 1:
+            assert s["t"] == 64
+            check_schedule(prob.A, s, 2048, 64)         # Algorithm 1 to the letter, with p = 64
+        if cfg == 2:
+            assert s["fast_mem_bytes"] == 80 * 1024     # two workgroups per compute unit
+    # any explicit tile size or tile count switches the choice off
+    prob = ti.config(2)
+    s = plan_schedule(prob.A, prob.bcol, prob.ccol, False, ct_size=2048)
+    assert s["automatic"] == 0 and s["grown_tiles"] == 0 and s["n_fused_rows"] == 0
+    check_schedule(prob.A, s, 2048, 32)
+
+
+@pytest.mark.parametrize("cfg", [3, 5])
+def test_defaults_on_graphs_stream_the_first_wavefront(cfg):
+    """The graph configurations at a quarter of their size: only rows with nothing but a diagonal
+    entry (config 3) or with no entry at all (config 5) fuse, plus a handful whose few neighbours
+    happen to sit in the same tile; those are left to the second wavefront (counted), so that no
+    fused row reads the LDS tile and the first wavefront streams.  Config 3's workspace (512-byte
+    rows, more than 64 MiB of them, read from all over the matrix) is cut into four slices."""
+    prob = ti.config(cfg, scale_down=18)
+    A = prob.A
+    s = plan_schedule(A, prob.bcol, prob.ccol, prob.kind == "spmm_spmm")
+    check_schedule_general(A, s)
+    lens = np.diff(A.rowptr.astype(np.int64))
+    diag_only = (lens == 1) & (A.colidx[np.minimum(A.rowptr[:-1], A.nnz - 1)] == np.arange(A.n_rows))
+    assert s["automatic"] == 1 and s["far_rows"] == 1 and s["grown_tiles"] == 0
+    assert s["n_direct_rows"] == int((lens == 0).sum() + diag_only.sum()) == s["n_fused_rows"]
+    assert s["first_wavefront_streams"] == 1
+    assert 0 < s["n_demoted_rows"] < 100
+    assert s["d1_slices"] == (4 if cfg == 3 else 1)
+    assert s["d1_rows"] == s["n_spill_rows"] == int(s["spill"].sum())
+    # the same matrix with Algorithm 1's parameters given keeps every row that a tile can fuse
+    s1 = plan_schedule(A, prob.bcol, prob.ccol, prob.kind == "spmm_spmm", ct_size=2048, p=64)
+    assert s1["n_demoted_rows"] == 0 and s1["n_fused_rows"] == s["n_fused_rows"] + s["n_demoted_rows"]
+    assert s1["first_wavefront_streams"] == 0
+    check_schedule(A, s1, 2048, 64)

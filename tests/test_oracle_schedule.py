@@ -153,6 +153,20 @@ def test_validator_catches_planted_mistakes():
     # V5 is a count, not an error
     s2 = np.ones(n, bool)
     assert so.validate(A.rowptr, A.colidx, tiles, units, s2)["superfluous_spill"] > 0
+    # V6: a tile larger than the fast memory.  Tiles have 20 rows; with a cost of 10 per row a
+    # budget of 200 holds them exactly, one less does not, and a tile that grew by merging two
+    # (still a valid schedule otherwise) breaks a budget that held the original ones
+    cost = lambda rows: 10 * rows
+    so.validate(A.rowptr, A.colidx, tiles, units, res["spill"], tile_cost=cost, fast_mem=200)
+    with pytest.raises(so.ScheduleError, match="V6"):
+        so.validate(A.rowptr, A.colidx, tiles, units, res["spill"], tile_cost=cost, fast_mem=199)
+    merged = so.algorithm1(A.rowptr, A.colidx, ct_size=40, p=1)
+    mt, mu = as_general(merged, n)
+    so.validate(A.rowptr, A.colidx, mt, mu, merged["spill"], tile_cost=cost, fast_mem=400)
+    with pytest.raises(so.ScheduleError, match="V6"):
+        so.validate(A.rowptr, A.colidx, mt, mu, merged["spill"], tile_cost=cost, fast_mem=200)
+    # the check needs both the cost and the budget: without either nothing is tested
+    so.validate(A.rowptr, A.colidx, mt, mu, merged["spill"], tile_cost=cost)
 
 
 def test_validator_with_unread_rows_skipped():

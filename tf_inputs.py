@@ -258,6 +258,35 @@ def random_local_csr(n: int, width: int, nnz_per_row: int, far_prob: float, dtyp
     return Csr(n, n, np.asarray(rowptr, dtype=np.int32), colidx, vals)
 
 
+def random_hub_csr(n: int, dtype, seed: int, n_hubs: int = 3, hub_len: int = 300,
+                   int_values: bool = True) -> Csr:
+    """Small square test matrix with the shape of a graph matrix: most rows hold a few columns
+    anywhere in the matrix (unsorted, may repeat), `n_hubs` rows hold `hub_len` columns, about a
+    fifth of the rows hold only their diagonal entry and about a tenth are empty."""
+    rng = _rng(seed)
+    hubs = set(rng.choice(n, size=min(n_hubs, n), replace=False).tolist())
+    rowptr = [0]
+    cols = []
+    for j in range(n):
+        u = rng.random()
+        if j in hubs:
+            c = rng.integers(0, n, size=hub_len)
+        elif u < 0.1:
+            c = np.zeros(0, dtype=np.int64)
+        elif u < 0.3:
+            c = np.array([j])
+        else:
+            c = rng.integers(0, n, size=int(rng.integers(1, 12)))
+        cols.append(c)
+        rowptr.append(rowptr[-1] + c.size)
+    colidx = np.concatenate(cols).astype(np.int32)
+    if int_values:
+        vals = rng.integers(-2, 3, size=colidx.size).astype(dtype)
+    else:
+        vals = rng.uniform(-1.0, 1.0, size=colidx.size).astype(dtype)
+    return Csr(n, n, np.asarray(rowptr, dtype=np.int32), colidx, vals)
+
+
 def dense_normal(rows: int, cols: int, dtype, seed: int, std: float = 1.0) -> np.ndarray:
     return np.ascontiguousarray((_rng(seed).standard_normal((rows, cols)) * std).astype(dtype))
 
