@@ -217,6 +217,19 @@ tf_status tf_plan_schedule(const tf_plan *plan, tf_schedule_view *out);
 tf_status tf_gemm_spmm(const tf_plan *plan, const void *B, const void *C, void *D,
                        void *hip_stream);
 
+/* tf_gemm_spmm for callers that cannot allocate device memory and do not want a plan-owned
+ * workspace to be touched: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments and result as tf_gemm_spmm, but the D1 rows that cross tiles
+ * go to a fixed array of 64 MiB that is part of the library's code object (one copy per GPU,
+ * held until the process ends) instead of the plan's workspace.  The call allocates nothing.
+ * A plan whose workspace (tf_schedule_view: d1_slices x d1_rows x d1_slice_cols elements) exceeds
+ * 64 MiB is rejected with TF_EUNSUPPORTED.  All calls on one GPU share that GPU's array, whatever
+ * the plan: calls that overlap in time on one GPU race (serialise them on one stream).  The array
+ * keeps the last call's contents; nothing in it needs clearing between calls, since every row is
+ * written by the first wavefront before the second one reads it. */
+tf_status tf_gemm_spmm_static(const tf_plan *plan, const void *B, const void *C, void *D,
+                              void *hip_stream);
+
 /* Fused execution with CSR B (Section 3.2, fused SpMM-SpMM listing).  B must be on the device,
  * n x bCol with the plan's bCol and dtype; C is bCol x cCol.  B may alias A's arrays.
  * B's arrays live on the device and are NOT validated by the execution calls (only its shape

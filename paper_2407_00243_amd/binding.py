@@ -81,7 +81,7 @@ class tf_schedule_view(ctypes.Structure):
 
 
 EXPORTS = ["tf_plan_create", "tf_plan_destroy", "tf_plan_schedule", "tf_plan_workspace",
-           "tf_gemm_spmm", "tf_spmm_spmm", "tf_unfused_gemm_spmm",
+           "tf_gemm_spmm", "tf_gemm_spmm_static", "tf_spmm_spmm", "tf_unfused_gemm_spmm",
            "tf_unfused_spmm_spmm", "tf_run_wavefront", "tf_plan_prepare_unfused", "tf_plan_workspace_unfused",
            "tf_csr_validate", "tf_last_error", "tf_version"]
 _INT_RETURNS = [e for e in EXPORTS if e not in ("tf_last_error", "tf_version")]
@@ -108,6 +108,7 @@ def load_library():
     lib.tf_plan_workspace.argtypes = [vp, ctypes.POINTER(vp)]
     lib.tf_gemm_spmm.argtypes = [vp, vp, vp, vp, vp]
     lib.tf_unfused_gemm_spmm.argtypes = [vp, vp, vp, vp, vp]
+    lib.tf_gemm_spmm_static.argtypes = [vp, vp, vp, vp, vp]
     lib.tf_spmm_spmm.argtypes = [vp, ctypes.POINTER(tf_csr), vp, vp, vp]
     lib.tf_unfused_spmm_spmm.argtypes = [vp, ctypes.POINTER(tf_csr), vp, vp, vp]
     lib.tf_run_wavefront.argtypes = [vp, i32, vp, ctypes.POINTER(tf_csr), vp, vp, vp]
@@ -251,6 +252,10 @@ def tf_csr_validate(M) -> None:
 
 def tf_gemm_spmm(plan: int, B, C, D, stream=None) -> None:
     _check(load_library().tf_gemm_spmm(plan, _addr(B), _addr(C), _addr(D), _addr(stream)))
+
+
+def tf_gemm_spmm_static(plan: int, B, C, D, stream=None) -> None:
+    _check(load_library().tf_gemm_spmm_static(plan, _addr(B), _addr(C), _addr(D), _addr(stream)))
 
 
 def tf_unfused_gemm_spmm(plan: int, B, C, D, stream=None) -> None:

@@ -309,6 +309,33 @@ tf_status second_wavefront(const tf_plan *p, void *D, void *ws, void *stream) {
     return TF_OK;
 }
 
+// Workspace of tf_gemm_spmm_static: one array per GPU, part of the loaded code object, so that
+// the call needs no allocation at all.  In host code the array's name is only a handle; its
+// device address is looked up once per device and used from then on.
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+// Address of the current device's copy of `scratch` (looked up on the first call on that device).
+tf_status static_scratch(void **out) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return fail(TF_EUNSUPPORTED, "device ordinal out of range");
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+        if (!ptr) return fail(TF_EHIP, "hipGetSymbolAddress(scratch) returned a null address");
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return TF_OK;
+}
+
 int device_compute_units() {
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess) return 256;
@@ -594,6 +621,25 @@ tf_status tf_gemm_spmm(const tf_plan *p, const void *B, const void *C, void *D, 
     st = first_wavefront_dense(p, B, C, D, p->d1.p, stream);
     if (st != TF_OK) return st;
     return second_wavefront(p, D, p->d1.p, stream);
+}
+
+tf_status tf_gemm_spmm_static(const tf_plan *p, const void *B, const void *C, void *D, void *stream) {
+    tf_status st = check_exec(p, 0, C, D);
+    if (st != TF_OK) return st;
+    if (!B || !aligned16(B)) return fail(TF_EINVAL, "B must be a 16-byte aligned device pointer");
+    const size_t need = (size_t)p->s.d1.elements() * (size_t)tf::elem_size(p->dtype);
+    if (need > kStaticScratchBytes)
+        return fail(TF_EUNSUPPORTED, "the plan's D1 workspace (" + std::to_string(need) +
+                                         " bytes) exceeds the static workspace of " +
+                                         std::to_string(kStaticScratchBytes) + " bytes");
+    void *ws = nullptr;
+    st = static_scratch(&ws);
+    if (st != TF_OK) return st;
+    // every spilled row is written by the first wavefront before the second one reads it: nothing
+    // in the array has to start at zero
+    st = first_wavefront_dense(p, B, C, D, ws, stream);
+    if (st != TF_OK) return st;
+    return second_wavefront(p, D, ws, stream);
 }
 
 tf_status tf_spmm_spmm(const tf_plan *p, const tf_csr *B, const void *C, void *D, void *stream) {
