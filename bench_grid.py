@@ -6,7 +6,13 @@ matrix collection, plus the tile-size sweep that stands in for its step-1 / step
     python bench_grid.py [--configs 1,2,3,4,5] [--widths 32,64,128] [--dtypes f32,f64]
                          [--sweep-config K --sweep ct_size=64,128,256 | col_slice=16,32,64
                           [--sweep-args "--width 128 --dtype f64"]]
+                         [--ablation]
                          [--steps K] [--warmup W] [--out table.md]
+
+--ablation is the paper's ablation (Section 4.2, "Ablation Study": step 1 alone, then with step 2)
+per configuration: Algorithm 1 with step 1 only (TF_FLAG_NO_SPLIT) at tile sizes 64 ... 2048 (a
+tile that does not fit the fast memory makes the plan fail: "does not fit"), step 1 + step 2 from
+the paper's ctSize = 2048, and the library's own choice (no tile parameters).
 
 Every grid point is one run of bench.py in a child process (cache-cold rotation, no CPU leg);
 this script only collects the JSON lines and prints a table (markdown) with one JSON line per
@@ -54,12 +60,26 @@ def main():
     ap.add_argument("--sweep", default="", help="name=v1,v2,...  (ct_size, col_slice or p)")
     ap.add_argument("--sweep-args", default="", help="further bench.py arguments of a sweep, "
                                                      "e.g. '--width 128 --dtype f64'")
+    ap.add_argument("--ablation", action="store_true")
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=4)
     ap.add_argument("--out", default="")
     a = ap.parse_args()
     lines = [HEAD]
-    if a.sweep_config:
+    if a.ablation:
+        for cfg in a.configs.split(","):
+            points = [(f"step 1 only, t = {t}", ["--ct-size", str(t), "--p", "1", "--no-split"])
+                      for t in (64, 128, 256, 512, 1024, 2048)]
+            points.append(("steps 1 + 2, ctSize = 2048", ["--ct-size", "2048", "--p", "1"]))
+            points.append(("library default", []))
+            for label, extra in points:
+                d = run_point(["--config", cfg] + extra, a.steps, a.warmup)
+                if "error" in d and "does not fit" in d["error"]:
+                    d["error"] = "does not fit the fast memory"
+                label = f"cfg{cfg} {label}"
+                print(json.dumps(dict(point=label, result=d)), file=sys.stderr, flush=True)
+                lines.append(row_of(label, d))
+    elif a.sweep_config:
         name, vals = a.sweep.split("=")
         for v in vals.split(","):
             d = run_point(["--config", str(a.sweep_config), "--" + name.replace("_", "-"), v] +

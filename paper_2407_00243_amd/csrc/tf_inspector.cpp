@@ -19,6 +19,20 @@
 
 #include "tf_internal.h"
 
+// Section timings on stderr, for profiling the inspector on its own (compile with -DTF_TIMING).
+#ifdef TF_TIMING
+#include <cstdio>
+#define TF_TICK(label)                                                                          \
+    do {                                                                                        \
+        const auto tf_now = std::chrono::steady_clock::now();                                   \
+        std::fprintf(stderr, "  [inspector] %-28s %8.2f ms\n", label,                           \
+                     std::chrono::duration<double>(tf_now - tf_tick).count() * 1e3);            \
+        tf_tick = tf_now;                                                                       \
+    } while (0)
+#else
+#define TF_TICK(label)
+#endif
+
 namespace tf {
 
 namespace {
@@ -308,6 +322,9 @@ static PackRules pack_rules(const InspectorInput &in, int64_t count, int sw) {
 tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err) {
     const int64_t n = in.n;
     const int es = elem_size(in.dtype);
+#ifdef TF_TIMING
+    auto tf_tick = std::chrono::steady_clock::now();
+#endif
     s = Schedule();
     s.n = n;
     s.nnz = in.nnz;
@@ -551,19 +568,24 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
     s.far_rows = far_rows;
     bool demote_lds_rows = false;
     Tiling tiling;
+    TF_TICK("setup, far-row sample");
     if (in.flags & TF_FLAG_REORDER) {
         make_grown(tiling);
+        TF_TICK("grown tiles");
     } else {
         make_consecutive(tiling);
         if (automatic && in.nnz > 0) {
             Worth w = evaluate(tiling);
+            TF_TICK("consecutive tiles + worth");
             // consecutive tiles that fuse less than half of the work of a matrix whose rows stay
             // near the diagonal (a stencil in natural ordering): try tiles grown along the graph
             // and keep them if they spill fewer D1 rows, i.e. move fewer bytes
             if (!far_rows && 2 * w.fused_nnz < in.nnz) {
                 Tiling grown;
                 make_grown(grown);
+                TF_TICK("grown tiles");
                 const Worth wg = evaluate(grown);
+                TF_TICK("worth of grown tiles");
                 if (wg.spill_rows < w.spill_rows) {
                     tiling = std::move(grown);
                     w = wg;
@@ -691,7 +713,9 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
         blocks[(size_t)vt] = pack_tile(in.rowptr, in.colidx, vals, es, tile_rows,
                                        [&](int32_t c) { return local_of[c] * pitch16; });
     };
+    TF_TICK("tile maps");
     for_each_item(nt, host_threads(in.nnz, nt, 16), classify);
+    TF_TICK("classify + pack tiles");
     for (int64_t vt = 0; vt < nt; ++vt) {
         const TileResult &tr = res[(size_t)vt];
         const int64_t rows = s.tile_first_ptr[vt + 1] - s.tile_first_ptr[vt];
@@ -714,6 +738,7 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
     s.n_fused_rows = (int64_t)s.second_rows.size();
     if (!s.grown_tiles && !std::is_sorted(wf1.begin(), wf1.end())) std::sort(wf1.begin(), wf1.end());
 
+    TF_TICK("collect tiles");
     // ---- spill set ----------------------------------------------------------------------
     // (several threads may mark the same row: every one of them stores the same byte)
     for_each_item((int64_t)wf1.size(), host_threads(in.nnz, (int64_t)wf1.size(), 4096), [&](int64_t k) {
@@ -780,6 +805,7 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
         const int groups = kSpmmThreads / lane_group(s.d1.sw, vv);
         s.gather_r = groups >= 64 ? 1 : groups >= 32 ? 2 : 4;
     }
+    TF_TICK("spill set, slots, layout");
     // ---- per-tile blocks (see TileDesc) ---------------------------------------------------
     s.tile_desc.resize((size_t)nt);
     s.first_stride = (int32_t)round_up(std::max<int64_t>(s.max_tile_rows, 1), 16);
@@ -859,6 +885,7 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
         s.second_block_in_lds = need <= s.fast_mem_bytes;
     }
 
+    TF_TICK("tile blocks, row arrays");
     // ---- balance: units of the second wavefront --------------------------------------------
     const PackRules wf1_rules = pack_rules(in, (int64_t)wf1.size(), s.d1.sw);
     auto slot_of = [&](int32_t c) { return s.spill_slot[(size_t)c]; };
@@ -867,6 +894,7 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
     s.wf1_unit_ptr.clear();
     for (const UnitDesc &u : s.wf1.units) s.wf1_unit_ptr.push_back(u.row_begin);
     s.wf1_unit_ptr.push_back((int32_t)s.wf1_rows.size());
+    TF_TICK("second-wavefront units");
     return TF_OK;
 }
 
