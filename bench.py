@@ -81,6 +81,9 @@ def parse():
                          "other four under per_config)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--no-per-config", action="store_true", help="headline configuration only")
+    ap.add_argument("--fused-only", action="store_true",
+                    help="skip the unfused baseline (for profiles: every launch of a kernel that both "
+                         "paths share then belongs to the fused path); its figures are null")
     ap.add_argument("--sets", type=int, default=0, help="buffer sets to rotate over (0 = auto)")
     ap.add_argument("--ct-size", type=int, default=None)
     ap.add_argument("--p", type=int, default=None)
@@ -154,7 +157,8 @@ def measure(cfg, args, steps, warmup, headline):
         t1 = time.perf_counter()
         plan = tf.Plan(prob.A, bcol, ccol, sparse, **params)
         plan_seconds.append(time.perf_counter() - t1)
-        plan.prepare_unfused()
+        if not args.fused_only:
+            plan.prepare_unfused()
         if sparse:
             B = tf.DeviceCsr(prob.B.n_rows, prob.B.n_cols, dev(prob.B.rowptr), dev(prob.B.colidx),
                              dev(prob.B.vals))
@@ -206,11 +210,14 @@ def measure(cfg, args, steps, warmup, headline):
 
     # ---- the timed region of the contract: exactly `steps` steps between two synchronisations
     ms_fused = timed(fused, steps, warmup)
-    ms_unfused = timed(unfused, steps, max(2, warmup // 2))
     med_fused = statistics.median(event_times(fused, 7))
-    med_unfused = statistics.median(event_times(unfused, 7))
     warm_fused = statistics.median(event_times(fused, 9, rotate=False)[2:])
-    warm_unfused = statistics.median(event_times(unfused, 9, rotate=False)[2:])
+    if args.fused_only:
+        ms_unfused = med_unfused = warm_unfused = float("nan")
+    else:
+        ms_unfused = timed(unfused, steps, max(2, warmup // 2))
+        med_unfused = statistics.median(event_times(unfused, 7))
+        warm_unfused = statistics.median(event_times(unfused, 9, rotate=False)[2:])
 
     graph_ms = None
     if args.graph and headline:
@@ -323,7 +330,7 @@ def measure(cfg, args, steps, warmup, headline):
         # scheduler time / (baseline time - fused time), as the paper counts it (Section 4, scheduler
         # overhead); plan_ms also holds the uploads and the baseline's own packed copy of A
         "amortisation_runs": (sched["plan_seconds"] * 1e3 / (ms_unfused - ms_fused))
-        if ms_unfused > ms_fused else None,
+        if ms_unfused > ms_fused else None,     # (also None when the baseline was not run)
         "roofline": roofline,
     }
 
@@ -434,7 +441,14 @@ def main():
     out["roofline"] = head["roofline"]
     out["cpu_baseline"] = head.get("cpu_baseline")
     out["per_config"] = per_config
-    print(json.dumps(out), flush=True)
+    # (figures that were not measured are null)
+    def clean(x):
+        if isinstance(x, float) and x != x:
+            return None
+        if isinstance(x, dict):
+            return {k: clean(v) for k, v in x.items()}
+        return x
+    print(json.dumps(clean(out)), flush=True)
 
 
 if __name__ == "__main__":
