@@ -464,37 +464,43 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
                 if (even >= 1 && even < cap) cap = even;
             }
         }
-        std::vector<uint8_t> taken((size_t)n, 0);
-        std::vector<int32_t> queue;
+        // (Growing the tiles of several row ranges at once on the host threads was measured: tiles
+        // cut off at the end of a range fuse less -- 80.6 % of config 2's rows with four ranges, 74 %
+        // with ranges of one tile height, against 82 % -- which costs every execution more than the
+        // millisecond of inspector time it saves.)
+        // tile_no[row]: number of the row's tile, -1 while the row is free
+        std::vector<int32_t> tile_no((size_t)n, -1), queue;
         queue.reserve((size_t)cap);
         int64_t seed = 0, filled = 0;
+        int32_t vt = 0;
         while (filled < n) {
             queue.clear();
             size_t head = 0;
             while ((int64_t)queue.size() < cap && filled + (int64_t)queue.size() < n) {
                 if (head == queue.size()) {               // start (or restart) from a free row
-                    while (taken[seed]) ++seed;
-                    taken[seed] = 1;
+                    while (tile_no[seed] >= 0) ++seed;
+                    tile_no[seed] = vt;
                     queue.push_back((int32_t)seed);
                     continue;
                 }
                 const int32_t j = queue[head++];
                 for (int64_t q = in.rowptr[j]; q < in.rowptr[j + 1]; ++q) {
                     const int32_t c = in.colidx[q];
-                    if (!taken[c] && (int64_t)queue.size() < cap) {
-                        taken[c] = 1;
+                    if (tile_no[c] < 0 && (int64_t)queue.size() < cap) {
+                        tile_no[c] = vt;
                         queue.push_back(c);
                     }
                 }
             }
-            std::copy(queue.begin(), queue.end(), tl.first_rows.begin() + filled);
             filled += (int64_t)queue.size();
             tl.tile_first_ptr.push_back((int32_t)filled);
+            ++vt;
         }
+        // the rows of every tile in ascending order: one pass over the rows instead of a sort per tile
+        std::vector<int32_t> cursor(tl.tile_first_ptr.begin(), tl.tile_first_ptr.end() - 1);
+        for (int64_t row = 0; row < n; ++row)
+            tl.first_rows[(size_t)cursor[(size_t)tile_no[(size_t)row]]++] = (int32_t)row;
         tl.n_coarse = (int64_t)tl.tile_first_ptr.size() - 1;
-        for_each_item(tl.n_coarse, host_threads(in.nnz, tl.n_coarse, 16), [&](int64_t vt) {
-            std::sort(tl.first_rows.begin() + tl.tile_first_ptr[vt], tl.first_rows.begin() + tl.tile_first_ptr[vt + 1]);
-        });
     };
     auto make_consecutive = [&](Tiling &tl) {
         // Algorithm 1: uniform tiles of t consecutive rows (step 1), halved until they fit (step 2)
