@@ -744,3 +744,17 @@ def test_workspace_slices_of_four_gib_and_more():
             del D
     finally:
         c.close()
+
+
+def test_csr_validate_on_device_arrays():
+    """tf_csr_validate copies device arrays to the host and applies the same checks."""
+    import torch
+    import paper_2407_00243_amd as tf
+    from gpu_util import dev_csr
+    B = ti.random_pattern_csr(200, 64, 0.05, np.float64, 8)
+    tf.tf_csr_validate(dev_csr(B))
+    ci = B.colidx.copy()
+    ci[3] = 64
+    with pytest.raises(tf.TfError) as e:
+        tf.tf_csr_validate(dev_csr(B._replace(colidx=ci)))
+    assert e.value.status_name == "TF_EBADCSR"

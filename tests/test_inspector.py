@@ -344,3 +344,28 @@ def test_defaults_on_graphs_stream_the_first_wavefront(cfg):
     assert s1["n_demoted_rows"] == 0 and s1["n_fused_rows"] == s["n_fused_rows"] + s["n_demoted_rows"]
     assert s1["first_wavefront_streams"] == 0
     check_schedule(A, s1, 2048, 64)
+
+
+def test_csr_validate_checks_a_matrix_on_request():
+    """The execution calls take a CSR B as given; tf_csr_validate is the check a caller can run
+    first: monotone row pointers from 0 to nnz, columns inside the matrix (host arrays here)."""
+    B = ti.random_pattern_csr(50, 30, 0.1, np.float32, 3)
+    tf.tf_csr_validate(B)
+
+    def bad(M):
+        with pytest.raises(tf.TfError) as e:
+            tf.tf_csr_validate(M)
+        return e.value.status_name
+
+    rp = B.rowptr.copy()
+    rp[0] = 1
+    assert bad(B._replace(rowptr=rp)) == "TF_EBADCSR"
+    rp = B.rowptr.copy()
+    rp[10], rp[11] = rp[11] + 1, rp[10]
+    assert bad(B._replace(rowptr=rp)) == "TF_EBADCSR"
+    ci = B.colidx.copy()
+    ci[5] = 30                                   # one past the last column
+    assert bad(B._replace(colidx=ci)) == "TF_EBADCSR"
+    ci[5] = -1
+    assert bad(B._replace(colidx=ci)) == "TF_EBADCSR"
+    assert bad(B._replace(rowptr=B.rowptr[:-1].copy(), n_rows=49)) == "TF_EBADCSR"   # rowptr[n] != nnz
