@@ -460,7 +460,35 @@ def test_gather_slices_bit_exact(dtype, kind, ccol, slices):
         c.close()
 
 
-@pytest.mark.parametrize("cfg,width", [(3, 128), (3, 64), (5, 32), (5, 128)])
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+@pytest.mark.parametrize("kind", ["gemm_spmm", "spmm_spmm"])
+@pytest.mark.parametrize("ccol,col_slice,slices", [(128, 64, 4), (128, 32, 2), (128, 64, 8), (64, 32, 4)])
+def test_fused_column_slices_with_workspace_slices(dtype, kind, ccol, col_slice, slices):
+    """A fused workgroup's column slice and the workspace's column slices are independent cuts of
+    the columns: every 16-column block a workgroup produces lands in the workspace slice that holds
+    its columns.  Small integers, bit for bit."""
+    n, bcol = 700, 16
+    if ccol // slices * np.dtype(dtype).itemsize < 64:
+        pytest.skip("slices narrower than 64 bytes are not offered")
+    A = ti.random_hub_csr(n, dtype, 61, n_hubs=2, hub_len=200)
+    if kind == "gemm_spmm":
+        B = ti.dense_small_int(n, bcol, dtype, 62)
+    else:
+        B = ti.random_pattern_csr(n, bcol, 0.3, dtype, 62, int_values=True)
+    C = ti.dense_small_int(bcol, ccol, dtype, 63)
+    prob = ti.Problem("slices2", kind, np.dtype(dtype), A, B, C)
+    D_ref, _ = oracle.chain(A, B, C)
+    c = _case(prob, ct_size=96, p=1, col_slice=col_slice, gather_slices=slices)
+    try:
+        s = c.plan.schedule()
+        assert s["n_slices"] == ccol // col_slice and s["d1_slices"] == slices
+        for fused in (True, False):
+            assert np.array_equal(c.run(fused=fused).astype(np.float64), D_ref), fused
+    finally:
+        c.close()
+
+
+@pytest.mark.parametrize("cfg,width", [(3, 128), (3, 64), (3, 256), (5, 32), (5, 128)])
 @pytest.mark.parametrize("slices", [0, 1, 2, 4, 8])
 def test_graph_configs_with_gather_slices(cfg, width, slices):
     """Small versions of the graph configurations for every slice count that fits (0 = the
