@@ -14,6 +14,8 @@ namespace tf {
 // Limits of the kernels.
 constexpr int kMaxMfmaSliceCols = 128;   // one wave holds at most 8 accumulator blocks of 16 columns
 constexpr int kRowGranuleDense = 16;     // dense-B tiles are produced in blocks of 16 rows (MFMA M/N)
+constexpr int kXcds = 8;                 // XCDs of the device: consecutive workgroup ids are dealt to them round robin,
+                                         // each has its own L2 (the kernels' work-to-workgroup maps and the grid sizes use it)
 constexpr int kFusedThreads = 512;       // workgroup size of the fused kernels
 constexpr int kSpmmThreads = 256;        // workgroup size of the row-list SpMM kernel
 constexpr int kWantedTileRows = 256;     // a default column slice is narrowed until tiles this large fit

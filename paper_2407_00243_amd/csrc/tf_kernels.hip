@@ -82,8 +82,8 @@ __device__ __forceinline__ int pow2_at_least(int x) {
 // units of the second wavefront) should share an L2, so item ids are handed out in eight
 // contiguous ranges, one per XCD: workgroup b works on item (b % 8) * ceil(total / 8) + b / 8.
 __device__ __forceinline__ int64_t xcd_contiguous(int64_t bid, int64_t total) {
-    const int64_t per = (total + 7) >> 3;
-    return (bid & 7) * per + (bid >> 3);
+    const int64_t per = (total + kXcds - 1) / kXcds;
+    return (bid % kXcds) * per + bid / kXcds;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -410,13 +410,13 @@ struct TileWalk {
     int slice, tile, tile_end, step;
 };
 __device__ __forceinline__ TileWalk tile_walk(int n_tiles, int n_slices) {
-    const int per = (n_tiles + 7) >> 3;
-    const int k = blockIdx.x >> 3, wg_per_xcd = gridDim.x >> 3;
+    const int per = (n_tiles + kXcds - 1) / kXcds;
+    const int k = blockIdx.x / kXcds, wg_per_xcd = gridDim.x / kXcds;
     TileWalk t;
     t.slice = k % n_slices;
     t.step = wg_per_xcd / n_slices;
-    t.tile = (blockIdx.x & 7) * per + k / n_slices;
-    t.tile_end = min(n_tiles, ((int)(blockIdx.x & 7) + 1) * per);
+    t.tile = (int)(blockIdx.x % kXcds) * per + k / n_slices;
+    t.tile_end = min(n_tiles, ((int)(blockIdx.x % kXcds) + 1) * per);
     return t;
 }
 
@@ -1231,9 +1231,9 @@ __global__ __launch_bounds__(kSpmmThreads) void k_packed_spmm(const PackedSpmmLa
     if (a.n_xs == 1) {
         u = a.contiguous ? xcd_contiguous(blockIdx.x, a.n_units) : (int64_t)blockIdx.x;
     } else {
-        const int x = blockIdx.x & 7, per = 8 / a.n_xs;
+        const int x = blockIdx.x % kXcds, per = kXcds / a.n_xs;
         slice = x % a.n_xs;
-        u = (int64_t)(blockIdx.x >> 3) * per + x / a.n_xs;
+        u = (int64_t)(blockIdx.x / kXcds) * per + x / a.n_xs;
     }
     if (u >= a.n_units) return;
     const UnitDesc d = a.pack.units[u];
@@ -1606,11 +1606,11 @@ template <typename K> FusedShape fused_shape(K kernel, int64_t lds_bytes, int ma
 // device's) hold at once (one or more per CU, by LDS and registers), a multiple of the number of
 // slices, no more than there are (tile, slice) pairs.
 int64_t fused_grid(const FusedLaunch &a, int wg_per_cu) {
-    const int64_t per = (a.n_tiles + 7) / 8;
-    const int64_t cu_per_xcd = std::max(1, a.n_cu / 8);
+    const int64_t per = (a.n_tiles + kXcds - 1) / kXcds;
+    const int64_t cu_per_xcd = std::max(1, a.n_cu / kXcds);
     int64_t wg_per_xcd = std::min<int64_t>(per * a.n_slices, cu_per_xcd * (int64_t)wg_per_cu);
     wg_per_xcd = std::max<int64_t>(a.n_slices, wg_per_xcd / a.n_slices * a.n_slices);
-    return 8 * wg_per_xcd;
+    return kXcds * wg_per_xcd;
 }
 
 // Per kernel instantiation: the dynamic-LDS limit raised so far (it only ever grows: lowering it
@@ -1772,8 +1772,8 @@ int launch_packed_spmm(const PackedSpmmLaunch &a, void *stream) {
     if (a.n_xs != 1 && a.n_xs != 2 && a.n_xs != 4 && a.n_xs != 8) return (int)hipErrorInvalidValue;
     const bool fast = spmm_fast(a.dtype, a.ccol, a.sw);
     // one workgroup per unit and slice; with slices, 8 / n_xs units per round of eight workgroups
-    const int64_t rounds = a.n_xs == 1 ? (a.n_units + 7) / 8 : (a.n_units * a.n_xs + 7) / 8;
-    const dim3 grid((unsigned)(rounds * 8)), block(kSpmmThreads);
+    const int64_t rounds = (a.n_units * a.n_xs + kXcds - 1) / kXcds;
+    const dim3 grid((unsigned)(rounds * kXcds)), block(kSpmmThreads);
     (void)hipGetLastError();
 #define TF_GO2(T, W)                                                                     \
     do {                                                                                 \
@@ -1799,7 +1799,7 @@ int launch_csr_spmm(const CsrSpmmLaunch &a, void *stream) {
     if (a.rows_per_wg < 1 || a.rows_per_wg > kCsrRowsPerWg) return (int)hipErrorInvalidValue;
     const bool fast = spmm_fast(a.dtype, a.ccol, a.ccol);
     const int64_t n_wg = (a.n_rows + a.rows_per_wg - 1) / a.rows_per_wg;
-    const dim3 grid((unsigned)((n_wg + 7) / 8 * 8)), block(kSpmmThreads);
+    const dim3 grid((unsigned)((n_wg + kXcds - 1) / kXcds * kXcds)), block(kSpmmThreads);
     (void)hipGetLastError();
     if (a.dtype == TF_F32) {
         if (fast) k_csr_spmm<float, true><<<grid, block, 0, st>>>(a);
