@@ -518,6 +518,7 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
     // (all of them, and those of rows that are not direct rows) and the number of D1 rows it spills.
     struct Worth {
         int64_t fused_nnz = 0, lds_nnz = 0, lds_rows = 0, spill_rows = 0;
+        std::vector<uint8_t> spilled;      // the spill set of the tiling (before any row is demoted)
     };
     auto evaluate = [&](const Tiling &tl) {
         const int64_t ntl = (int64_t)tl.tile_first_ptr.size() - 1;
@@ -555,24 +556,31 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
             w.lds_rows += pw.lds_rows;
         }
         w.spill_rows = std::accumulate(spilled.begin(), spilled.end(), (int64_t)0);
+        w.spilled = std::move(spilled);
         return w;
     };
     // Rows that reach far (graphs): mean distance, over a sample of the entries, between a row and
     // the columns it holds, in bytes of D1 rows, against the 4 MiB of one XCD's L2.
     bool far_rows = false;
     if (n > 0 && in.nnz > 0) {
-        const int64_t stride = std::max<int64_t>(1, n / 65536);
+        // the sample: 64 runs of up to 1024 consecutive rows, evenly spread (runs, not single rows:
+        // their entries are read as a stream)
+        const int64_t run = std::min<int64_t>(1024, std::max<int64_t>(1, n / 64));
         double dist = 0.0;
         int64_t cnt = 0;
-        for (int64_t j = 0; j < n; j += stride)
-            for (int64_t q = in.rowptr[j]; q < in.rowptr[j + 1]; ++q) {
-                dist += std::abs((double)in.colidx[q] - (double)j);
-                ++cnt;
-            }
+        for (int64_t k = 0; k < 64; ++k) {
+            const int64_t j0 = std::min(n - run, n * k / 64);
+            for (int64_t j = j0; j < j0 + run; ++j)
+                for (int64_t q = in.rowptr[j]; q < in.rowptr[j + 1]; ++q) {
+                    dist += std::abs((double)in.colidx[q] - (double)j);
+                    ++cnt;
+                }
+        }
         far_rows = cnt > 0 && dist / (double)cnt * (double)in.ccol * es > 4.0 * 1048576.0;
     }
     s.far_rows = far_rows;
     bool demote_lds_rows = false;
+    std::vector<uint8_t> known_spill;      // spill set of the chosen tiling, when it was evaluated
     Tiling tiling;
     TF_TICK("setup, far-row sample");
     if (in.flags & TF_FLAG_REORDER) {
@@ -590,11 +598,11 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
                 Tiling grown;
                 make_grown(grown);
                 TF_TICK("grown tiles");
-                const Worth wg = evaluate(grown);
+                Worth wg = evaluate(grown);
                 TF_TICK("worth of grown tiles");
                 if (wg.spill_rows < w.spill_rows) {
                     tiling = std::move(grown);
-                    w = wg;
+                    w = std::move(wg);
                 }
             }
             // Fused rows that read the LDS tile make every workgroup keep a tile in LDS and pass
@@ -603,6 +611,7 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
             // handful of such rows, first wavefront 0.44 ms with tiles against 0.31 ms without):
             // they are left to the second wavefront and the first wavefront streams.
             demote_lds_rows = w.lds_rows > 0 && 50 * w.lds_nnz < in.nnz;
+            known_spill = std::move(w.spilled);
         }
     }
     s.first_rows = std::move(tiling.first_rows);
@@ -672,7 +681,7 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
     // lets several host threads share the tiles of a large matrix; the results are put together
     // in tile order afterwards, so the schedule does not depend on the number of threads.
     struct TileResult {
-        std::vector<int32_t> wf1, direct;
+        std::vector<int32_t> wf1, direct, demoted_rows;
         int64_t tile_nnz = 0, uc = 0, nj = 0, demoted = 0;
     };
     std::vector<TileResult> res((size_t)nt);
@@ -695,6 +704,7 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
             if (inside && demote_lds_rows && !direct) {
                 inside = false;
                 ++tr.demoted;
+                tr.demoted_rows.push_back((int32_t)j);
             }
             if (inside) {
                 if (direct) {
@@ -746,16 +756,25 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
 
     TF_TICK("collect tiles");
     // ---- spill set ----------------------------------------------------------------------
-    // (several threads may mark the same row: every one of them stores the same byte)
-    for_each_item((int64_t)wf1.size(), host_threads(in.nnz, (int64_t)wf1.size(), 4096), [&](int64_t k) {
-        const int32_t j = wf1[(size_t)k];
-        for (int64_t q = in.rowptr[j]; q < in.rowptr[j + 1]; ++q) {
-            // (a marked row is not written again: the columns of hub rows would otherwise keep
-            // their cache lines travelling between the threads)
-            uint8_t *m = &s.spill[(size_t)in.colidx[q]];
-            if (!__atomic_load_n(m, __ATOMIC_RELAXED)) __atomic_store_n(m, (uint8_t)1, __ATOMIC_RELAXED);
-        }
-    });
+    if (!known_spill.empty() && !(in.flags & TF_FLAG_SKIP_UNREAD)) {
+        // the tiling was evaluated: its spill set is known; rows left to the second wavefront since
+        // then add the rows they read
+        s.spill = std::move(known_spill);
+        for (const TileResult &tr : res)
+            for (int32_t j : tr.demoted_rows)
+                for (int64_t q = in.rowptr[j]; q < in.rowptr[j + 1]; ++q) s.spill[(size_t)in.colidx[q]] = 1;
+    } else {
+        // (several threads may mark the same row: every one of them stores the same byte)
+        for_each_item((int64_t)wf1.size(), host_threads(in.nnz, (int64_t)wf1.size(), 4096), [&](int64_t k) {
+            const int32_t j = wf1[(size_t)k];
+            for (int64_t q = in.rowptr[j]; q < in.rowptr[j + 1]; ++q) {
+                // (a marked row is not written again: the columns of hub rows would otherwise keep
+                // their cache lines travelling between the threads)
+                uint8_t *m = &s.spill[(size_t)in.colidx[q]];
+                if (!__atomic_load_n(m, __ATOMIC_RELAXED)) __atomic_store_n(m, (uint8_t)1, __ATOMIC_RELAXED);
+            }
+        });
+    }
     s.n_spill_rows = std::accumulate(s.spill.begin(), s.spill.end(), (int64_t)0);
     if (s.n_spill_rows > (int64_t)kInfoSlotMask) {
         err = "more than 2^29 D1 rows cross tiles";
