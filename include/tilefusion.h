@@ -255,7 +255,7 @@ tf_status tf_unfused_spmm_spmm(const tf_plan *plan, const tf_csr *B, const void 
 tf_status tf_run_wavefront(const tf_plan *plan, int32_t wavefront, const void *B_dense,
                            const tf_csr *B_csr, const void *C, void *D, void *hip_stream);
 
-/* Allocates the n x cCol workspace of the unfused baseline if it does not exist yet. */
+/* Allocates the workspace of the unfused baseline (all n rows of D1) if it does not exist yet. */
 tf_status tf_plan_prepare_unfused(const tf_plan *plan);
 
 /* Device pointer of the plan's D1 workspace: after a fused execution slot spill_slot[i] holds D1

@@ -112,10 +112,11 @@ inline int mfma_ksteps_special(int dtype, int bcol, int ccol, int cs) {
     return (ks == 2 || ks == 4 || ks == 8 || ks == 16) ? ks : 0;
 }
 
-// What a fused workgroup needs to know about one tile: the ids of its D1 rows (bit 31 = spill)
-// in an array with the same stride for every tile, so that their address follows from the tile's
-// number alone (the first loads of a workgroup do not wait for a descriptor); padding up to the
-// stride repeats the last row without the bit.  And, so that nothing in the tile waits for a
+// What a fused workgroup needs to know about one tile: the ids of its D1 rows, one info word per
+// row (kInfo*: spill slot, direct, zero) and the diagonal entry of direct rows, in three arrays with
+// the same stride for every tile, so that their addresses follow from the tile's number alone
+// (the first loads of a workgroup do not wait for a descriptor); padding up to the stride repeats
+// the last row, with an empty info word.  And, so that nothing in the tile waits for a
 // chain of dependent loads (row list -> unit -> entries), this fixed-size descriptor plus one
 // contiguous, 16-byte aligned second-phase block of s_bytes bytes (each array padded to 16 bytes):
 //   TileUnit units[n_units]
@@ -128,7 +129,7 @@ struct TileDesc {
     int64_t meta_off;      // byte offset of the block
     int32_t n_rows;        // D1 rows the tile produces
     int32_t n_units;
-    int32_t n_second;      // fused rows of D
+    int32_t n_second;      // fused rows of D that read the LDS tile (direct rows are not among them)
     int32_t n_entries;     // padded entries over all units
     int32_t s_bytes;       // size of the second-phase block
     int32_t reserved;
