@@ -1351,35 +1351,65 @@ __global__ __launch_bounds__(kSpmmThreads) void k_packed_spmm(const PackedSpmmLa
             T acc[VV];
 #pragma unroll
             for (int i = 0; i < VV; ++i) acc[i] = T(0);
-            if (row_i < d.n_rows) {
-                const int64_t at = d.entry_base + (int64_t)row_i * d.slots;
-                const int32_t *__restrict__ ip = idx + at;
-                const T *__restrict__ vp = val + at;
-                int sl = s0;
-                for (; sl + 8 <= s1; sl += 8) {
-                    uint32_t c[8];
-                    T v[8];
-                    T x[8][VV];
+            // The entries of the group's part travel through LDS as well, a window of 8 G slots at a
+            // time: the G lanes fetch them with coalesced loads (one word per lane and load instead of
+            // the same word for every lane), put them into the group's piece of the staging arrays,
+            // and read them back as broadcasts, 8 per pass.  The next window's entries are in flight
+            // while the current window is gathered.  A group is part of one wave and LDS operations
+            // of a wave complete in order, so no workgroup barrier is involved.
+            const int WS = 8 * G;
+            int32_t *gi = idx_s + grp * WS;
+            T *gv = val_s + grp * WS;
+            const bool has_row = row_i < d.n_rows;
+            const int64_t at = d.entry_base + (int64_t)(has_row ? row_i : 0) * d.slots;
+            const int32_t *__restrict__ ip = idx + at;
+            const T *__restrict__ vp = val + at;
+            int32_t ci[8];
+            T vi[8];
+            auto fetch_window = [&](int w0) {          // slots past the part's end repeat its last one
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        c[e] = (uint32_t)ip[sl + e];
-                        v[e] = vp[sl + e];
-                    }
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) load_x<T, VV, WIDE>(x[e], X, c[e], ldx, lane_off);
-#pragma unroll
-                    for (int e = 0; e < 8; ++e)
-#pragma unroll
-                        for (int i = 0; i < VV; ++i) acc[i] += v[e] * x[e][i];
+                for (int k = 0; k < 8; ++k) {
+                    const int e = w0 + k * G + gl;
+                    const int ec = e < s1 ? e : s1 - 1;
+                    ci[k] = ip[ec];
+                    vi[k] = e < s1 ? vp[ec] : T(0);
                 }
-                for (; sl < s1; ++sl) {
-                    T x[VV];
-                    load_x<T, VV, WIDE>(x, X, (uint32_t)ip[sl], ldx, lane_off);
-                    const T v = vp[sl];
+            };
+            if (has_row && s0 < s1) {
+                fetch_window(s0);
+                for (int w0 = s0; w0 < s1; w0 += WS) {
 #pragma unroll
-                    for (int i = 0; i < VV; ++i) acc[i] += v * x[i];
+                    for (int k = 0; k < 8; ++k) {
+                        gi[k * G + gl] = ci[k];
+                        gv[k * G + gl] = vi[k];
+                    }
+                    if (w0 + WS < s1) fetch_window(w0 + WS);
+                    __builtin_amdgcn_wave_barrier();
+                    asm volatile("" ::: "memory");
+                    const int n_here = min(WS, s1 - w0);
+                    for (int p0 = 0; p0 < n_here; p0 += 8) {
+                        uint32_t c[8];
+                        T v[8];
+                        T x[8][VV];
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            c[e] = (uint32_t)gi[p0 + e];
+                            v[e] = gv[p0 + e];
+                        }
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) load_x<T, VV, WIDE>(x[e], X, c[e], ldx, lane_off);
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            if (p0 + e >= n_here) continue;      // (a surplus slot adds nothing)
+#pragma unroll
+                            for (int i = 0; i < VV; ++i) acc[i] += v[e] * x[e][i];
+                        }
+                    }
+                    __builtin_amdgcn_wave_barrier();
+                    asm volatile("" ::: "memory");
                 }
             }
+            __syncthreads();          // the staging arrays become the partial sums
 #pragma unroll
             for (int i = 0; i < VV; ++i) red[(grp * G + gl) * VV + i] = acc[i];
             __syncthreads();
