@@ -458,7 +458,8 @@ tf_status tf_plan_create(const tf_csr *A, int64_t bCol, int64_t cCol, int32_t b_
             return TF_OK;
         }
         p->has_baseline = !(tp && (tp->flags & TF_FLAG_NO_BASELINE));
-        if (p->has_baseline) tf::build_baseline_pack(in, p->s);
+        if (p->has_baseline && !tf::build_baseline_pack(in, p->s))
+            return fail(TF_EUNSUPPORTED, "internal: a unit of the baseline exceeds the staging arrays of the gather kernel");
         p->lds_per_cu = lds_limit;
         // the launch must fit the device whatever the schedule's own estimate said
         auto launch_lds = [&]() {

@@ -319,6 +319,15 @@ static PackRules pack_rules(const InspectorInput &in, int64_t count, int sw) {
                      groups};
 }
 
+// The gather kernel stages the entries of a unit whose rows are not split in LDS arrays of
+// kUnitSlots entries; a unit beyond that would write past them.  pack_rows never cuts one (rows that
+// long are split), this is the check behind that.
+static bool units_fit_staging(const RowPack &pk) {
+    for (const UnitDesc &u : pk.units)
+        if (u.split <= 1 && (int64_t)u.n_rows * u.slots > kUnitSlots) return false;
+    return true;
+}
+
 tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err) {
     const int64_t n = in.n;
     const int es = elem_size(in.dtype);
@@ -915,6 +924,10 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
     const PackRules wf1_rules = pack_rules(in, (int64_t)wf1.size(), s.d1.sw);
     auto slot_of = [&](int32_t c) { return s.spill_slot[(size_t)c]; };
     pack_rows(in.rowptr, in.colidx, vals, es, wf1, wf1_rules, true, slot_of, s.wf1);
+    if (!units_fit_staging(s.wf1)) {
+        err = "internal: a unit of the second wavefront exceeds the staging arrays of the gather kernel";
+        return TF_EUNSUPPORTED;
+    }
     s.wf1_rows = s.wf1.rows;
     s.wf1_unit_ptr.clear();
     for (const UnitDesc &u : s.wf1.units) s.wf1_unit_ptr.push_back(u.row_begin);
@@ -923,12 +936,13 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
     return TF_OK;
 }
 
-void build_baseline_pack(const InspectorInput &in, Schedule &s) {
+bool build_baseline_pack(const InspectorInput &in, Schedule &s) {
     std::vector<int32_t> all((size_t)in.n);
     std::iota(all.begin(), all.end(), 0);
     auto ident = [](int32_t c) { return c; };
     pack_rows(in.rowptr, in.colidx, static_cast<const unsigned char *>(in.vals), elem_size(in.dtype),
               all, pack_rules(in, in.n, s.d1.sw), true, ident, s.all);
+    return units_fit_staging(s.all);
 }
 
 }  // namespace tf

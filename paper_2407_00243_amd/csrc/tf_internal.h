@@ -23,6 +23,10 @@ constexpr int kUnitRows = 64;            // most rows in one unit of a packed ro
 constexpr int kUnitSlots = 2048;         // most padded entries (rows x slots) in one such unit (they are staged in LDS)
 constexpr int kSplitMinSlots = 128;      // rows at least this long are split over several lane groups
 constexpr int kSplitPartSlots = 96;      // target slots per part of a split row
+// a row long enough to be split gets at least two parts: units whose rows are not split are staged
+// in LDS whole (kUnitSlots entries at most), so a row that long must never end up in one
+static_assert(kSplitMinSlots > kSplitPartSlots && kSplitMinSlots <= kUnitSlots,
+              "rows of kSplitMinSlots entries or more must be split");
 constexpr int kGatherSliceBytes = 128;    // narrowest column slice of the gather kernel chosen by default, bytes
 
 // Per D1 row of a tile, beside its row id: one info word.  kInfoSpill: the row is also stored to
@@ -275,7 +279,8 @@ struct InspectorInput {
 tf_status build_schedule(const InspectorInput &in, Schedule &out, std::string &err);
 // The packed copy of all rows of A that the unfused baseline's second operation runs on
 // (Schedule::all).  Not part of the fused schedule and not counted in its time.
-void build_baseline_pack(const InspectorInput &in, Schedule &s);
+// (false: a unit exceeds the gather kernel's staging arrays; never expected)
+bool build_baseline_pack(const InspectorInput &in, Schedule &s);
 
 
 // ---------------------------------------------------------------- device launch interface
