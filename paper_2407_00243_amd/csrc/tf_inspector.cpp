@@ -188,13 +188,13 @@ void pack_rows(const int32_t *rowptr, const int32_t *colidx, const unsigned char
         at = (at + take * L + 3) / 4 * 4;
         pos += take;
     }
-    const int64_t end = at + 4;                       // four spare entries behind the last unit
+    const int64_t end = at + kPackSpareSlots;         // spare zero entries behind the last unit
     out.idx32.resize((size_t)end);
     out.vals.resize((size_t)end * es);
     const int64_t n_new = (int64_t)(out.units.size() - first_unit);
     if (n_new == 0) {
-        std::memset(out.idx32.data() + at, 0, 4 * 4);
-        std::memset(out.vals.data() + (size_t)at * es, 0, (size_t)4 * es);
+        std::memset(out.idx32.data() + at, 0, (size_t)kPackSpareSlots * 4);
+        std::memset(out.vals.data() + (size_t)at * es, 0, (size_t)kPackSpareSlots * es);
     }
     for_each_item(n_new, host_threads(real, n_new, 64), [&](int64_t k) {
         const UnitDesc &u = out.units[first_unit + (size_t)k];

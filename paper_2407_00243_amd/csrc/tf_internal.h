@@ -21,6 +21,9 @@ constexpr int kSpmmThreads = 256;        // workgroup size of the row-list SpMM 
 constexpr int kWantedTileRows = 256;     // a default column slice is narrowed until tiles this large fit
 constexpr int kUnitRows = 64;            // most rows in one unit of a packed row list
 constexpr int kUnitSlots = 2048;         // most padded entries (rows x slots) in one such unit (they are staged in LDS)
+constexpr int kPackSpareSlots = 8 * 64 + 8;  // zero entries behind the last unit of a packed row list: the gather kernel
+                                         // fetches the entries of split rows in windows of 8 slots per lane of a lane
+                                         // group (64 lanes at most), which may reach that far past the last row
 constexpr int kSplitMinSlots = 128;      // rows at least this long are split over several lane groups
 constexpr int kSplitPartSlots = 96;      // target slots per part of a split row
 // a row long enough to be split gets at least two parts: units whose rows are not split are staged

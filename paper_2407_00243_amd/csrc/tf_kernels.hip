@@ -1364,15 +1364,20 @@ __global__ __launch_bounds__(kSpmmThreads) void k_packed_spmm(const PackedSpmmLa
             const int64_t at = d.entry_base + (int64_t)(has_row ? row_i : 0) * d.slots;
             const int32_t *__restrict__ ip = idx + at;
             const T *__restrict__ vp = val + at;
+            // Lane gl fetches the eight consecutive slots 8 gl .. 8 gl + 7 of a window (one address,
+            // eight immediate offsets).  A window may reach past the end of the part, of the row and,
+            // for the last row of the list, of the packed arrays, which therefore end with
+            // kPackSpareSlots zero entries: whatever index is read there names a valid row, and
+            // slots past the part's end are left out of the sum.
             int32_t ci[8];
             T vi[8];
-            auto fetch_window = [&](int w0) {          // slots past the part's end repeat its last one
+            const int32_t *__restrict__ ipl = ip + 8 * gl;
+            const T *__restrict__ vpl = vp + 8 * gl;
+            auto fetch_window = [&](int w0) {
 #pragma unroll
                 for (int k = 0; k < 8; ++k) {
-                    const int e = w0 + k * G + gl;
-                    const int ec = e < s1 ? e : s1 - 1;
-                    ci[k] = ip[ec];
-                    vi[k] = e < s1 ? vp[ec] : T(0);
+                    ci[k] = ipl[w0 + k];
+                    vi[k] = vpl[w0 + k];
                 }
             };
             if (has_row && s0 < s1) {
@@ -1380,8 +1385,8 @@ __global__ __launch_bounds__(kSpmmThreads) void k_packed_spmm(const PackedSpmmLa
                 for (int w0 = s0; w0 < s1; w0 += WS) {
 #pragma unroll
                     for (int k = 0; k < 8; ++k) {
-                        gi[k * G + gl] = ci[k];
-                        gv[k * G + gl] = vi[k];
+                        gi[8 * gl + k] = ci[k];
+                        gv[8 * gl + k] = vi[k];
                     }
                     if (w0 + WS < s1) fetch_window(w0 + WS);
                     __builtin_amdgcn_wave_barrier();
