@@ -105,7 +105,8 @@ typedef struct tf_tile_params {
  * by the fused calls: they leave the tiles' first lists.  The paper's schedule runs every
  * iteration of both operations exactly once (Section 3.1); this flag gives that up for the first
  * operation, D is unchanged.  The unfused calls still compute all of D1, and after a fused call
- * the workspace rows of skipped D1 rows are not written. */
+ * the workspace rows of skipped D1 rows are not written.  (A plan for a CSR B whose first
+ * wavefront streams leaves the rows out one by one instead; the schedule view is the same.) */
 #define TF_FLAG_SKIP_UNREAD 16u
 /* The plan serves the fused calls only: the packed copy of all rows of A that the unfused
  * baseline runs on is not built (saves its time and device memory); tf_unfused_* then fail with

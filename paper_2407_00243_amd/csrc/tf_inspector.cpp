@@ -651,6 +651,7 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
         return TF_EUNSUPPORTED;
     }
     std::vector<int32_t> wf1;
+    int64_t lds_nonempty = 0;          // fused rows that read the LDS tile and have entries
     // A row belongs to one tile: there it is a candidate for fusion and there its D1 row is
     // produced.  With TF_FLAG_SKIP_UNREAD the D1 rows that no row of A reads are not produced at
     // all: they leave the tiles' first lists (a tile keeps at least one row) and get no place in LDS.
@@ -691,7 +692,7 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
     // in tile order afterwards, so the schedule does not depend on the number of threads.
     struct TileResult {
         std::vector<int32_t> wf1, direct, demoted_rows;
-        int64_t tile_nnz = 0, uc = 0, nj = 0, demoted = 0;
+        int64_t tile_nnz = 0, uc = 0, nj = 0, demoted = 0, lds_nonempty = 0;
     };
     std::vector<TileResult> res((size_t)nt);
     auto classify = [&](int64_t vt) {
@@ -710,7 +711,7 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
             }
             const int64_t ln = in.rowptr[j + 1] - in.rowptr[j];
             const bool direct = kept[j] && (ln == 0 || (ln == 1 && in.colidx[in.rowptr[j]] == (int32_t)j));
-            if (inside && demote_lds_rows && !direct) {
+            if (inside && demote_lds_rows && !direct && ln > 0) {       // (a row without entries reads no tile)
                 inside = false;
                 ++tr.demoted;
                 tr.demoted_rows.push_back((int32_t)j);
@@ -721,6 +722,8 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
                     tr.direct.push_back((int32_t)j);
                 } else {
                     tile_rows.push_back((int32_t)j);
+                    direct_kind[j] = 3;          // fused through the LDS tile
+                    if (ln > 0) ++tr.lds_nonempty;
                 }
                 for (int64_t q = in.rowptr[j]; q < in.rowptr[j + 1]; ++q) {
                     const int32_t c = in.colidx[q];
@@ -750,6 +753,7 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
                              blocks[(size_t)vt].rows.end());
         s.second_rows.insert(s.second_rows.end(), tr.direct.begin(), tr.direct.end());
         s.n_demoted_rows += tr.demoted;
+        lds_nonempty += tr.lds_nonempty;
         s.n_lds_rows += (int64_t)blocks[(size_t)vt].rows.size();
         s.n_direct_rows += (int64_t)tr.direct.size();
         // Eq. 2 (diagnostic): (nz + uc + t + |J|) * cCol + idx, counted in elements; for a dense B
@@ -786,7 +790,7 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
     }
     s.n_spill_rows = std::accumulate(s.spill.begin(), s.spill.end(), (int64_t)0);
     if (s.n_spill_rows > (int64_t)kInfoSlotMask) {
-        err = "more than 2^29 D1 rows cross tiles";
+        err = "more than 2^28 D1 rows cross tiles";
         return TF_EUNSUPPORTED;
     }
     // Only the rows in the spill set reach device memory (one barrier: nothing else crosses tiles),
@@ -891,23 +895,32 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
         TileBlock().bytes.swap(tb.bytes);
     });
     // A plan none of whose fused rows reads the LDS tile needs no tiles at execution: the first
-    // wavefront streams through the rows; the same words again, by row.  (Not when unread D1 rows
-    // are skipped: the streaming kernels produce every row.)
-    s.streaming = s.n_lds_rows == 0 && !(in.flags & TF_FLAG_SKIP_UNREAD) && n > 0;
+    // wavefront streams through the rows, and what happens to each finished D1 row is told by a word
+    // per row.  (Fused rows without entries read nothing: where unread D1 rows are skipped some of
+    // them have no D1 row of their own to leave with and sit in the tiles' second lists; by row they
+    // are zero rows like the others.)  With TF_FLAG_SKIP_UNREAD only a CSR B streams: its kernel
+    // leaves out single rows (kInfoSkip), the dense product works on blocks of sixteen.
+    const bool skip_unread = in.flags & TF_FLAG_SKIP_UNREAD;
+    s.streaming = n > 0 && lds_nonempty == 0 && (!skip_unread || in.b_is_sparse);
     if (s.streaming) {
         s.row_info.assign((size_t)n, 0u);
-        if (s.n_direct_rows > 0) {
+        const bool scales = s.n_direct_rows > 0;
+        if (scales) {
             s.row_scale.resize((size_t)n * es);
             std::memset(s.row_scale.data(), 0, s.row_scale.size());
         }
         for_each_item(nt, host_threads(in.nnz, nt, 16), [&](int64_t vt) {
-            const int64_t f0 = s.tile_first_ptr[vt], f1 = s.tile_first_ptr[vt + 1];
-            for (int64_t q = f0; q < f1; ++q) {
-                const int32_t row = s.first_rows[q];
-                const size_t at = (size_t)vt * s.first_stride + (size_t)(q - f0);
-                s.row_info[(size_t)row] = s.tile_info[at];
-                if (s.n_direct_rows > 0)
-                    std::memcpy(s.row_scale.data() + (size_t)row * es, s.tile_scale.data() + at * es, (size_t)es);
+            for (int64_t q = member_ptr[vt]; q < member_ptr[vt + 1]; ++q) {
+                const int32_t row = member_rows[q];
+                uint32_t w = s.spill[row] ? (kInfoSpill | (uint32_t)s.spill_slot[row]) : 0u;
+                if (direct_kind[row] == 1) {
+                    w |= kInfoDirect;
+                    std::memcpy(s.row_scale.data() + (size_t)row * es, vals + (size_t)in.rowptr[row] * es, (size_t)es);
+                } else if (direct_kind[row] == 2 || direct_kind[row] == 3) {
+                    w |= kInfoZero;
+                }
+                if (skip_unread && !kept[row]) w |= kInfoSkip;
+                s.row_info[(size_t)row] = w;
             }
         });
     }

@@ -41,7 +41,10 @@ constexpr int kGatherSliceBytes = 128;    // narrowest column slice of the gathe
 constexpr uint32_t kInfoSpill = 0x80000000u;
 constexpr uint32_t kInfoDirect = 0x40000000u;
 constexpr uint32_t kInfoZero = 0x20000000u;
-constexpr uint32_t kInfoSlotMask = 0x1fffffffu;
+// kInfoSkip (streaming first wavefront of a CSR-B plan with TF_FLAG_SKIP_UNREAD only): no row of A
+// reads this D1 row, it is not computed.
+constexpr uint32_t kInfoSkip = 0x10000000u;
+constexpr uint32_t kInfoSlotMask = 0x0fffffffu;
 
 // Where the D1 rows that cross tiles live in device memory: `n_sl` column slices of `sw` columns
 // each (the last may be narrower in use, never in storage), slice after slice, each slice a dense

@@ -1455,7 +1455,18 @@ __global__ __launch_bounds__(kSpmmThreads) void k_csr_spmm(const CsrSpmmLaunch a
     __shared__ __align__(16) int32_t idx_s[kSparseEntryCap * kCsrRowsPerWg];
     __shared__ __align__(16) T val_s[kSparseEntryCap * kCsrRowsPerWg];
     const int rows = (int)(r1 - r0);
-    stage_extents(rows, ext_s, a.S.rowptr, [&](int i) { return r0 + i; });
+    if (!a.row_info) {
+        stage_extents(rows, ext_s, a.S.rowptr, [&](int i) { return r0 + i; });
+    } else {
+        // a row whose D1 row nobody reads and that the plan leaves out counts as empty here: nothing
+        // of it is fetched (its gathers name row 0 of X with a zero value)
+        for (int i = threadIdx.x; i < rows; i += (int)blockDim.x) {
+            const int64_t rid = r0 + i;
+            const int kb = a.S.rowptr[rid], ke = a.S.rowptr[rid + 1];
+            ext_s[2 * i] = kb;
+            ext_s[2 * i + 1] = (a.row_info[rid] & kInfoSkip) ? 0 : ke - kb;
+        }
+    }
     __syncthreads();
     stage_entries<T>(rows, ext_s, idx_s, val_s, a.S.colidx, vals);
     for (int cb = 0; cb < ccol; cb += G * VV) {

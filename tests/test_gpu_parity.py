@@ -501,11 +501,21 @@ def test_graph_configs_with_gather_slices(cfg, width, slices):
     assert s["n_direct_rows"] > 0
     empty = np.diff(prob.A.rowptr) == 0
     assert np.all(D[empty] == 0)
-    # the same plan with the tiled kernels (a plan that skips unread D1 rows never streams)
+    # the same with the unread D1 rows skipped: a dense B then runs the tiled kernels (the dense
+    # product works on blocks of sixteen rows and cannot leave single rows out), a CSR B still
+    # streams and leaves the rows out one by one
     import paper_2407_00243_amd as tf
-    s2, D2, _ = _parity(prob, fused=True, ct_size=256, p=1, gather_slices=slices,
+    # (tiling left to the library, which leaves the few rows that would read an LDS tile to the
+    # second wavefront)
+    s2, D2, _ = _parity(prob, fused=True, gather_slices=slices, flags=tf.TF_FLAG_SKIP_UNREAD)
+    assert s2["first_wavefront_streams"] == (1 if prob.kind == "spmm_spmm" else 0)
+    assert np.all(D2[empty] == 0)
+    if cfg == 5:
+        assert s2["n_first_rows"] < prob.n
+    # and with given tile parameters (tiled kernels, rows leave the tiles' first lists)
+    s3, D3, _ = _parity(prob, fused=True, ct_size=256, p=1, gather_slices=slices,
                         flags=tf.TF_FLAG_SKIP_UNREAD)
-    assert s2["first_wavefront_streams"] == 0 and np.all(D2[empty] == 0)
+    assert np.all(D3[empty] == 0)
 
 
 def test_rows_that_leave_from_registers():
