@@ -347,7 +347,8 @@ def measure(cfg, args, steps, warmup, headline):
                 passes += 1
             sample, sample_flops = f"whole workload, {passes} passes", flops * passes
         else:
-            rows = np.arange(0, n, max(1, n // 20000))
+            # (about 60 000 rows: ten to fifteen seconds on the 16 host cores)
+            rows = np.arange(0, n, max(1, n // 60000))
             oracle.chain_rows(prob.A, prob.B, prob.C, rows)
             lens = np.diff(prob.A.rowptr.astype(np.int64))[rows]
             per_dep = 2 * (bcol if not sparse else 8) * ccol
