@@ -295,6 +295,13 @@ def measure(cfg, args, steps, warmup, headline):
     roofline["kernel"] = kernel
     roofline["kernel_ms"] = dom_ms
     roofline["alg_bytes_per_launch"] = int(dom_q)
+    # the whole fused step against its own floor: the algorithmic bytes at the HBM peak or the
+    # dense product at the matrix peak of its precision, whichever takes longer
+    step_t_mem = q_alg / (HBM_PEAK_GBS * 1e9)
+    step_t_mfma = gemm_flops / (MFMA_PEAK_TFLOPS[dname] * 1e12)
+    step_bound = dict(t_mem_ms=step_t_mem * 1e3, t_mfma_ms=step_t_mfma * 1e3,
+                      bound="mfma" if step_t_mfma > step_t_mem else "hbm",
+                      frac=max(step_t_mem, step_t_mfma) / (ms_fused * 1e-3))
 
     out = {
         "workload": workload,
@@ -307,6 +314,7 @@ def measure(cfg, args, steps, warmup, headline):
         "useful_flops": int(flops),
         "hbm_alg_gbs": q_alg / (ms_fused * 1e-3) / 1e9,
         "hbm_alg_frac": q_alg / (ms_fused * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "step_bound": step_bound,
         "alg_bytes": int(q_alg),
         "alg_bytes_unfused": int(q_unf),
         "unfused_ms_per_step": ms_unfused,
@@ -347,8 +355,8 @@ def measure(cfg, args, steps, warmup, headline):
                 passes += 1
             sample, sample_flops = f"whole workload, {passes} passes", flops * passes
         else:
-            # (about 60 000 rows: ten to fifteen seconds on the 16 host cores)
-            rows = np.arange(0, n, max(1, n // 60000))
+            # (about 150 000 rows: ten to fifteen seconds on the 16 host cores)
+            rows = np.arange(0, n, max(1, n // 140000))
             oracle.chain_rows(prob.A, prob.B, prob.C, rows)
             lens = np.diff(prob.A.rowptr.astype(np.int64))[rows]
             per_dep = 2 * (bcol if not sparse else 8) * ccol
@@ -424,7 +432,8 @@ def main():
                 "fused_ms": r["ms_per_step"], "unfused_ms": r["unfused_ms_per_step"],
                 "speedup_vs_unfused": r["speedup_vs_unfused"],
                 "useful_gflops": r["value"], "hbm_alg_gbs": r["hbm_alg_gbs"],
-                "hbm_alg_frac": r["hbm_alg_frac"], "kernels_ms": r["kernels_ms"],
+                "hbm_alg_frac": r["hbm_alg_frac"], "step_bound": r["step_bound"],
+                "kernels_ms": r["kernels_ms"],
                 "dominant_kernel": r["roofline"]["kernel"],
                 "dominant_kernel_bound": r["roofline"]["bound"],
                 "dominant_kernel_frac": r["roofline"]["frac"],
@@ -450,7 +459,7 @@ def main():
         "config": {"workload": head["workload"], "tile_params": head["tile_params"],
                    "buffer_sets": head["buffer_sets"], "useful_flops": head["useful_flops"]},
     }
-    for k in ("hbm_alg_gbs", "hbm_alg_frac", "alg_bytes", "alg_bytes_unfused", "unfused_ms_per_step",
+    for k in ("hbm_alg_gbs", "hbm_alg_frac", "step_bound", "alg_bytes", "alg_bytes_unfused", "unfused_ms_per_step",
               "speedup_vs_unfused", "median7_ms", "warm_ms", "graph_ms", "kernels_ms", "fused_ratio",
               "spill_fraction", "first_rows_fraction", "schedule", "plan_ms", "schedule_ms",
               "amortisation_runs"):
