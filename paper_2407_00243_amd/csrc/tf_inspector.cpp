@@ -655,8 +655,16 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
     // A row belongs to one tile: there it is a candidate for fusion and there its D1 row is
     // produced.  With TF_FLAG_SKIP_UNREAD the D1 rows that no row of A reads are not produced at
     // all: they leave the tiles' first lists (a tile keeps at least one row) and get no place in LDS.
-    std::vector<int32_t> member_ptr = s.tile_first_ptr, member_rows = s.first_rows;
-    if (in.flags & TF_FLAG_SKIP_UNREAD) {
+    // (member_*: the tiles' rows before any are taken out; the lists themselves when none are)
+    const bool skip_rows = (in.flags & TF_FLAG_SKIP_UNREAD) != 0;
+    std::vector<int32_t> all_ptr, all_rows;
+    if (skip_rows) {
+        all_ptr = s.tile_first_ptr;
+        all_rows = s.first_rows;
+    }
+    const std::vector<int32_t> &member_ptr = skip_rows ? all_ptr : s.tile_first_ptr;
+    const std::vector<int32_t> &member_rows = skip_rows ? all_rows : s.first_rows;
+    if (skip_rows) {
         std::vector<uint8_t> read((size_t)n, 0);
         for (int64_t q = 0; q < in.nnz; ++q) read[in.colidx[q]] = 1;
         int64_t kept = 0;
@@ -677,14 +685,15 @@ tf_status build_schedule(const InspectorInput &in, Schedule &s, std::string &err
     // direct_kind[row]: 1 = the row of D is the D1 row times its only entry, the diagonal one;
     // 2 = the row of D is empty; both leave from the registers that hold the D1 row
     std::vector<uint8_t> kept((size_t)n, 0), direct_kind((size_t)n, 0);
-    for (int64_t vt = 0; vt < nt; ++vt) {
+    // (every row is in one tile: the threads write to places of their own tiles only)
+    for_each_item(nt, host_threads(in.nnz, nt, 16), [&](int64_t vt) {
         for (int64_t q = member_ptr[vt]; q < member_ptr[vt + 1]; ++q)
             tile_of[member_rows[q]] = (int32_t)vt;
         for (int64_t q = s.tile_first_ptr[vt]; q < s.tile_first_ptr[vt + 1]; ++q) {
             local_of[s.first_rows[q]] = (int32_t)(q - s.tile_first_ptr[vt]);
             kept[s.first_rows[q]] = 1;
         }
-    }
+    });
     std::vector<int32_t> seen((size_t)n, -1);      // Eq. 2: distinct columns per tile
     // Per tile: which of its rows are fused, and their packed block.  Tiles are independent (a fused
     // row only names columns of its own tile, so even `seen` is written at disjoint places), which
